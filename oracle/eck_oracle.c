@@ -1,0 +1,831 @@
+/*
+ * eck_oracle.c -- plain, slow, single-purpose CPU oracle for the batched
+ * energy-cost-model evaluation path of arXiv 2411.18873.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  Only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg may build, load or call it.  It shares no code,
+ * header, table or constant generator with the HIP library; both sides were
+ * written separately from the same written specification.
+ *
+ * What it computes, and the passage of the paper each part follows:
+ *   orc_enumerate  -- candidate generation: exhaustive index decode, random
+ *                     initial sampling (Sec. 6.4, first paragraph) and the
+ *                     GeneticReproduction step of Alg. 1 (mutation only).
+ *   orc_features   -- analytic high-level kernel features: float ops, integer
+ *                     ops, vectorisation-, loop- and cache-access features
+ *                     (Sec. 5.3 "Insight", Sec. 5.4 "Approach"); grid / block /
+ *                     global-load / shared-store / global-store counts follow
+ *                     the case study (Sec. 8, Table 5).
+ *   orc_score      -- the cost model's forward pass (Sec. 5.4); the model form
+ *                     is a 2-hidden-layer ReLU MLP (the workload configs fix
+ *                     that; the paper itself uses boosted trees).
+ *   orc_topk       -- "lowest latency first, then lowest energy" selection
+ *                     (Sec. 4.3 "Insight", Sec. 4.4; Alg. 1 LatencyEvaAndPick
+ *                     and EnergyModelEvaAndPick).
+ *   orc_update     -- ModelUpdate + SNR of Alg. 1 with the weighted squared
+ *                     error of Eq. (1), minimised by Adam.
+ *   orc_k_step     -- the k controller of Alg. 1 (the If/Else on mu).
+ *
+ * Pins (tests/test_oracle_*.py): Table 5 counters (grid, block, glb_ld,
+ * shared_st, glb_st of K2), closed-form FLOP/byte counts, table sizes by the
+ * stars-and-bars formula, brute-force top-k, Eq. (1) gradient by finite
+ * differences, hand-computed first Adam step, scripted k trajectories.
+ * parity unpinned: feature 20 (shared-load element count) -- Table 5's
+ * shared_ld column is not reproduced by any simple register-tile formula; and
+ * the 100-step bf16 update trajectory (checked statistically only).
+ *
+ * Floating point: scores and the update run in fp64 on the fp32/bf16 values
+ * handed in.  Integer parts are exact.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_OK 0
+#define ORC_EINVAL (-1)
+
+enum { ORC_OP_GEMM = 0, ORC_OP_BGEMM = 1, ORC_OP_CONV2D = 2 };
+enum { ORC_SPACE_KNOB = 0, ORC_SPACE_SPLIT = 1 };
+enum { ORC_MODE_EXHAUSTIVE = 0, ORC_MODE_SAMPLE = 1, ORC_MODE_MUTATE = 2 };
+enum { ORC_SEL_THRESHOLD = 0, ORC_SEL_RANK = 1 };
+
+/* problem fields, in the order the Python side packs them */
+typedef struct {
+    int32_t op;
+    int32_t dim[8]; /* GEMM/BGEMM: B,M,N,K.  CONV2D: N,C,K,H,W,R,S,stride | pad<<16 */
+    int32_t elem_bytes;
+    int32_t hw_num_cu, hw_wave, hw_lds_bytes, hw_max_threads_cu, hw_max_blocks_cu;
+} orc_problem;
+
+/* The five axis slots every operator is mapped to: four spatial, one reduction.
+ * GEMM/BGEMM: (B, M, N, -, K).  CONV2D: (N, K_out, H_out, W_out, C). */
+#define NAX 5
+#define RED_AXIS 4
+
+typedef struct {
+    orc_problem pb;
+    int kind;
+    int n_genes;
+    uint32_t radix[16];
+    /* SPLIT: which axis slot each leading gene splits, and that axis's table */
+    int n_split;
+    int split_axis[NAX];
+    uint32_t *table[NAX]; /* table[g][4*t + l] */
+    uint32_t table_n[NAX];
+    /* derived, true extents per axis slot */
+    uint64_t ext[NAX];
+    uint64_t R, S, stride, pad;
+    int vec_axis; /* last spatial axis present: its innermost level is contiguous */
+} orc_space;
+
+static const uint32_t KNOB_TILE_MN[5] = {16, 32, 64, 128, 256};
+static const uint32_t KNOB_TILE_K[4] = {8, 16, 32, 64};
+static const uint32_t KNOB_THREADS[4] = {64, 128, 256, 512};
+static const uint32_t POW2_VALUES[5] = {1, 2, 4, 8, 16};
+
+/* ---------------------------------------------------------------- tables */
+
+/* All ordered 4-tuples (f0,f1,f2,f3) of positive integers with product
+ * `extent`, in lexicographic order.  Returns how many there are; writes at
+ * most `cap` of them. */
+uint32_t orc_split_table(uint32_t extent, uint32_t *out, uint32_t cap)
+{
+    uint32_t count = 0;
+    if (extent == 0) return 0;
+    for (uint32_t f0 = 1; f0 <= extent; ++f0) {
+        if (extent % f0) continue;
+        uint32_t r0 = extent / f0;
+        for (uint32_t f1 = 1; f1 <= r0; ++f1) {
+            if (r0 % f1) continue;
+            uint32_t r1 = r0 / f1;
+            for (uint32_t f2 = 1; f2 <= r1; ++f2) {
+                if (r1 % f2) continue;
+                uint32_t f3 = r1 / f2;
+                if (out && count < cap) {
+                    out[4 * count + 0] = f0;
+                    out[4 * count + 1] = f1;
+                    out[4 * count + 2] = f2;
+                    out[4 * count + 3] = f3;
+                }
+                ++count;
+            }
+        }
+    }
+    return count;
+}
+
+void orc_space_destroy(void *h)
+{
+    orc_space *sp = (orc_space *)h;
+    if (!sp) return;
+    for (int g = 0; g < NAX; ++g) free(sp->table[g]);
+    free(sp);
+}
+
+void *orc_space_create(const int32_t *pb_fields, int32_t kind)
+{
+    orc_space *sp = (orc_space *)calloc(1, sizeof(orc_space));
+    if (!sp) return NULL;
+    memcpy(&sp->pb, pb_fields, sizeof(orc_problem));
+    const orc_problem *pb = &sp->pb;
+    sp->kind = kind;
+    sp->R = sp->S = sp->stride = 1;
+    sp->pad = 0;
+    int present[NAX] = {0, 0, 0, 0, 0};
+    if (pb->op == ORC_OP_GEMM || pb->op == ORC_OP_BGEMM) {
+        sp->ext[0] = (uint64_t)pb->dim[0];
+        sp->ext[1] = (uint64_t)pb->dim[1];
+        sp->ext[2] = (uint64_t)pb->dim[2];
+        sp->ext[3] = 1;
+        sp->ext[4] = (uint64_t)pb->dim[3];
+        present[0] = (pb->op == ORC_OP_BGEMM);
+        present[1] = present[2] = present[4] = 1;
+        sp->vec_axis = 2;
+        if (pb->op == ORC_OP_GEMM && pb->dim[0] != 1) goto bad;
+    } else if (pb->op == ORC_OP_CONV2D) {
+        uint64_t H = (uint64_t)pb->dim[3], W = (uint64_t)pb->dim[4];
+        sp->R = (uint64_t)pb->dim[5];
+        sp->S = (uint64_t)pb->dim[6];
+        sp->stride = (uint64_t)(pb->dim[7] & 0xFFFF);
+        sp->pad = (uint64_t)((pb->dim[7] >> 16) & 0xFFFF);
+        if (sp->stride == 0 || sp->R == 0 || sp->S == 0) goto bad;
+        if (H + 2 * sp->pad < sp->R || W + 2 * sp->pad < sp->S) goto bad;
+        sp->ext[0] = (uint64_t)pb->dim[0];
+        sp->ext[1] = (uint64_t)pb->dim[2];                       /* output channels */
+        sp->ext[2] = (H + 2 * sp->pad - sp->R) / sp->stride + 1; /* H_out */
+        sp->ext[3] = (W + 2 * sp->pad - sp->S) / sp->stride + 1; /* W_out */
+        sp->ext[4] = (uint64_t)pb->dim[1];                       /* input channels */
+        for (int a = 0; a < NAX; ++a) present[a] = 1;
+        sp->vec_axis = 3;
+    } else {
+        goto bad;
+    }
+    for (int a = 0; a < NAX; ++a)
+        if (sp->ext[a] == 0 || sp->ext[a] > 65535) goto bad;
+    if (pb->elem_bytes != 2 && pb->elem_bytes != 4) goto bad;
+
+    if (kind == ORC_SPACE_KNOB) {
+        if (pb->op == ORC_OP_CONV2D) goto bad;
+        sp->n_genes = 6;
+        sp->radix[0] = 5; sp->radix[1] = 5; sp->radix[2] = 4;
+        sp->radix[3] = 4; sp->radix[4] = 4; sp->radix[5] = 4;
+    } else if (kind == ORC_SPACE_SPLIT) {
+        int g = 0;
+        for (int a = 0; a < NAX; ++a) {
+            if (!present[a]) continue;
+            uint32_t cnt = orc_split_table((uint32_t)sp->ext[a], NULL, 0);
+            if (cnt == 0 || cnt > 65535) goto bad;
+            sp->table[g] = (uint32_t *)malloc((size_t)cnt * 4 * sizeof(uint32_t));
+            orc_split_table((uint32_t)sp->ext[a], sp->table[g], cnt);
+            sp->table_n[g] = cnt;
+            sp->split_axis[g] = a;
+            sp->radix[g] = cnt;
+            ++g;
+        }
+        sp->n_split = g;
+        sp->radix[g] = 5;     /* unroll in {1,2,4,8,16} */
+        sp->radix[g + 1] = 4; /* vec in {1,2,4,8} */
+        sp->n_genes = g + 2;
+    } else {
+        goto bad;
+    }
+    return sp;
+bad:
+    orc_space_destroy(sp);
+    return NULL;
+}
+
+/* size = product of radices, or 0 when it does not fit 64 bits */
+int32_t orc_space_info(const void *h, int32_t *n_genes, uint32_t *radix, uint64_t *size)
+{
+    const orc_space *sp = (const orc_space *)h;
+    if (!sp) return ORC_EINVAL;
+    *n_genes = sp->n_genes;
+    uint64_t prod = 1;
+    int overflow = 0;
+    for (int g = 0; g < 16; ++g) radix[g] = g < sp->n_genes ? sp->radix[g] : 0;
+    for (int g = 0; g < sp->n_genes; ++g) {
+        if (prod > UINT64_MAX / sp->radix[g]) overflow = 1;
+        prod *= sp->radix[g];
+    }
+    *size = overflow ? 0 : prod;
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------- random */
+
+/* SplitMix64 (Steele, Lea, Flood 2014): state advances by the golden-ratio
+ * constant, the output is this finaliser of the state. */
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+#define GOLDEN 0x9E3779B97F4A7C15ULL
+
+/* The random word for gene `gene` of candidate `idx` in stream (seed, round):
+ * output number (16*idx + gene + 1) of a SplitMix64 generator whose initial
+ * state is mix64(seed + GOLDEN*(round+1)). */
+uint64_t orc_hash(uint64_t seed, uint32_t round, uint64_t idx, uint32_t gene)
+{
+    uint64_t key = mix64(seed + GOLDEN * ((uint64_t)round + 1));
+    uint64_t counter = idx * 16 + gene + 1;
+    return mix64(key + GOLDEN * counter);
+}
+
+/* uniform integer in [0, radix) from the low 32 bits: multiply-high, no modulo */
+static uint32_t draw_value(uint64_t u, uint32_t radix)
+{
+    return (uint32_t)(((uint64_t)(uint32_t)u * (uint64_t)radix) >> 32);
+}
+
+int32_t orc_enumerate(const void *h, int32_t mode, uint64_t seed, uint32_t round,
+                      uint64_t first_index, uint64_t n, const uint16_t *parents,
+                      uint32_t n_parents, uint32_t p_mut_q32, uint16_t *genes, uint64_t ld)
+{
+    const orc_space *sp = (const orc_space *)h;
+    if (!sp || !genes || ld < n) return ORC_EINVAL;
+    const int G = sp->n_genes;
+    if (mode == ORC_MODE_EXHAUSTIVE) {
+        /* mixed radix, first-listed gene most significant */
+        for (uint64_t i = 0; i < n; ++i) {
+            uint64_t rest = first_index + i;
+            for (int g = G - 1; g >= 0; --g) {
+                genes[(uint64_t)g * ld + i] = (uint16_t)(rest % sp->radix[g]);
+                rest /= sp->radix[g];
+            }
+            if (rest != 0) return ORC_EINVAL; /* index beyond the space */
+        }
+    } else if (mode == ORC_MODE_SAMPLE) {
+        for (uint64_t i = 0; i < n; ++i)
+            for (int g = 0; g < G; ++g) {
+                uint64_t u = orc_hash(seed, round, first_index + i, (uint32_t)g);
+                genes[(uint64_t)g * ld + i] = (uint16_t)draw_value(u, sp->radix[g]);
+            }
+    } else if (mode == ORC_MODE_MUTATE) {
+        if (!parents || n_parents == 0) return ORC_EINVAL;
+        for (uint64_t i = 0; i < n; ++i) {
+            uint64_t child = first_index + i;
+            uint64_t parent = child % n_parents;
+            for (int g = 0; g < G; ++g) {
+                uint64_t u = orc_hash(seed, round, child, (uint32_t)g);
+                uint32_t coin = (uint32_t)(u >> 32);
+                uint16_t value = parents[(uint64_t)g * n_parents + parent];
+                if (coin < p_mut_q32) value = (uint16_t)draw_value(u, sp->radix[g]);
+                genes[(uint64_t)g * ld + i] = value;
+            }
+        }
+    } else {
+        return ORC_EINVAL;
+    }
+    return ORC_OK;
+}
+
+/* -------------------------------------------------------------- features */
+
+typedef struct {
+    uint64_t f[NAX][4]; /* loop-nest levels per axis slot */
+    uint64_t U, V;
+    int knob_ok; /* KNOB only: thread rows fit the tile */
+} orc_record;
+
+static uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+static uint64_t min_u64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+static uint64_t gcd_u64(uint64_t a, uint64_t b)
+{
+    while (b) { uint64_t t = a % b; a = b; b = t; }
+    return a;
+}
+
+/* genes -> loop-nest record.
+ * Spatial axis levels: f0 -> grid, f1 -> threads, f2*f3 -> per thread (f3 innermost).
+ * Reduction axis levels: f0 -> outer stage loop, f1*f2*f3 -> staged per stage. */
+static void build_record(const orc_space *sp, const uint16_t *g, orc_record *rec)
+{
+    for (int a = 0; a < NAX; ++a)
+        for (int l = 0; l < 4; ++l) rec->f[a][l] = 1;
+    rec->knob_ok = 1;
+    if (sp->kind == ORC_SPACE_KNOB) {
+        uint64_t tm = KNOB_TILE_MN[g[0]], tn = KNOB_TILE_MN[g[1]], tk = KNOB_TILE_K[g[2]];
+        uint64_t T = KNOB_THREADS[g[3]];
+        rec->U = POW2_VALUES[g[4]];
+        rec->V = POW2_VALUES[g[5]];
+        uint64_t tpn = min_u64(T, tn); /* threads along N */
+        uint64_t tpm = T / tpn;        /* threads along M */
+        uint64_t rn = tn / tpn;        /* outputs per thread along N */
+        uint64_t rm = ceil_div(tm, tpm);
+        rec->knob_ok = (tpm <= tm);
+        rec->f[0][0] = sp->ext[0]; /* batch goes to the grid */
+        rec->f[1][0] = ceil_div(sp->ext[1], tm);
+        rec->f[1][1] = tpm;
+        rec->f[1][2] = rm;
+        rec->f[2][0] = ceil_div(sp->ext[2], tn);
+        rec->f[2][1] = tpn;
+        rec->f[2][3] = rn;
+        rec->f[4][0] = ceil_div(sp->ext[4], tk);
+        rec->f[4][3] = tk;
+    } else {
+        for (int s = 0; s < sp->n_split; ++s) {
+            const uint32_t *t = sp->table[s] + 4 * (uint64_t)g[s];
+            for (int l = 0; l < 4; ++l) rec->f[sp->split_axis[s]][l] = t[l];
+        }
+        rec->U = POW2_VALUES[g[sp->n_split]];
+        rec->V = POW2_VALUES[g[sp->n_split + 1]];
+    }
+}
+
+#define ORC_NFEAT_MAX 64
+
+/* The 64 raw integer features of one candidate, and whether it is legal. */
+static void raw_features(const orc_space *sp, const orc_record *rec, uint64_t *x, int *legal)
+{
+    const orc_problem *pb = &sp->pb;
+    const int conv = (pb->op == ORC_OP_CONV2D);
+    const uint64_t b = (uint64_t)pb->elem_bytes;
+    const uint64_t R = sp->R, S = sp->S, st = sp->stride;
+
+    uint64_t G = 1, T = 1, Pt = 1, tile[NAX], per_thread[NAX];
+    for (int a = 0; a < NAX; ++a) {
+        tile[a] = rec->f[a][1] * rec->f[a][2] * rec->f[a][3];
+        per_thread[a] = rec->f[a][2] * rec->f[a][3];
+    }
+    for (int a = 0; a < RED_AXIS; ++a) {
+        G *= rec->f[a][0];
+        T *= rec->f[a][1];
+        Pt *= per_thread[a];
+    }
+    const uint64_t stages = rec->f[RED_AXIS][0];
+    const uint64_t stage_red = tile[RED_AXIS] * R * S; /* reduction elements per stage */
+    const uint64_t Red = stages * stage_red;           /* padded reduction length */
+    const uint64_t inner_trip = rec->f[RED_AXIS][3];
+    const uint64_t U = rec->U, V = rec->V;
+
+    uint64_t true_out = 1;
+    for (int a = 0; a < RED_AXIS; ++a) true_out *= sp->ext[a];
+    const uint64_t true_red = sp->ext[RED_AXIS] * R * S;
+
+    /* operand footprints (elements) staged per block per stage, and operand
+     * elements one thread touches per reduction step */
+    uint64_t fpA, fpB, pa, pb_, nohalo;
+    if (conv) {
+        uint64_t in_h = (tile[2] - 1) * st + R, in_w = (tile[3] - 1) * st + S;
+        fpA = tile[0] * tile[4] * in_h * in_w; /* input patch with halo */
+        fpB = tile[1] * tile[4] * R * S;       /* filter slice */
+        nohalo = tile[0] * tile[4] * tile[2] * tile[3];
+        pa = per_thread[0] * per_thread[2] * per_thread[3];
+        pb_ = per_thread[1];
+    } else {
+        fpA = tile[0] * tile[1] * tile[4];
+        fpB = tile[0] * tile[2] * tile[4];
+        nohalo = fpA;
+        pa = per_thread[0] * per_thread[1];
+        pb_ = per_thread[0] * per_thread[2];
+    }
+    const uint64_t fp = fpA + fpB;
+    const uint64_t smem_bytes = fp * b;
+    const uint64_t ld_per_thread_stage = ceil_div(fp, T * V); /* cooperative vector loads */
+    const uint64_t glb_ld_elems = G * stages * fp;
+    const uint64_t glb_ld_bytes = glb_ld_elems * b;
+    const uint64_t glb_ld_sectors = ceil_div(glb_ld_bytes, 32);
+    const uint64_t glb_st_sectors = ceil_div(G * T * Pt * b, 32);
+
+    /* occupancy */
+    uint64_t bpc = (uint64_t)pb->hw_max_threads_cu / T;
+    if (smem_bytes > 0) bpc = min_u64(bpc, (uint64_t)pb->hw_lds_bytes / smem_bytes);
+    bpc = min_u64(bpc, (uint64_t)pb->hw_max_blocks_cu);
+    const uint64_t slots = (uint64_t)pb->hw_num_cu * (bpc > 0 ? bpc : 1);
+    const uint64_t active_cu = min_u64(G, (uint64_t)pb->hw_num_cu);
+
+    /* compulsory traffic of the operator itself */
+    uint64_t in_elems, w_elems, out_elems = true_out;
+    if (conv) {
+        in_elems = (uint64_t)pb->dim[0] * (uint64_t)pb->dim[1] * (uint64_t)pb->dim[3] * (uint64_t)pb->dim[4];
+        w_elems = sp->ext[1] * sp->ext[4] * R * S;
+    } else {
+        in_elems = sp->ext[0] * sp->ext[1] * sp->ext[4];
+        w_elems = sp->ext[0] * sp->ext[4] * sp->ext[2];
+    }
+
+    uint64_t depth = (R > 1) + (S > 1);
+    for (int a = 0; a < NAX; ++a)
+        for (int l = 0; l < 4; ++l) depth += (rec->f[a][l] > 1);
+
+    memset(x, 0, ORC_NFEAT_MAX * sizeof(uint64_t));
+    /* floating-point operations */
+    x[0] = 2 * true_out * true_red;
+    x[1] = 2 * G * T * Pt * Red;
+    x[2] = Pt * Red;
+    /* integer (address / loop) operations */
+    x[3] = G * T * (stages * (4 * ld_per_thread_stage + 2) + 2 * ceil_div(Red, U));
+    /* loop / parallelism */
+    x[4] = Pt;
+    x[5] = Pt + pa + pb_;
+    x[6] = G;
+    x[7] = T;
+    x[8] = ceil_div(T, (uint64_t)pb->hw_wave);
+    x[9] = bpc;
+    x[10] = active_cu;
+    x[11] = (uint64_t)pb->hw_num_cu - active_cu;
+    x[12] = ceil_div(G, slots);
+    x[13] = G % slots;
+    /* cache access / vectorisation */
+    x[14] = G * T * stages * ld_per_thread_stage;
+    x[15] = glb_ld_sectors;
+    x[16] = glb_st_sectors;
+    x[17] = G * T * ceil_div(Pt, V);
+    x[18] = smem_bytes;
+    x[19] = ceil_div(glb_ld_bytes, 128);
+    x[20] = G * T * Red * (pa + pb_);
+    x[21] = (x[1] << 3) / (glb_ld_sectors + glb_st_sectors); /* flop per byte, Q8 */
+    x[22] = (in_elems + w_elems + out_elems) * b;
+    x[23] = (glb_ld_bytes << 8) / ((in_elems + w_elems) * b);
+    /* loop structure */
+    x[24] = stages;
+    x[25] = stage_red;
+    x[26] = inner_trip;
+    x[27] = U;
+    x[28] = min_u64(U, inner_trip) * Pt;
+    x[29] = depth;
+    x[30] = V;
+    x[31] = gcd_u64(V, rec->f[sp->vec_axis][3]);
+    for (int a = 0; a < NAX; ++a)
+        for (int l = 0; l < 4; ++l) x[32 + 4 * a + l] = rec->f[a][l];
+    for (int a = 0; a < NAX; ++a) x[52 + a] = tile[a];
+    x[57] = fpA;
+    x[58] = fpB;
+    x[59] = (fpA << 8) / nohalo;
+    x[60] = b;
+    x[61] = (uint64_t)pb->op;
+    x[62] = true_out;
+    x[63] = true_red;
+
+    *legal = (T >= 32 && T <= 1024) && rec->knob_ok &&
+             (smem_bytes <= (uint64_t)pb->hw_lds_bytes) && (V * b <= 16) &&
+             (rec->f[sp->vec_axis][3] % V == 0);
+}
+
+/* Fixed-point log2 with a 10-bit linear mantissa: v = raw+1 (saturating),
+ * e = floor(log2 v), m = the 10 bits below v's leading one; result e + m/1024.
+ * At most 16 significant bits, so the float is exact. */
+float orc_transform(uint64_t raw)
+{
+    uint64_t v = (raw == UINT64_MAX) ? raw : raw + 1;
+    int e = 0;
+    while ((v >> e) > 1) ++e;
+    uint64_t below = v - ((uint64_t)1 << e); /* bits under the leading one */
+    uint64_t m = (e >= 10) ? (below >> (e - 10)) : (below << (10 - e));
+    return (float)(1024 * (uint64_t)e + m) / 1024.0f;
+}
+
+/* float -> bfloat16 bits, round to nearest, ties to even (finite inputs) */
+uint16_t orc_bf16_rne(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u) /* inf / nan: truncate, keep nan a nan */
+        return (uint16_t)((u >> 16) | ((u & 0xFFFFu) ? 0x40 : 0));
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7FFFu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+float orc_bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float x;
+    memcpy(&x, &u, 4);
+    return x;
+}
+
+int32_t orc_features(const void *h, const uint16_t *genes, uint64_t ld, uint64_t n, int32_t n_feat,
+                     uint64_t *raw_out, float *feat_f32, uint16_t *feat_bf16, uint8_t *legal_out)
+{
+    const orc_space *sp = (const orc_space *)h;
+    if (!sp || !genes || ld < n || (n_feat != 32 && n_feat != 64)) return ORC_EINVAL;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        uint16_t g[16];
+        for (int j = 0; j < sp->n_genes; ++j) {
+            g[j] = genes[(uint64_t)j * ld + (uint64_t)i];
+            if (g[j] >= sp->radix[j]) { bad = 1; g[j] = 0; }
+        }
+        orc_record rec;
+        uint64_t x[ORC_NFEAT_MAX];
+        int legal;
+        build_record(sp, g, &rec);
+        raw_features(sp, &rec, x, &legal);
+        for (int f = 0; f < n_feat; ++f) {
+            uint64_t at = (uint64_t)f * ld + (uint64_t)i;
+            float t = orc_transform(x[f]);
+            if (raw_out) raw_out[at] = x[f];
+            if (feat_f32) feat_f32[at] = t;
+            if (feat_bf16) feat_bf16[at] = orc_bf16_rne(t);
+        }
+        if (legal_out) legal_out[i] = (uint8_t)legal;
+    }
+    return bad ? ORC_EINVAL : ORC_OK;
+}
+
+/* ----------------------------------------------------------------- score */
+
+/* Parameter vector layout: for each layer l in order, W_l[fan_in][fan_out]
+ * row-major, then b_l[fan_out].  y_j = sum_i x_i W[i][j] + b_j; ReLU after
+ * every layer but the last. */
+static uint64_t param_count(int n_layers, const int32_t *w)
+{
+    uint64_t p = 0;
+    for (int l = 0; l < n_layers; ++l) p += (uint64_t)w[l] * (uint64_t)w[l + 1] + (uint64_t)w[l + 1];
+    return p;
+}
+
+uint64_t orc_param_count(int32_t n_layers, const int32_t *widths) { return param_count(n_layers, widths); }
+
+#define ORC_MAX_WIDTH 4096
+
+/* forward of one input; act[l] receives layer l's input (act[0] = x), the
+ * return value is the scalar output.  round_hidden: round hidden activations
+ * of every layer but the last hidden one to bf16 (what a bf16 matrix pipeline
+ * feeds its next contraction). */
+static double forward_one(int n_layers, const int32_t *w, const double *theta, double **act, int round_hidden)
+{
+    const double *p = theta;
+    for (int l = 0; l < n_layers; ++l) {
+        const int fi = w[l], fo = w[l + 1];
+        const double *W = p, *bias = p + (uint64_t)fi * fo;
+        double *out = act[l + 1];
+        for (int j = 0; j < fo; ++j) out[j] = bias[j];
+        for (int i = 0; i < fi; ++i) {
+            const double xi = act[l][i];
+            for (int j = 0; j < fo; ++j) out[j] += xi * W[(uint64_t)i * fo + j];
+        }
+        if (l + 1 < n_layers) {
+            for (int j = 0; j < fo; ++j) out[j] = out[j] > 0.0 ? out[j] : 0.0;
+            if (round_hidden && l + 2 < n_layers)
+                for (int j = 0; j < fo; ++j) out[j] = (double)orc_bf16_to_f32(orc_bf16_rne((float)out[j]));
+        }
+        p += (uint64_t)fi * fo + fo;
+    }
+    return act[n_layers][0];
+}
+
+int32_t orc_score(int32_t n_layers, const int32_t *widths, const float *theta32, const float *feat,
+                  uint64_t ld, uint64_t n, int32_t emulate_bf16, double *out)
+{
+    if (n_layers < 1 || n_layers > 8 || widths[n_layers] != 1 || ld < n) return ORC_EINVAL;
+    for (int l = 0; l <= n_layers; ++l)
+        if (widths[l] < 1 || widths[l] > ORC_MAX_WIDTH) return ORC_EINVAL;
+    const uint64_t P = param_count(n_layers, widths);
+    double *theta = (double *)malloc(P * sizeof(double));
+    for (uint64_t i = 0; i < P; ++i) theta[i] = (double)theta32[i];
+#pragma omp parallel
+    {
+        double *act[9];
+        for (int l = 0; l <= n_layers; ++l) act[l] = (double *)malloc((size_t)widths[l] * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t c = 0; c < (int64_t)n; ++c) {
+            for (int i = 0; i < widths[0]; ++i) act[0][i] = (double)feat[(uint64_t)i * ld + (uint64_t)c];
+            out[c] = forward_one(n_layers, widths, theta, act, emulate_bf16);
+        }
+        for (int l = 0; l <= n_layers; ++l) free(act[l]);
+    }
+    free(theta);
+    return ORC_OK;
+}
+
+/* ----------------------------------------------------------------- top-k */
+
+/* IEEE-754 totalOrder as an unsigned key: ascending key == ascending value,
+ * -0 before +0. */
+static uint32_t order_key(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+typedef struct { uint32_t key; uint32_t idx; } orc_pair;
+
+static int cmp_pair(const void *a, const void *b)
+{
+    const orc_pair *p = (const orc_pair *)a, *q = (const orc_pair *)b;
+    if (p->key != q->key) return p->key < q->key ? -1 : 1;
+    if (p->idx != q->idx) return p->idx < q->idx ? -1 : 1;
+    return 0;
+}
+
+/* Per segment (n / n_segments consecutive candidates):
+ *   THRESHOLD: L_min = least latency over legal, non-NaN candidates;
+ *              tau = L_min + (alpha-1)*|L_min| in fp32, product and sum rounded
+ *              separately (tau = +inf when alpha = +inf); feasible = legal and
+ *              latency <= tau.
+ *   RANK:      feasible = the m_latency legal candidates of least latency
+ *              (ties to the lower index).
+ *   latency == NULL: feasible = legal.
+ * A NaN energy or latency is never feasible.  Output: the k feasible candidates
+ * of least energy (ties to the lower index), ascending; count = how many exist
+ * (at most k); unused slots hold 0xFFFFFFFF / +inf. */
+int32_t orc_topk(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                 uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
+                 uint32_t *idx_out, float *energy_out, uint32_t *count_out)
+{
+    if (!energy || n == 0 || n_segments == 0 || n % n_segments || k == 0) return ORC_EINVAL;
+    const uint64_t seg_len = n / n_segments;
+    if (k > seg_len) return ORC_EINVAL;
+    orc_pair *pairs = (orc_pair *)malloc(seg_len * sizeof(orc_pair));
+    uint8_t *feasible = (uint8_t *)malloc(seg_len);
+    for (uint32_t s = 0; s < n_segments; ++s) {
+        const float *e = energy + (uint64_t)s * seg_len;
+        const float *lat = latency ? latency + (uint64_t)s * seg_len : NULL;
+        const uint8_t *lg = legal ? legal + (uint64_t)s * seg_len : NULL;
+        for (uint64_t i = 0; i < seg_len; ++i) feasible[i] = (!lg || lg[i]) && !(e[i] != e[i]);
+        if (lat && mode == ORC_SEL_THRESHOLD) {
+            int have = 0;
+            float lmin = 0.0f;
+            for (uint64_t i = 0; i < seg_len; ++i) {
+                if ((lg && !lg[i]) || lat[i] != lat[i]) continue;
+                if (!have || lat[i] < lmin) { lmin = lat[i]; have = 1; }
+            }
+            float tau = INFINITY;
+            if (have && !isinf(alpha)) {
+                volatile float slack = (alpha - 1.0f) * fabsf(lmin); /* rounded product */
+                tau = lmin + slack;                                  /* rounded sum */
+            }
+            for (uint64_t i = 0; i < seg_len; ++i)
+                if (!(lat[i] <= tau)) feasible[i] = 0;
+        } else if (lat && mode == ORC_SEL_RANK) {
+            uint64_t cnt = 0;
+            for (uint64_t i = 0; i < seg_len; ++i) {
+                if ((lg && !lg[i]) || lat[i] != lat[i]) continue;
+                pairs[cnt].key = order_key(lat[i]);
+                pairs[cnt].idx = (uint32_t)i;
+                ++cnt;
+            }
+            qsort(pairs, cnt, sizeof(orc_pair), cmp_pair);
+            uint8_t *fast = (uint8_t *)calloc(seg_len, 1);
+            for (uint64_t r = 0; r < cnt && r < m_latency; ++r) fast[pairs[r].idx] = 1;
+            for (uint64_t i = 0; i < seg_len; ++i) feasible[i] = feasible[i] && fast[i];
+            free(fast);
+        } else if (lat) {
+            free(pairs); free(feasible);
+            return ORC_EINVAL;
+        }
+        uint64_t cnt = 0;
+        for (uint64_t i = 0; i < seg_len; ++i) {
+            if (!feasible[i]) continue;
+            pairs[cnt].key = order_key(e[i]);
+            pairs[cnt].idx = (uint32_t)i;
+            ++cnt;
+        }
+        qsort(pairs, cnt, sizeof(orc_pair), cmp_pair);
+        uint32_t take = cnt < k ? (uint32_t)cnt : k;
+        for (uint32_t r = 0; r < k; ++r) {
+            idx_out[(uint64_t)s * k + r] = r < take ? pairs[r].idx : 0xFFFFFFFFu;
+            energy_out[(uint64_t)s * k + r] = r < take ? e[pairs[r].idx] : INFINITY;
+        }
+        count_out[s] = take;
+    }
+    free(pairs);
+    free(feasible);
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------- update */
+
+/* Eq. (1): per-sample loss (p - y)^2 / y and its derivative in p. */
+double orc_loss(double pred, double y) { return (pred - y) * (pred - y) / y; }
+double orc_loss_grad(double pred, double y) { return 2.0 * (pred - y) / y; }
+
+/* Gradient of the mean Eq.-(1) loss over rows [row0, row0+rows) with respect
+ * to theta (fp64), by back-propagation.  Returns the mean loss. */
+static double batch_gradient(int n_layers, const int32_t *w, const double *theta, const float *feat,
+                             uint64_t ld, const double *y, uint64_t row0, uint64_t rows, double *grad)
+{
+    const uint64_t P = param_count(n_layers, w);
+    memset(grad, 0, P * sizeof(double));
+    double *act[9], *delta[9];
+    for (int l = 0; l <= n_layers; ++l) {
+        act[l] = (double *)malloc((size_t)w[l] * sizeof(double));
+        delta[l] = (double *)malloc((size_t)w[l] * sizeof(double));
+    }
+    double loss = 0.0;
+    for (uint64_t r = 0; r < rows; ++r) {
+        const uint64_t c = row0 + r;
+        for (int i = 0; i < w[0]; ++i) act[0][i] = (double)feat[(uint64_t)i * ld + c];
+        const double pred = forward_one(n_layers, w, theta, act, 0);
+        loss += orc_loss(pred, y[c]);
+        delta[n_layers][0] = orc_loss_grad(pred, y[c]) / (double)rows;
+        /* walk the layers backwards; offsets of layer l's W in theta */
+        uint64_t off[9];
+        off[0] = 0;
+        for (int l = 0; l < n_layers; ++l) off[l + 1] = off[l] + (uint64_t)w[l] * w[l + 1] + w[l + 1];
+        for (int l = n_layers - 1; l >= 0; --l) {
+            const int fi = w[l], fo = w[l + 1];
+            const double *W = theta + off[l];
+            double *gW = grad + off[l], *gb = gW + (uint64_t)fi * fo;
+            for (int j = 0; j < fo; ++j) gb[j] += delta[l + 1][j];
+            for (int i = 0; i < fi; ++i) {
+                double back = 0.0;
+                for (int j = 0; j < fo; ++j) {
+                    gW[(uint64_t)i * fo + j] += act[l][i] * delta[l + 1][j];
+                    back += W[(uint64_t)i * fo + j] * delta[l + 1][j];
+                }
+                /* act[l] (l >= 1) is a ReLU output: derivative 1 where positive */
+                delta[l][i] = (l >= 1 && !(act[l][i] > 0.0)) ? 0.0 : back;
+            }
+        }
+    }
+    for (int l = 0; l <= n_layers; ++l) { free(act[l]); free(delta[l]); }
+    return loss / (double)rows;
+}
+
+/* exposed for the finite-difference pin */
+double orc_batch_gradient(int32_t n_layers, const int32_t *widths, const double *theta, const float *feat,
+                          uint64_t ld, const double *y, uint64_t row0, uint64_t rows, double *grad)
+{
+    return batch_gradient(n_layers, widths, theta, feat, ld, y, row0, rows, grad);
+}
+
+/* ModelUpdate + SNR of Alg. 1.
+ * state = [theta(P) | m(P) | v(P) | t] in fp64 (fp32 master values widened).
+ * Labels y = E_m / max(E_m).  SNR = sum y^2 / sum (pred - y)^2 with the
+ * predictions of the model as it is on entry.  Then n_steps of Adam on the
+ * mean Eq.-(1) loss of minibatch s = rows [(s mod nb)*mb, +mb), nb = n/mb.
+ * bf16_weights: forward/backward see the master weights rounded to bf16.
+ * loss_out = the last step's minibatch loss (before that step's update).
+ * Any E_m <= 0 (or NaN): snr = loss = NaN, model untouched. */
+int32_t orc_update(int32_t n_layers, const int32_t *widths, int32_t bf16_weights, double *state,
+                   const float *feat, uint64_t ld, const float *e_meas, uint64_t n_pairs,
+                   int32_t n_steps, int32_t minibatch, double lr, double beta1, double beta2,
+                   double eps, double *snr_out, double *loss_out)
+{
+    if (n_layers < 1 || n_layers > 8 || widths[n_layers] != 1 || minibatch <= 0 || n_pairs == 0 ||
+        n_pairs % (uint64_t)minibatch || ld < n_pairs || n_steps < 0)
+        return ORC_EINVAL;
+    const uint64_t P = param_count(n_layers, widths);
+    double *theta = state, *m = state + P, *v = state + 2 * P, *tcount = state + 3 * P;
+    double emax = 0.0;
+    int bad = 0;
+    for (uint64_t i = 0; i < n_pairs; ++i) {
+        if (!(e_meas[i] > 0.0f) || isinf(e_meas[i])) bad = 1;
+        if ((double)e_meas[i] > emax) emax = (double)e_meas[i];
+    }
+    if (bad) { *snr_out = NAN; *loss_out = NAN; return ORC_OK; }
+    double *y = (double *)malloc(n_pairs * sizeof(double));
+    for (uint64_t i = 0; i < n_pairs; ++i) y[i] = (double)e_meas[i] / emax;
+
+    double *eff = (double *)malloc(P * sizeof(double));
+    double *grad = (double *)malloc(P * sizeof(double));
+#define REFRESH_EFF()                                                                            \
+    for (uint64_t i = 0; i < P; ++i)                                                             \
+        eff[i] = bf16_weights ? (double)orc_bf16_to_f32(orc_bf16_rne((float)theta[i])) : theta[i];
+    REFRESH_EFF();
+
+    /* SNR of the predictions made before the update */
+    {
+        double *act[9];
+        for (int l = 0; l <= n_layers; ++l) act[l] = (double *)malloc((size_t)widths[l] * sizeof(double));
+        double sig = 0.0, noise = 0.0;
+        for (uint64_t c = 0; c < n_pairs; ++c) {
+            for (int i = 0; i < widths[0]; ++i) act[0][i] = (double)feat[(uint64_t)i * ld + c];
+            double pred = forward_one(n_layers, widths, eff, act, 0);
+            sig += y[c] * y[c];
+            noise += (pred - y[c]) * (pred - y[c]);
+        }
+        *snr_out = sig / noise;
+        for (int l = 0; l <= n_layers; ++l) free(act[l]);
+    }
+
+    const uint64_t nb = n_pairs / (uint64_t)minibatch;
+    double last_loss = NAN;
+    for (int s = 0; s < n_steps; ++s) {
+        const uint64_t row0 = ((uint64_t)s % nb) * (uint64_t)minibatch;
+        last_loss = batch_gradient(n_layers, widths, eff, feat, ld, y, row0, (uint64_t)minibatch, grad);
+        *tcount += 1.0;
+        const double c1 = 1.0 - pow(beta1, *tcount), c2 = 1.0 - pow(beta2, *tcount);
+        for (uint64_t i = 0; i < P; ++i) {
+            m[i] = beta1 * m[i] + (1.0 - beta1) * grad[i];
+            v[i] = beta2 * v[i] + (1.0 - beta2) * grad[i] * grad[i];
+            theta[i] -= lr * (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+        }
+        REFRESH_EFF();
+    }
+#undef REFRESH_EFF
+    *loss_out = last_loss;
+    free(y); free(eff); free(grad);
+    return ORC_OK;
+}
+
+/* k controller of Alg. 1.  `snr` is the PredictionError signal (a signal-to-
+ * noise ratio: higher = better model).  Returns the next k; k*M rounding to
+ * zero measurements leaves k unchanged (no update happened, no SNR exists). */
+double orc_k_step(double k, double snr, double mu, int64_t M)
+{
+    int64_t measured = (int64_t)floor(k * (double)M + 0.5);
+    if (measured == 0) return k;
+    if (snr < mu) return fmin(1.0, k + 0.2);
+    return fmax(0.0, k - 0.2);
+}

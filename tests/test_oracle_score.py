@@ -1,0 +1,86 @@
+"""Pins for the oracle's model forward pass.  CPU only."""
+import numpy as np
+
+import oracle
+from paper_2411_18873_amd import synth
+
+
+def test_single_layer_is_a_dot_product():
+    rng = np.random.default_rng(0)
+    F, n = 32, 50
+    theta = rng.standard_normal(F + 1).astype(np.float32)
+    feat = rng.standard_normal((F, n)).astype(np.float32)
+    got = oracle.score([F, 1], theta, feat)
+    want = feat.astype(np.float64).T @ theta[:F].astype(np.float64) + float(theta[F])
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
+
+
+def test_hand_worked_two_layer_network():
+    # x = (1, 2); W1 = [[1, -1], [0.5, 1]], b1 = (0, -2); W2 = (2, 3), b2 = 1
+    # pre1 = (1*1 + 2*0.5, 1*-1 + 2*1 - 2) = (2, -1) -> relu (2, 0) -> 2*2 + 0*3 + 1 = 5
+    theta = np.array([1, -1, 0.5, 1, 0, -2, 2, 3, 1], dtype=np.float32)
+    feat = np.array([[1.0, 0.0], [2.0, 0.0]], dtype=np.float32)  # second candidate: x = 0
+    got = oracle.score([2, 2, 1], theta, feat)
+    assert got[0] == 5.0
+    assert got[1] == 1.0  # relu(b1) = (0,0) -> b2
+
+
+def test_three_layers_against_matmul():
+    widths = [64, 256, 256, 1]
+    theta = synth.mlp_theta(widths, seed=3, bias_scale=0.5)
+    rng = np.random.default_rng(1)
+    feat = (rng.random((64, 300)) * 40).astype(np.float32)
+    got = oracle.score(widths, theta, feat)
+    t = theta.astype(np.float64)
+    o = 0
+    h = feat.astype(np.float64).T
+    for li, (fi, fo) in enumerate(zip(widths[:-1], widths[1:])):
+        W = t[o:o + fi * fo].reshape(fi, fo)
+        b = t[o + fi * fo:o + fi * fo + fo]
+        o += fi * fo + fo
+        h = h @ W + b
+        if li < 2:
+            h = np.maximum(h, 0)
+    assert np.allclose(got, h[:, 0], rtol=1e-12, atol=1e-12)
+    # leading dimension larger than n
+    got2 = oracle.score(widths, theta, feat, n=123)
+    assert np.array_equal(got2, got[:123])
+
+
+def test_transposed_weights_or_dropped_bias_would_show():
+    widths = [32, 64, 64, 1]
+    theta = synth.mlp_theta(widths, seed=1, bias_scale=0.5)
+    rng = np.random.default_rng(2)
+    feat = (rng.random((32, 64)) * 30).astype(np.float32)
+    base = oracle.score(widths, theta, feat)
+    # second layer is square: transposing it must change the answer
+    t2 = theta.copy()
+    o = 32 * 64 + 64
+    t2[o:o + 64 * 64] = theta[o:o + 64 * 64].reshape(64, 64).T.ravel()
+    assert not np.allclose(oracle.score(widths, t2, feat), base, rtol=1e-3)
+    t3 = theta.copy()
+    t3[o + 64 * 64:o + 64 * 64 + 64] = 0
+    assert not np.allclose(oracle.score(widths, t3, feat), base, rtol=1e-3)
+
+
+def test_bf16_emulation_rounds_only_the_first_hidden_layer():
+    widths = [64, 256, 256, 1]
+    theta = synth.mlp_theta(widths, seed=4, bf16=True)
+    rng = np.random.default_rng(5)
+    feat = synth.round_to_bf16((rng.random((64, 200)) * 40).astype(np.float32))
+    exact = oracle.score(widths, theta, feat)
+    emu = oracle.score(widths, theta, feat, emulate_bf16=True)
+    rms = np.sqrt((exact ** 2).mean())
+    err = np.abs(emu - exact).max() / rms
+    assert 0 < err < 1e-2
+    # independent emulation in numpy
+    t = theta.astype(np.float64)
+    W1, b1 = t[:64 * 256].reshape(64, 256), t[64 * 256:64 * 256 + 256]
+    o = 64 * 256 + 256
+    W2, b2 = t[o:o + 256 * 256].reshape(256, 256), t[o + 256 * 256:o + 256 * 256 + 256]
+    o += 256 * 256 + 256
+    w3, b3 = t[o:o + 256], t[o + 256]
+    h1 = np.maximum(feat.astype(np.float64).T @ W1 + b1, 0)
+    h1 = synth.round_to_bf16(h1.astype(np.float32)).astype(np.float64)
+    h2 = np.maximum(h1 @ W2 + b2, 0)
+    assert np.allclose(emu, h2 @ w3 + b3, rtol=1e-12, atol=1e-12)
