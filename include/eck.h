@@ -1,0 +1,243 @@
+/*
+ * eck.h -- C ABI of libeck: batched energy-cost-model evaluation for
+ * search-based kernel compilation (arXiv 2411.18873), native to MI355X (gfx950).
+ *
+ * The paper's search round (Alg. 1) is: reproduce a generation of candidate
+ * kernels, keep the low-latency ones, pick among them those of least predicted
+ * energy with a learned cost model, measure the picked ones, refit the model,
+ * and adapt how many to measure next.  This library runs the data-parallel
+ * part of that round on one GPU for millions of candidates at once:
+ *
+ *   candidate_enumerate -> features_compute -> costmodel_score (energy model,
+ *   latency model) -> topk_select            [+ costmodel_update when measured
+ *   energies arrive]
+ *
+ * Conventions
+ *   - Plain C, every function returns int32_t: ECK_OK or a negative ECK_E*.
+ *   - All arguments are validated on the host before anything is launched; an
+ *     error return means nothing was enqueued and no output was touched.
+ *   - "device" pointers are HIP device memory owned by the caller (the library
+ *     never frees or keeps them); "host" pointers are ordinary memory.
+ *   - Kernels are enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No call synchronises unless its comment says so.
+ *   - Results that depend on device data (count, snr, loss) are written to
+ *     device memory, never returned through the host.
+ *   - Matrices over candidates are structure-of-arrays: row r of a [R][ld]
+ *     array is at base + r*ld elements, candidate i at column i, ld >= n.
+ *   - There is no CPU fallback: without a usable GPU the compute calls return
+ *     ECK_EDEVICE.
+ */
+#ifndef ECK_H
+#define ECK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ECK_OK 0
+#define ECK_EINVAL (-1)       /* null pointer, zero size, value out of range */
+#define ECK_ESHAPE (-2)       /* sizes inconsistent with each other (ld < n, k > segment, widths) */
+#define ECK_EUNSUPPORTED (-3) /* valid request this build has no kernel for */
+#define ECK_EALIGN (-4)       /* pointer or leading dimension not aligned as required */
+#define ECK_EWORKSPACE (-5)   /* workspace missing or too small */
+#define ECK_EDEVICE (-6)      /* HIP runtime error (no device, allocation or launch failure) */
+
+/* operator kinds */
+#define ECK_OP_GEMM 0   /* dim = {1, M, N, K} */
+#define ECK_OP_BGEMM 1  /* dim = {B, M, N, K} */
+#define ECK_OP_CONV2D 2 /* dim = {N, C, K, H, W, R, S, stride | pad << 16} (NCHW, square stride/pad) */
+
+/* schedule-space kinds */
+#define ECK_SPACE_KNOB 0  /* genes: tile_M, tile_N in {16..256}, tile_K in {8..64}, threads in {64..512},
+                             unroll in {1,2,4,8}, vec in {1,2,4,8}; GEMM/BGEMM only */
+#define ECK_SPACE_SPLIT 1 /* one gene per split axis (index into the table of ordered 4-way factorisations of
+                             the axis extent, lexicographic), then unroll in {1,2,4,8,16}, vec in {1,2,4,8}.
+                             Axis order: GEMM (M,N,K); BGEMM (B,M,N,K); CONV2D (N,K,H_out,W_out,C) */
+
+/* enumeration modes */
+#define ECK_MODE_EXHAUSTIVE 0
+#define ECK_MODE_SAMPLE 1
+#define ECK_MODE_MUTATE 2
+
+/* element types of feature matrices and models */
+#define ECK_F32 0
+#define ECK_BF16 1
+
+/* selection modes */
+#define ECK_SELECT_THRESHOLD 0
+#define ECK_SELECT_RANK 1
+
+#define ECK_MAX_GENES 16
+#define ECK_MAX_K 4096 /* largest k topk_select accepts */
+
+/* The tensor operator being compiled plus the parameters of the GPU the
+ * candidate kernels are meant for (they enter the occupancy features; the
+ * paper's case study, Sec. 8, reasons with the number of multiprocessors). */
+typedef struct {
+    int32_t op;
+    int32_t dim[8];
+    int32_t elem_bytes; /* 2 or 4 */
+    int32_t hw_num_cu, hw_wave, hw_lds_bytes, hw_max_threads_cu, hw_max_blocks_cu;
+} eck_problem;
+
+typedef struct eck_space eck_space; /* schedule space of one problem (host tables + device copy) */
+typedef struct eck_model eck_model; /* cost model: fp32 master weights, Adam moments, packed bf16 weights */
+
+/* ------------------------------------------------------------------ spaces */
+
+/* Build the schedule space of `problem` (Sec. 2.2: the hierarchical search
+ * space of an auto-scheduler; Sec. 5.3: kernels represented through loops).
+ * Host-only work; the device copy of the tables is made lazily by the first
+ * call that launches a kernel.  Every axis extent must be in [1, 65535], every
+ * factorisation table at most 65535 entries, and 2*outputs*reduction < 2^48.
+ * Errors: ECK_EINVAL (null, bad op/kind/elem_bytes/hw fields, zero extents),
+ * ECK_EUNSUPPORTED (KNOB space on a convolution, limits above exceeded). */
+int32_t eck_space_create(const eck_problem *problem, int32_t kind, eck_space **out);
+
+/* Frees host tables and the device copy (synchronises the device first). NULL is ignored. */
+void eck_space_destroy(eck_space *space);
+
+/* n_genes, the radix of every gene (radix[ECK_MAX_GENES], unused entries 0)
+ * and the size of the space (0 when it does not fit 64 bits).  Host only. */
+int32_t eck_space_info(const eck_space *space, int32_t *n_genes, uint32_t *radix, uint64_t *size);
+
+/* Copies the factorisation table of split gene `gene` to `out` (host,
+ * [capacity][4] uint32); returns the number of entries, or a negative error.
+ * out == NULL just returns the count.  Host only. */
+int32_t eck_space_table(const eck_space *space, int32_t gene, uint32_t *out, uint32_t capacity);
+
+/* -------------------------------------------------------------- candidates */
+
+/* Generate the genes of candidates first_index .. first_index+n-1
+ * (Sec. 6.4: "randomly generate numerous kernels"; Alg. 1: GeneticReproduction).
+ *   EXHAUSTIVE: candidate index -> genes by mixed radix, first gene most
+ *               significant; first_index+n must not exceed the space size.
+ *   SAMPLE:     gene g of candidate c = (low32(u) * radix_g) >> 32 with
+ *               u = output number 16*c+g+1 of a SplitMix64 generator whose
+ *               state starts at mix(seed + gamma*(round+1)).
+ *   MUTATE:     child c copies parent (c mod n_parents); gene g is redrawn as
+ *               in SAMPLE when high32(u) < p_mut_q32 (probability p*2^32).
+ * genes_out: device, uint16 [n_genes][ld].  parents: device, uint16
+ * [n_genes][n_parents] (MUTATE only, else NULL).
+ * Errors: EINVAL (nulls, n == 0, bad mode, index range), ESHAPE (ld < n),
+ * EALIGN (genes_out not 4-byte aligned or ld odd). */
+int32_t candidate_enumerate(const eck_space *space, int32_t mode, uint64_t seed, uint32_t round,
+                            uint64_t first_index, uint64_t n, const uint16_t *parents, uint32_t n_parents,
+                            uint32_t p_mut_q32, uint16_t *genes_out, uint64_t ld, void *stream);
+
+/* ---------------------------------------------------------------- features */
+
+/* High-level kernel features of each candidate, computed analytically from
+ * its loop structure (Sec. 5.3; Sec. 5.4: numbers of floating-point and
+ * integer operations, vectorisation-, loop- and cache-access features; the
+ * grid / block / global-load / shared-store counts are those of Table 5).
+ * Feature f of candidate i is the 64-bit integer raw[f][i]; the model input is
+ * its fixed-point log2: with v = raw+1 (saturating), e = floor(log2 v) and m =
+ * the 10 bits below v's leading one, feat = e + m/1024 (exact in fp32; rounded
+ * to nearest-even for bf16).  n_feat = 32 gives features 0..31, 64 all.
+ *   genes:     device, uint16 [n_genes][ld] (values >= radix are clamped to radix-1)
+ *   feat_out:  device, [n_feat][ld] of out_dtype (ECK_F32 or ECK_BF16); may be NULL
+ *   raw_out:   device, uint64 [n_feat][ld] or NULL
+ *   legal_out: device, uint8 [n] or NULL; 1 when the schedule can be launched
+ *              (32 <= threads <= 1024, staged bytes fit the LDS, vector width
+ *              <= 16 bytes and divides the contiguous per-thread extent)
+ * Errors: EINVAL, ESHAPE (ld < n), EUNSUPPORTED (n_feat not 32/64), EALIGN
+ * (ld not a multiple of 2). */
+int32_t features_compute(const eck_space *space, const uint16_t *genes, uint64_t ld, uint64_t n,
+                         int32_t n_feat, int32_t out_dtype, void *feat_out, uint64_t *raw_out,
+                         uint8_t *legal_out, void *stream);
+
+/* ------------------------------------------------------------------ models */
+
+/* A multilayer perceptron widths[0] -> ... -> widths[n_layers] with ReLU
+ * between layers and a linear scalar output: the cost model of Sec. 5.4 in the
+ * form the workloads prescribe (the paper's own model is a tree ensemble).
+ * dtype ECK_F32: fp32 weights and arithmetic.  ECK_BF16: bf16 weights and
+ * bf16 first-hidden activations on the matrix cores, fp32 accumulation.
+ * Supported: n_layers == 3, widths[3] == 1, widths[0] in {32, 64}; BF16 needs
+ * hidden widths that are multiples of 32 and at most 512; F32 at most 1024.
+ * Allocates device memory (parameters, Adam moments, packed weights). */
+int32_t eck_model_create(int32_t n_layers, const int32_t *widths, int32_t dtype, eck_model **out);
+void eck_model_destroy(eck_model *model);
+
+/* Number of parameters P: sum over layers of fan_in*fan_out + fan_out. Host only. */
+int32_t eck_model_param_count(int32_t n_layers, const int32_t *widths, uint64_t *out);
+
+/* State blob (device, fp32): [theta(P) | m(P) | v(P) | t] with theta = per
+ * layer W[fan_in][fan_out] row-major then b[fan_out]; m, v Adam moments, t the
+ * step count.  set_state accepts n_floats == P (moments and t reset to zero)
+ * or 3P+1; get_state needs 3P+1.  The blob is the checkpoint format. */
+int32_t eck_model_set_state(eck_model *model, const float *blob, uint64_t n_floats, void *stream);
+int32_t eck_model_get_state(const eck_model *model, float *blob, uint64_t n_floats, void *stream);
+
+/* ------------------------------------------------------------------- score */
+
+/* Predicted score of every candidate (Alg. 1: LatencyEvaAndPick /
+ * EnergyModelEvaAndPick evaluate the generation with a model; Sec. 5.4: the
+ * model outputs a normalised energy score, lower is better).
+ *   feat: device [widths[0]][ld] of feat_dtype; score_out: device float [n].
+ * A BF16 model takes BF16 or F32 features (F32 is rounded to bf16 on load); an
+ * F32 model takes F32 features.  ws/ws_bytes are reserved (pass NULL, 0).
+ * Errors: EINVAL, ESHAPE (ld < n), EUNSUPPORTED (dtype combination), EALIGN
+ * (ld odd for BF16 features). */
+int32_t costmodel_score(const eck_model *model, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n,
+                        float *score_out, void *ws, uint64_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------ select */
+
+/* Bytes of workspace topk_select needs for these sizes (0 on invalid sizes). */
+uint64_t topk_select_workspace_bytes(uint64_t n, uint32_t n_segments, uint32_t k);
+
+/* Selection under the paper's objective -- low latency first, then least
+ * energy (Sec. 4.3, 4.4; Alg. 1).  The n candidates form n_segments equal
+ * consecutive segments (one per operator); each is handled independently.
+ *   THRESHOLD: L_min = least latency among legal candidates; tau = L_min +
+ *              (alpha-1)*|L_min| (fp32, product and sum rounded separately;
+ *              +inf when alpha is +inf); feasible = legal and latency <= tau.
+ *   RANK:      feasible = the m_latency legal candidates of least latency
+ *              (Alg. 1's "fastest M"), ties to the lower index.
+ *   latency == NULL: feasible = legal.  legal == NULL: all legal.
+ * Output per segment: the k feasible candidates of least energy in ascending
+ * order (IEEE total order, ties to the lower index): idx_out uint32 [S][k]
+ * (index within the segment, 0xFFFFFFFF padding), energy_out float [S][k]
+ * (+inf padding), count_out uint32 [S] = min(k, #feasible).  NaN energies or
+ * latencies are never feasible.  All pointers device; ws device, 16-byte aligned.
+ * Errors: EINVAL (nulls, n == 0, k == 0, bad mode, alpha < 1 or NaN), ESHAPE
+ * (n % n_segments, k > n/n_segments, segment longer than 2^32-2), EUNSUPPORTED
+ * (k > ECK_MAX_K), EWORKSPACE. */
+int32_t topk_select(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                    uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
+                    uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
+                    void *stream);
+
+/* ------------------------------------------------------------------ update */
+
+uint64_t costmodel_update_workspace_bytes(const eck_model *model, uint64_t n_pairs, int32_t minibatch);
+
+/* ModelUpdate and SNR of Alg. 1 on a buffer of measured kernels.
+ *   labels y = energy_measured / max(energy_measured)   ("normalised", Sec. 5.4)
+ *   snr  = sum y^2 / sum (pred - y)^2 with the model as it is on entry
+ *   then n_steps of Adam (bias-corrected, no weight decay) on the mean of
+ *   Eq. (1), (pred - y)^2 / y, over minibatch s = rows [(s mod nb)*minibatch,
+ *   +minibatch), nb = n_pairs / minibatch;  loss = the last step's value.
+ * BF16 models run forward/backward on bf16 copies of the fp32 master weights.
+ *   feat: device [widths[0]][ld]; energy_measured: device float [n_pairs];
+ *   snr_out, loss_out: device float (one each).
+ * A non-positive or non-finite measured energy is a data error found on the
+ * device: snr = loss = NaN and the model is left unchanged.
+ * Errors: EINVAL, ESHAPE (n_pairs % minibatch, ld < n_pairs), EUNSUPPORTED,
+ * EWORKSPACE. */
+int32_t costmodel_update(eck_model *model, const void *feat, int32_t feat_dtype, uint64_t ld,
+                         const float *energy_measured, uint64_t n_pairs, int32_t n_steps, int32_t minibatch,
+                         float lr, float beta1, float beta2, float eps, float *snr_out, float *loss_out,
+                         void *ws, uint64_t ws_bytes, void *stream);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int32_t eck_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECK_H */

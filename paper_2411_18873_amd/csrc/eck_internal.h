@@ -1,0 +1,67 @@
+// Internal declarations shared by the translation units of libeck (HIP, gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "eck.h"
+
+#define ECK_HIP_TRY(expr)                       \
+    do {                                        \
+        if ((expr) != hipSuccess) {             \
+            (void)hipGetLastError();            \
+            return ECK_EDEVICE;                 \
+        }                                       \
+    } while (0)
+
+namespace eck {
+
+constexpr int NAX = 5;      // axis slots: four spatial, one reduction
+constexpr int RED_AXIS = 4; // GEMM/BGEMM: (B, M, N, -, K); CONV2D: (N, K_out, H_out, W_out, C)
+
+// Everything the enumerate / feature kernels need about one space; passed by value.
+struct SpaceParams {
+    int32_t kind, op, n_genes, n_split;
+    uint32_t radix[8];
+    int32_t split_axis[NAX];   // axis slot of split gene s
+    uint32_t table_off[NAX];   // first entry of split gene s in the concatenated table
+    uint32_t table_total;      // entries in the concatenated table
+    uint32_t ext[NAX];         // true extents per axis slot
+    uint32_t R, S, stride;
+    uint32_t elem_bytes;
+    uint32_t hw_num_cu, hw_wave, hw_lds_bytes, hw_max_threads_cu, hw_max_blocks_cu;
+    int32_t vec_axis;          // spatial axis whose innermost level is contiguous in memory
+    uint64_t true_out, true_red, flop_useful, compulsory_bytes, compulsory_in_bytes;
+};
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+} // namespace eck
+
+struct eck_space {
+    eck_problem pb;
+    eck::SpaceParams prm;
+    std::vector<uint16_t> tables; // [table_total][4]
+    uint32_t table_n[eck::NAX];
+    uint64_t size;                // 0 when it overflows
+    uint16_t *d_tables = nullptr; // device copy, made on first use
+    int device = -1;
+};
+
+struct eck_model {
+    int32_t n_layers;
+    int32_t widths[4];
+    int32_t dtype;
+    uint64_t n_params;
+    uint64_t off_w[3], off_b[3]; // offsets of W_l and b_l in theta
+    float *d_state = nullptr;    // [theta | m | v | t]  (3P+1 floats)
+    void *d_packed = nullptr;    // BF16: weights in matrix-core fragment order + fp32 bias/output vectors
+    uint64_t packed_bytes = 0;
+    int device = -1;
+};
+
+namespace eck {
+// re-derive the packed weights from theta (BF16 models); enqueued on stream
+int32_t model_repack(eck_model *m, hipStream_t stream);
+} // namespace eck

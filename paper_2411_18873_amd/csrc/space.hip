@@ -1,0 +1,598 @@
+// Schedule spaces, candidate generation and analytic features (HIP, gfx950).
+//
+// candidate_enumerate: Sec. 6.4 (random initial population) and Alg. 1
+// GeneticReproduction (mutation).  features_compute: Sec. 5.3 / 5.4 feature
+// categories; Table 5 fixes grid, block, global-load, global-store and
+// shared-store counts.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "eck_internal.h"
+
+using namespace eck;
+
+// ------------------------------------------------------------------ host side
+
+namespace {
+
+// ordered factorisations n = f0*f1*f2*f3, lexicographic, appended as 4 x uint16
+uint32_t append_factorisations(uint32_t n, std::vector<uint16_t> *out)
+{
+    std::vector<uint32_t> divs;
+    for (uint32_t d = 1; d * d <= n; ++d)
+        if (n % d == 0) {
+            divs.push_back(d);
+            if (d != n / d) divs.push_back(n / d);
+        }
+    std::sort(divs.begin(), divs.end());
+    uint32_t count = 0;
+    for (uint32_t a : divs)
+        for (uint32_t b : divs) {
+            if ((n / a) % b) continue;
+            const uint32_t rest = n / a / b;
+            for (uint32_t c : divs) {
+                if (c > rest) break;
+                if (rest % c) continue;
+                if (out) {
+                    out->push_back((uint16_t)a);
+                    out->push_back((uint16_t)b);
+                    out->push_back((uint16_t)c);
+                    out->push_back((uint16_t)(rest / c));
+                }
+                ++count;
+            }
+        }
+    return count;
+}
+
+bool pow2_leq(uint64_t v, int bits) { return v < (1ull << bits); }
+
+int32_t ensure_device_tables(eck_space *sp)
+{
+    if (sp->prm.kind != ECK_SPACE_SPLIT || sp->d_tables) return ECK_OK;
+    int dev = 0;
+    ECK_HIP_TRY(hipGetDevice(&dev));
+    const size_t bytes = sp->tables.size() * sizeof(uint16_t);
+    ECK_HIP_TRY(hipMalloc((void **)&sp->d_tables, bytes));
+    if (hipMemcpy(sp->d_tables, sp->tables.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(sp->d_tables);
+        sp->d_tables = nullptr;
+        return ECK_EDEVICE;
+    }
+    sp->device = dev;
+    return ECK_OK;
+}
+
+} // namespace
+
+extern "C" int32_t eck_version(void) { return 100; }
+
+extern "C" int32_t eck_space_create(const eck_problem *pb, int32_t kind, eck_space **out)
+{
+    if (!pb || !out) return ECK_EINVAL;
+    *out = nullptr;
+    if (kind != ECK_SPACE_KNOB && kind != ECK_SPACE_SPLIT) return ECK_EINVAL;
+    if (pb->elem_bytes != 2 && pb->elem_bytes != 4) return ECK_EINVAL;
+    if (pb->hw_num_cu < 1 || pb->hw_wave < 1 || pb->hw_lds_bytes < 1 || pb->hw_max_threads_cu < 1 ||
+        pb->hw_max_blocks_cu < 1)
+        return ECK_EINVAL;
+
+    SpaceParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.kind = kind;
+    p.op = pb->op;
+    p.R = p.S = p.stride = 1;
+    p.elem_bytes = (uint32_t)pb->elem_bytes;
+    p.hw_num_cu = (uint32_t)pb->hw_num_cu;
+    p.hw_wave = (uint32_t)pb->hw_wave;
+    p.hw_lds_bytes = (uint32_t)pb->hw_lds_bytes;
+    p.hw_max_threads_cu = (uint32_t)pb->hw_max_threads_cu;
+    p.hw_max_blocks_cu = (uint32_t)pb->hw_max_blocks_cu;
+    bool present[NAX] = {false, false, false, false, false};
+    uint64_t in_elems = 0, w_elems = 0, opA_bound = 0, opB_bound = 0, halo_growth = 1;
+
+    for (int i = 0; i < 8; ++i)
+        if (pb->dim[i] < 0) return ECK_EINVAL;
+    if (pb->op == ECK_OP_GEMM || pb->op == ECK_OP_BGEMM) {
+        const uint64_t B = pb->dim[0], M = pb->dim[1], N = pb->dim[2], K = pb->dim[3];
+        if (pb->op == ECK_OP_GEMM && B != 1) return ECK_EINVAL;
+        p.ext[0] = (uint32_t)B; p.ext[1] = (uint32_t)M; p.ext[2] = (uint32_t)N; p.ext[3] = 1; p.ext[4] = (uint32_t)K;
+        present[0] = pb->op == ECK_OP_BGEMM;
+        present[1] = present[2] = present[4] = true;
+        p.vec_axis = 2;
+        in_elems = B * M * K;
+        w_elems = B * K * N;
+    } else if (pb->op == ECK_OP_CONV2D) {
+        if (kind == ECK_SPACE_KNOB) return ECK_EUNSUPPORTED;
+        const uint64_t N = pb->dim[0], C = pb->dim[1], K = pb->dim[2], H = pb->dim[3], W = pb->dim[4];
+        const uint64_t R = pb->dim[5], S = pb->dim[6];
+        const uint64_t stride = (uint32_t)pb->dim[7] & 0xFFFFu, pad = ((uint32_t)pb->dim[7] >> 16) & 0xFFFFu;
+        if (!R || !S || !stride || H + 2 * pad < R || W + 2 * pad < S) return ECK_EINVAL;
+        if (R > 255 || S > 255 || stride > 255) return ECK_EUNSUPPORTED;
+        p.R = (uint32_t)R; p.S = (uint32_t)S; p.stride = (uint32_t)stride;
+        p.ext[0] = (uint32_t)N; p.ext[1] = (uint32_t)K;
+        p.ext[2] = (uint32_t)((H + 2 * pad - R) / stride + 1);
+        p.ext[3] = (uint32_t)((W + 2 * pad - S) / stride + 1);
+        p.ext[4] = (uint32_t)C;
+        for (bool &b : present) b = true;
+        p.vec_axis = 3;
+        in_elems = N * C * H * W;
+        w_elems = K * C * R * S;
+        halo_growth = (stride + R) * (stride + S);
+    } else {
+        return ECK_EINVAL;
+    }
+    for (int a = 0; a < NAX; ++a)
+        if (p.ext[a] == 0) return ECK_EINVAL;
+    // original dims must fit 16 bits too (ext[] was narrowed from them)
+    for (int i = 0; i < (pb->op == ECK_OP_CONV2D ? 5 : 4); ++i)
+        if (pb->dim[i] < 1 || pb->dim[i] > 65535) return pb->dim[i] < 1 ? ECK_EINVAL : ECK_EUNSUPPORTED;
+
+    // range limits that keep the kernels' 32/64-bit arithmetic exact.  Knob tiles pad M and N to
+    // below ext + 256 (M twice that when the thread rows overhang the tile) and K to below ext + 64.
+    const uint64_t pad_sp = kind == ECK_SPACE_KNOB ? 255 : 0, pad_red = kind == ECK_SPACE_KNOB ? 63 : 0;
+    uint64_t out_pad = 1;
+    for (int a = 0; a < RED_AXIS; ++a) {
+        uint64_t e = p.ext[a] + ((a == 1 || a == 2) ? pad_sp : 0);
+        if (a == 1 && kind == ECK_SPACE_KNOB) e *= 2;
+        if (out_pad > (1ull << 40)) return ECK_EUNSUPPORTED;
+        out_pad *= e;
+    }
+    const uint64_t red_pad = (uint64_t)(p.ext[RED_AXIS] + pad_red) * p.R * p.S;
+    if (!pow2_leq(out_pad, 32) || !pow2_leq(red_pad, 24) || !pow2_leq(out_pad * red_pad, 47))
+        return ECK_EUNSUPPORTED;
+    if (pb->op == ECK_OP_CONV2D) {
+        opA_bound = (uint64_t)p.ext[0] * p.ext[4] * ((uint64_t)(p.ext[2] - 1) * p.stride + p.R) *
+                    ((uint64_t)(p.ext[3] - 1) * p.stride + p.S);
+        opB_bound = (uint64_t)p.ext[1] * p.ext[4] * p.R * p.S;
+        if (!pow2_leq(out_pad * p.ext[4] * halo_growth, 46)) return ECK_EUNSUPPORTED;
+    } else {
+        opA_bound = (uint64_t)p.ext[0] * 2 * (p.ext[1] + pad_sp) * (p.ext[4] + pad_red);
+        opB_bound = (uint64_t)p.ext[0] * (p.ext[2] + pad_sp) * (p.ext[4] + pad_red);
+    }
+    if (!pow2_leq(opA_bound, 31) || !pow2_leq(opB_bound, 31)) return ECK_EUNSUPPORTED;
+
+    p.true_out = (uint64_t)p.ext[0] * p.ext[1] * p.ext[2] * p.ext[3];
+    p.true_red = (uint64_t)p.ext[4] * p.R * p.S;
+    p.flop_useful = 2 * p.true_out * p.true_red;
+    p.compulsory_in_bytes = (in_elems + w_elems) * p.elem_bytes;
+    p.compulsory_bytes = (in_elems + w_elems + p.true_out) * p.elem_bytes;
+
+    eck_space *sp = new (std::nothrow) eck_space();
+    if (!sp) return ECK_EDEVICE;
+    sp->pb = *pb;
+    std::memset(sp->table_n, 0, sizeof(sp->table_n));
+    if (kind == ECK_SPACE_KNOB) {
+        static const uint32_t radices[6] = {5, 5, 4, 4, 4, 4};
+        p.n_genes = 6;
+        for (int g = 0; g < 6; ++g) p.radix[g] = radices[g];
+    } else {
+        int s = 0;
+        for (int a = 0; a < NAX; ++a) {
+            if (!present[a]) continue;
+            p.table_off[s] = (uint32_t)(sp->tables.size() / 4);
+            const uint32_t cnt = append_factorisations(p.ext[a], &sp->tables);
+            if (cnt > 65535) {
+                delete sp;
+                return ECK_EUNSUPPORTED;
+            }
+            sp->table_n[s] = cnt;
+            p.split_axis[s] = a;
+            p.radix[s] = cnt;
+            ++s;
+        }
+        p.n_split = s;
+        p.radix[s] = 5;
+        p.radix[s + 1] = 4;
+        p.n_genes = s + 2;
+        p.table_total = (uint32_t)(sp->tables.size() / 4);
+    }
+    uint64_t size = 1;
+    for (int g = 0; g < p.n_genes; ++g) {
+        if (size && size > UINT64_MAX / p.radix[g]) size = 0;
+        size *= p.radix[g];
+    }
+    sp->size = size;
+    sp->prm = p;
+    *out = sp;
+    return ECK_OK;
+}
+
+extern "C" void eck_space_destroy(eck_space *sp)
+{
+    if (!sp) return;
+    if (sp->d_tables) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(sp->d_tables);
+    }
+    delete sp;
+}
+
+extern "C" int32_t eck_space_info(const eck_space *sp, int32_t *n_genes, uint32_t *radix, uint64_t *size)
+{
+    if (!sp || !n_genes || !radix || !size) return ECK_EINVAL;
+    *n_genes = sp->prm.n_genes;
+    for (int g = 0; g < ECK_MAX_GENES; ++g) radix[g] = g < sp->prm.n_genes ? sp->prm.radix[g] : 0;
+    *size = sp->size;
+    return ECK_OK;
+}
+
+extern "C" int32_t eck_space_table(const eck_space *sp, int32_t gene, uint32_t *out, uint32_t capacity)
+{
+    if (!sp || sp->prm.kind != ECK_SPACE_SPLIT || gene < 0 || gene >= sp->prm.n_split) return ECK_EINVAL;
+    const uint32_t n = sp->table_n[gene];
+    if (out) {
+        const uint16_t *src = sp->tables.data() + 4ull * sp->prm.table_off[gene];
+        for (uint32_t i = 0; i < n && i < capacity; ++i)
+            for (int l = 0; l < 4; ++l) out[4 * i + l] = src[4 * i + l];
+    }
+    return (int32_t)n;
+}
+
+// --------------------------------------------------------------- enumeration
+
+namespace {
+
+__device__ __forceinline__ uint64_t splitmix_finalise(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+
+template <int MODE>
+__global__ __launch_bounds__(256) void enumerate_kernel(SpaceParams p, uint64_t stream_state, uint64_t first,
+                                                        uint64_t n, const uint16_t *__restrict__ parents,
+                                                        uint32_t n_parents, uint32_t p_mut,
+                                                        uint16_t *__restrict__ genes, uint64_t ld)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t c = first + i;
+    if (MODE == ECK_MODE_EXHAUSTIVE) {
+        uint64_t rest = c;
+        for (int g = p.n_genes - 1; g >= 0; --g) {
+            const uint64_t q = rest / p.radix[g];
+            genes[(uint64_t)g * ld + i] = (uint16_t)(rest - q * p.radix[g]);
+            rest = q;
+        }
+    } else {
+        // generator state before the first gene's word: stream_state + gamma * 16c
+        uint64_t state = stream_state + kGamma * (c << 4);
+        const uint32_t parent = MODE == ECK_MODE_MUTATE ? (uint32_t)(c % n_parents) : 0;
+        for (int g = 0; g < p.n_genes; ++g) {
+            state += kGamma;
+            const uint64_t u = splitmix_finalise(state);
+            uint32_t value = __umulhi((uint32_t)u, p.radix[g]);
+            if (MODE == ECK_MODE_MUTATE) {
+                const uint32_t inherited = parents[(uint64_t)g * n_parents + parent];
+                value = ((uint32_t)(u >> 32) < p_mut) ? value : inherited;
+            }
+            genes[(uint64_t)g * ld + i] = (uint16_t)value;
+        }
+    }
+}
+
+} // namespace
+
+extern "C" int32_t candidate_enumerate(const eck_space *space, int32_t mode, uint64_t seed, uint32_t round,
+                                       uint64_t first_index, uint64_t n, const uint16_t *parents,
+                                       uint32_t n_parents, uint32_t p_mut_q32, uint16_t *genes_out, uint64_t ld,
+                                       void *stream)
+{
+    if (!space || !genes_out || n == 0) return ECK_EINVAL;
+    if (mode != ECK_MODE_EXHAUSTIVE && mode != ECK_MODE_SAMPLE && mode != ECK_MODE_MUTATE) return ECK_EINVAL;
+    if (ld < n) return ECK_ESHAPE;
+    if ((ld & 1) || ((uintptr_t)genes_out & 3)) return ECK_EALIGN;
+    if (n > (1ull << 40) || first_index > UINT64_MAX - n) return ECK_EINVAL;
+    if (mode == ECK_MODE_EXHAUSTIVE) {
+        if (space->size == 0) return ECK_EUNSUPPORTED;
+        if (first_index + n > space->size) return ECK_EINVAL;
+    }
+    if (mode == ECK_MODE_MUTATE && (!parents || n_parents == 0)) return ECK_EINVAL;
+
+    // SplitMix64 state of stream (seed, round); done once on the host
+    uint64_t z = seed + kGamma * ((uint64_t)round + 1);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+
+    const dim3 block(256), grid((unsigned)((n + 255) / 256));
+    hipStream_t st = as_stream(stream);
+    const SpaceParams &p = space->prm;
+    if (mode == ECK_MODE_EXHAUSTIVE)
+        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_EXHAUSTIVE>, grid, block, 0, st, p, z, first_index, n, parents,
+                           n_parents, p_mut_q32, genes_out, ld);
+    else if (mode == ECK_MODE_SAMPLE)
+        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_SAMPLE>, grid, block, 0, st, p, z, first_index, n, parents,
+                           n_parents, p_mut_q32, genes_out, ld);
+    else
+        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_MUTATE>, grid, block, 0, st, p, z, first_index, n, parents,
+                           n_parents, p_mut_q32, genes_out, ld);
+    ECK_HIP_TRY(hipGetLastError());
+    return ECK_OK;
+}
+
+// ------------------------------------------------------------------ features
+
+namespace {
+
+// loop-nest levels of one candidate; every factor is below 2^16
+struct Levels {
+    uint32_t f[NAX][4];
+    uint32_t log2_unroll, log2_vec;
+    bool shape_ok;
+};
+
+__device__ __forceinline__ uint32_t ceil_div_u32(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
+
+// the knob tables are powers of two, so they are kept as exponents
+__device__ __forceinline__ void levels_from_knobs(const SpaceParams &p, const uint32_t *g, Levels *lv)
+{
+    const uint32_t tm = 16u << g[0], tn = 16u << g[1], tk = 8u << g[2], threads = 64u << g[3];
+    const uint32_t along_n = threads < tn ? threads : tn;
+    const uint32_t along_m = threads / along_n;
+    lv->shape_ok = along_m <= tm;
+    lv->f[0][0] = p.ext[0];
+    lv->f[1][0] = ceil_div_u32(p.ext[1], tm);
+    lv->f[1][1] = along_m;
+    lv->f[1][2] = along_m <= tm ? tm / along_m : 1;
+    lv->f[2][0] = ceil_div_u32(p.ext[2], tn);
+    lv->f[2][1] = along_n;
+    lv->f[2][3] = tn / along_n;
+    lv->f[4][0] = ceil_div_u32(p.ext[4], tk);
+    lv->f[4][3] = tk;
+    lv->log2_unroll = g[4];
+    lv->log2_vec = g[5];
+}
+
+// floor(log2) fixed point with 10 mantissa bits, as 1024*e + m  (v >= 1)
+__device__ __forceinline__ uint32_t log2_q10(uint64_t v)
+{
+    const int e = 63 - __clzll((long long)v);
+    const uint64_t frac = v ^ (1ull << e);
+    const uint32_t m = e >= 10 ? (uint32_t)(frac >> (e - 10)) : (uint32_t)(frac << (10 - e));
+    return ((uint32_t)e << 10) + m;
+}
+
+__device__ __forceinline__ uint16_t bf16_bits_rne(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <int OUT_DTYPE, bool TABLES_IN_LDS>
+__global__ __launch_bounds__(256) void features_kernel(SpaceParams p, const uint16_t *__restrict__ tables,
+                                                       const uint16_t *__restrict__ genes, uint64_t ld, uint64_t n,
+                                                       int n_feat, void *__restrict__ feat_out,
+                                                       uint64_t *__restrict__ raw_out, uint8_t *__restrict__ legal_out)
+{
+    extern __shared__ uint2 lds_tables[];
+    const uint2 *tab = reinterpret_cast<const uint2 *>(tables);
+    if (TABLES_IN_LDS) {
+        for (uint32_t t = threadIdx.x; t < p.table_total; t += blockDim.x) lds_tables[t] = tab[t];
+        __syncthreads();
+        tab = lds_tables;
+    }
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+
+    uint32_t g[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        g[j] = 0;
+        if (j < p.n_genes) {
+            const uint32_t v = genes[(uint64_t)j * ld + i];
+            g[j] = v < p.radix[j] ? v : p.radix[j] - 1;
+        }
+    }
+
+    Levels lv;
+#pragma unroll
+    for (int a = 0; a < NAX; ++a)
+#pragma unroll
+        for (int l = 0; l < 4; ++l) lv.f[a][l] = 1;
+    lv.shape_ok = true;
+    if (p.kind == ECK_SPACE_KNOB) {
+        levels_from_knobs(p, g, &lv);
+    } else {
+#pragma unroll
+        for (int s = 0; s < NAX; ++s) {
+            if (s < p.n_split) {
+                const uint2 e = tab[p.table_off[s] + g[s]];
+                const int a = p.split_axis[s];
+                // static indexing keeps lv in registers
+#pragma unroll
+                for (int aa = 0; aa < NAX; ++aa)
+                    if (aa == a) {
+                        lv.f[aa][0] = e.x & 0xFFFFu;
+                        lv.f[aa][1] = e.x >> 16;
+                        lv.f[aa][2] = e.y & 0xFFFFu;
+                        lv.f[aa][3] = e.y >> 16;
+                    }
+            }
+        }
+        uint32_t gu = 0, gv = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (j == p.n_split) gu = g[j];
+            if (j == p.n_split + 1) gv = g[j];
+        }
+        lv.log2_unroll = gu;
+        lv.log2_vec = gv;
+    }
+
+    // ---- derived quantities
+    uint32_t tile[NAX], per_thread[NAX];
+#pragma unroll
+    for (int a = 0; a < NAX; ++a) {
+        per_thread[a] = lv.f[a][2] * lv.f[a][3];
+        tile[a] = lv.f[a][1] * per_thread[a];
+    }
+    const uint32_t grid = lv.f[0][0] * lv.f[1][0] * lv.f[2][0] * lv.f[3][0];
+    const uint32_t threads = lv.f[0][1] * lv.f[1][1] * lv.f[2][1] * lv.f[3][1];
+    const uint32_t outs_thread = per_thread[0] * per_thread[1] * per_thread[2] * per_thread[3];
+    const uint32_t grid_threads = grid * threads; // <= padded outputs < 2^32
+    const uint32_t stages = lv.f[RED_AXIS][0];
+    const uint32_t rs = p.R * p.S;
+    const uint32_t stage_red = tile[RED_AXIS] * rs;
+    const uint32_t red = stages * stage_red;
+    const uint32_t inner_trip = lv.f[RED_AXIS][3];
+    const uint32_t lu = lv.log2_unroll, lvv = lv.log2_vec;
+    const uint32_t unroll = 1u << lu, vec = 1u << lvv;
+    const bool conv = p.op == ECK_OP_CONV2D;
+
+    uint32_t fp_a, fp_b, thr_a, thr_b;
+    uint64_t halo_q8;
+    if (conv) {
+        const uint32_t in_h = (tile[2] - 1) * p.stride + p.R, in_w = (tile[3] - 1) * p.stride + p.S;
+        const uint32_t patch = in_h * in_w;
+        fp_a = tile[0] * tile[4] * patch;
+        fp_b = tile[1] * tile[4] * rs;
+        thr_a = per_thread[0] * per_thread[2] * per_thread[3];
+        thr_b = per_thread[1];
+        halo_q8 = ((uint64_t)patch << 8) / (tile[2] * tile[3]);
+    } else {
+        fp_a = tile[0] * tile[1] * tile[4];
+        fp_b = tile[0] * tile[2] * tile[4];
+        thr_a = per_thread[0] * per_thread[1];
+        thr_b = per_thread[0] * per_thread[2];
+        halo_q8 = 256;
+    }
+    const uint32_t fp = fp_a + fp_b;
+    const uint64_t smem_bytes = (uint64_t)fp * p.elem_bytes;
+    // vector loads per thread per stage: ceil(fp / (threads * vec)) == ceil(ceil(fp / threads) / vec)
+    const uint32_t loads_thread_stage = (ceil_div_u32(fp, threads) + vec - 1) >> lvv;
+    const uint64_t gs = (uint64_t)grid * stages;
+    const uint64_t ld_bytes = gs * fp * p.elem_bytes;
+    const uint64_t ld_sectors = (ld_bytes + 31) >> 5;
+    const uint64_t padded_out = (uint64_t)grid_threads * outs_thread;
+    const uint64_t st_sectors = (padded_out * p.elem_bytes + 31) >> 5;
+    const uint64_t flop_exec = 2 * padded_out * red;
+
+    uint32_t blocks_cu = p.hw_max_threads_cu / threads;
+    if (smem_bytes > p.hw_lds_bytes) blocks_cu = 0;
+    else if (smem_bytes > 0) blocks_cu = min(blocks_cu, p.hw_lds_bytes / (uint32_t)smem_bytes);
+    blocks_cu = min(blocks_cu, p.hw_max_blocks_cu);
+    const uint32_t slots = p.hw_num_cu * (blocks_cu ? blocks_cu : 1);
+    const uint32_t waves = grid / slots;
+    const uint32_t tail = grid - waves * slots;
+    const uint32_t active = min(grid, p.hw_num_cu);
+
+    uint32_t depth = (p.R > 1) + (p.S > 1);
+#pragma unroll
+    for (int a = 0; a < NAX; ++a)
+#pragma unroll
+        for (int l = 0; l < 4; ++l) depth += lv.f[a][l] > 1;
+
+    const uint32_t contiguous = p.vec_axis == 3 ? lv.f[3][3] : lv.f[2][3];
+    // gcd with a power of two: the power of two dividing both
+    const uint32_t low_bit = contiguous & (0u - contiguous);
+    const uint32_t vec_contig = low_bit < vec ? low_bit : vec;
+
+    const bool legal = threads >= 32 && threads <= 1024 && lv.shape_ok && smem_bytes <= p.hw_lds_bytes &&
+                       vec * p.elem_bytes <= 16 && (contiguous & (vec - 1)) == 0;
+    if (legal_out) legal_out[i] = legal ? 1 : 0;
+
+    auto emit = [&](int f, uint64_t raw) {
+        if (f >= n_feat) return;
+        const uint64_t at = (uint64_t)f * ld + i;
+        if (raw_out) raw_out[at] = raw;
+        if (feat_out) {
+            const uint64_t v = raw == ~0ull ? raw : raw + 1;
+            const float x = (float)log2_q10(v) * (1.0f / 1024.0f);
+            if (OUT_DTYPE == ECK_F32) reinterpret_cast<float *>(feat_out)[at] = x;
+            else reinterpret_cast<uint16_t *>(feat_out)[at] = bf16_bits_rne(x);
+        }
+    };
+
+    emit(0, p.flop_useful);
+    emit(1, flop_exec);
+    emit(2, (uint64_t)outs_thread * red);
+    emit(3, (uint64_t)grid_threads *
+                ((uint64_t)stages * (4ull * loads_thread_stage + 2) + 2ull * ((red + unroll - 1) >> lu)));
+    emit(4, outs_thread);
+    emit(5, (uint64_t)outs_thread + thr_a + thr_b);
+    emit(6, grid);
+    emit(7, threads);
+    emit(8, ceil_div_u32(threads, p.hw_wave));
+    emit(9, blocks_cu);
+    emit(10, active);
+    emit(11, p.hw_num_cu - active);
+    emit(12, waves + (tail != 0));
+    emit(13, tail);
+    emit(14, (uint64_t)grid_threads * stages * loads_thread_stage);
+    emit(15, ld_sectors);
+    emit(16, st_sectors);
+    emit(17, (uint64_t)grid_threads * ((outs_thread + vec - 1) >> lvv));
+    emit(18, smem_bytes);
+    emit(19, (ld_bytes + 127) >> 7);
+    emit(20, (uint64_t)grid_threads * ((uint64_t)thr_a + thr_b) * red);
+    emit(21, (flop_exec << 3) / (ld_sectors + st_sectors));
+    emit(22, p.compulsory_bytes);
+    emit(23, (ld_bytes << 8) / p.compulsory_in_bytes);
+    emit(24, stages);
+    emit(25, stage_red);
+    emit(26, inner_trip);
+    emit(27, unroll);
+    emit(28, (uint64_t)(unroll < inner_trip ? unroll : inner_trip) * outs_thread);
+    emit(29, depth);
+    emit(30, vec);
+    emit(31, vec_contig);
+    if (n_feat > 32) {
+#pragma unroll
+        for (int a = 0; a < NAX; ++a)
+#pragma unroll
+            for (int l = 0; l < 4; ++l) emit(32 + 4 * a + l, lv.f[a][l]);
+#pragma unroll
+        for (int a = 0; a < NAX; ++a) emit(52 + a, tile[a]);
+        emit(57, fp_a);
+        emit(58, fp_b);
+        emit(59, halo_q8);
+        emit(60, p.elem_bytes);
+        emit(61, (uint64_t)p.op);
+        emit(62, p.true_out);
+        emit(63, p.true_red);
+    }
+}
+
+} // namespace
+
+extern "C" int32_t features_compute(const eck_space *space, const uint16_t *genes, uint64_t ld, uint64_t n,
+                                    int32_t n_feat, int32_t out_dtype, void *feat_out, uint64_t *raw_out,
+                                    uint8_t *legal_out, void *stream)
+{
+    if (!space || !genes || n == 0) return ECK_EINVAL;
+    if (!feat_out && !raw_out && !legal_out) return ECK_EINVAL;
+    if (out_dtype != ECK_F32 && out_dtype != ECK_BF16) return ECK_EINVAL;
+    if (n_feat != 32 && n_feat != 64) return ECK_EUNSUPPORTED;
+    if (ld < n) return ECK_ESHAPE;
+    if (ld & 1) return ECK_EALIGN;
+    if (n > (1ull << 40)) return ECK_EINVAL;
+    eck_space *sp = const_cast<eck_space *>(space);
+    const int32_t rc = ensure_device_tables(sp);
+    if (rc != ECK_OK) return rc;
+
+    const SpaceParams &p = sp->prm;
+    const dim3 block(256), grid((unsigned)((n + 255) / 256));
+    hipStream_t st = as_stream(stream);
+    const bool in_lds = p.kind == ECK_SPACE_SPLIT && p.table_total <= 6144;
+    const size_t lds = in_lds ? (size_t)p.table_total * 8 : 0;
+#define ECK_LAUNCH_FEATURES(DT, INLDS)                                                                       \
+    hipLaunchKernelGGL((features_kernel<DT, INLDS>), grid, block, lds, st, p, sp->d_tables, genes, ld, n,   \
+                       (int)n_feat, feat_out, raw_out, legal_out)
+    if (out_dtype == ECK_F32) {
+        if (in_lds) ECK_LAUNCH_FEATURES(ECK_F32, true);
+        else ECK_LAUNCH_FEATURES(ECK_F32, false);
+    } else {
+        if (in_lds) ECK_LAUNCH_FEATURES(ECK_BF16, true);
+        else ECK_LAUNCH_FEATURES(ECK_BF16, false);
+    }
+#undef ECK_LAUNCH_FEATURES
+    ECK_HIP_TRY(hipGetLastError());
+    return ECK_OK;
+}

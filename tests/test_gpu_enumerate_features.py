@@ -1,0 +1,150 @@
+"""GPU parity: candidate_enumerate and features_compute against the oracle, bit for bit."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2411_18873_amd import eck, synth
+
+pytestmark = pytest.mark.gpu
+
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _spaces(name_or_pb, kind):
+    pb = synth.CONFIGS[name_or_pb]["problem"] if isinstance(name_or_pb, str) else name_or_pb
+    return eck.Space(pb, kind), oracle.Space(pb, kind)
+
+
+def test_exhaustive_c1(G):
+    mine, ref = _spaces("c1", eck.SPACE_KNOB)
+    got = G.enumerate_gpu(mine, eck.MODE_EXHAUSTIVE, 6400)
+    want = oracle.enumerate_candidates(ref, oracle.MODE_EXHAUSTIVE, 6400)
+    assert np.array_equal(got[:, :6400], want)
+    got = G.enumerate_gpu(mine, eck.MODE_EXHAUSTIVE, 777, first_index=5000, ld=1000)
+    assert np.array_equal(got[:, :777], want[:, 5000:5777])
+    assert np.all(got[:, 777:] == 0xFFFF)  # nothing written past n
+
+
+@pytest.mark.parametrize("cfg,n,first", [("c2", (1 << 16) + 37, 0), ("c3", 5001, (1 << 40) + 3), ("c1", 3000, 10)])
+def test_sample(G, cfg, n, first):
+    kind = eck.SPACE_KNOB if cfg == "c1" else eck.SPACE_SPLIT
+    mine, ref = _spaces(cfg, kind)
+    got = G.enumerate_gpu(mine, eck.MODE_SAMPLE, n, seed=2024, rnd=3, first_index=first)
+    want = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, n, seed=2024, rnd=3, first_index=first)
+    assert np.array_equal(got[:, :n], want)
+
+
+def test_sample_sweep_shapes(G):
+    for i, (m, n_, k) in enumerate(synth.sweep_shapes()[::9]):
+        mine, ref = _spaces(synth.gemm(m, n_, k), eck.SPACE_SPLIT)
+        got = G.enumerate_gpu(mine, eck.MODE_SAMPLE, 4099, seed=100 + i)
+        want = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, 4099, seed=100 + i)
+        assert np.array_equal(got[:, :4099], want)
+
+
+@pytest.mark.parametrize("p_mut", [synth.P_MUT_Q32, 0, 0xFFFFFFFF])
+def test_mutate(G, p_mut):
+    mine, ref = _spaces("c3", eck.SPACE_SPLIT)
+    parents = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, 1024, seed=7)
+    n = (1 << 16) + 11
+    for rnd, first in [(1, 0), (5, 123457)]:
+        got = G.enumerate_gpu(mine, eck.MODE_MUTATE, n, seed=7, rnd=rnd, first_index=first, parents=parents,
+                              p_mut_q32=p_mut)
+        want = oracle.enumerate_candidates(ref, oracle.MODE_MUTATE, n, seed=7, rnd=rnd, first_index=first,
+                                           parents=parents, p_mut_q32=p_mut)
+        assert np.array_equal(got[:, :n], want)
+
+
+def _check_features(G, mine, ref, genes, n_feat):
+    n = genes.shape[1]
+    if n & 1:
+        genes = np.concatenate([genes, genes[:, :1]], axis=1)
+    raw_o, f32_o, b16_o, legal_o = oracle.features(ref, genes, n_feat, n=n)
+    raw_g, f32_g, legal_g = G.features_gpu(mine, genes, n, n_feat, eck.F32)
+    _, b16_g, legal_g2 = G.features_gpu(mine, genes, n, n_feat, eck.BF16, want_raw=False)
+    assert np.array_equal(raw_g[:, :n], raw_o[:, :n])
+    assert np.array_equal(f32_g[:, :n].view(np.uint32), f32_o[:, :n].view(np.uint32))
+    assert np.array_equal(b16_g[:, :n], b16_o[:, :n])
+    assert np.array_equal(legal_g, legal_o) and np.array_equal(legal_g2, legal_o)
+    return raw_o, legal_o
+
+
+def test_features_c1_all(G):
+    mine, ref = _spaces("c1", eck.SPACE_KNOB)
+    genes = oracle.enumerate_candidates(ref, oracle.MODE_EXHAUSTIVE, 6400)
+    _check_features(G, mine, ref, genes, 32)
+    _check_features(G, mine, ref, genes, 64)
+    # fp32 elements and the case-study machine (Table 5 configuration)
+    pb = synth.gemm(512, 512, 512, elem_bytes=4, hw=synth.HW_CASE_STUDY)
+    _check_features(G, *_spaces(pb, eck.SPACE_KNOB), genes, 64)
+    # a problem that is not a multiple of any tile
+    _check_features(G, *_spaces(synth.bgemm(3, 100, 77, 130), eck.SPACE_KNOB), genes, 64)
+
+
+@pytest.mark.parametrize("cfg,n", [("c2", (1 << 16) + 37), ("c3", (1 << 15) + 1)])
+def test_features_split_spaces(G, cfg, n):
+    mine, ref = _spaces(cfg, eck.SPACE_SPLIT)
+    genes = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, n, seed=11)
+    raw, legal = _check_features(G, mine, ref, genes, 64)
+    assert 0 < legal.mean() < 1
+
+
+def test_features_sweep_shapes_and_odd_problems(G):
+    for i, (m, n_, k) in enumerate(synth.sweep_shapes()[::7]):
+        mine, ref = _spaces(synth.gemm(m, n_, k), eck.SPACE_SPLIT)
+        genes = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, 2048, seed=i)
+        _check_features(G, mine, ref, genes, 64)
+    odd = [synth.conv2d(2, 4, 8, 6, 6, 3, 3, 1, 1, elem_bytes=4, hw=(8, 64, 65536, 1024, 16)),
+           synth.conv2d(4, 96, 60, 30, 27, 5, 3, 2, 2),
+           synth.conv2d(16, 64, 64, 56, 56, 1, 1, 1, 0, elem_bytes=4),
+           synth.bgemm(2, 8, 12, 6, elem_bytes=2, hw=(4, 64, 1024, 256, 8)),
+           synth.gemm(1, 4096, 1024, elem_bytes=4),
+           synth.gemm(60060, 2, 2)]  # 10240 factorisations: the table stays in global memory
+    for pb in odd:
+        mine, ref = _spaces(pb, eck.SPACE_SPLIT)
+        n = min(ref.size, 3001)
+        mode = oracle.MODE_EXHAUSTIVE if ref.size <= 3001 else oracle.MODE_SAMPLE
+        genes = oracle.enumerate_candidates(ref, mode, n, seed=5)
+        _check_features(G, mine, ref, genes, 64)
+
+
+def test_features_hand_worked_schedules(G, golden):
+    def gene_of(extent, tup):
+        divs = [d for d in range(1, extent + 1) if extent % d == 0]
+        return sorted(t for t in itertools.product(divs, repeat=4) if math.prod(t) == extent).index(tuple(tup))
+    rows = golden("hand_conv.txt")
+    pb = synth.conv2d(2, 4, 8, 6, 6, 3, 3, 1, 1, elem_bytes=4, hw=(8, 64, 65536, 1024, 16))
+    mine = eck.Space(pb, eck.SPACE_SPLIT)
+    g = [gene_of(2, (1, 2, 1, 1)), gene_of(8, (1, 4, 2, 1)), gene_of(6, (3, 2, 1, 1)), gene_of(6, (1, 3, 1, 2)),
+         gene_of(4, (2, 1, 1, 2)), 2, 1]
+    genes = np.array([g, g], dtype=np.uint16).T.copy()
+    raw, _, legal = G.features_gpu(mine, genes, 2, 64, eck.F32)
+    assert [int(v) for v in raw[:, 0]] == [int(t) for t in rows[0]] and legal[0] == int(rows[1][0])
+    rows = golden("hand_bgemm.txt")
+    pb = synth.bgemm(2, 8, 12, 6, elem_bytes=2, hw=(4, 64, 1024, 256, 8))
+    mine = eck.Space(pb, eck.SPACE_SPLIT)
+    g = [gene_of(2, (1, 1, 2, 1)), gene_of(8, (2, 2, 1, 2)), gene_of(12, (1, 3, 2, 2)), gene_of(6, (3, 1, 2, 1)), 1, 1]
+    genes = np.array([g, g], dtype=np.uint16).T.copy()
+    raw, _, legal = G.features_gpu(mine, genes, 2, 64, eck.F32)
+    assert [int(v) for v in raw[:, 1]] == [int(t) for t in rows[0]] and legal[1] == int(rows[1][0])
+
+
+def test_table5_counters_on_gpu(G, golden):
+    pb = synth.gemm(512, 512, 512, elem_bytes=4, hw=synth.HW_CASE_STUDY)
+    mine = eck.Space(pb, eck.SPACE_KNOB)
+    tiles, threads = [16, 32, 64, 128, 256], [64, 128, 256, 512]
+    for row in golden("table5_case_study.txt"):
+        tm, tn, thr, grid, block, glb_ld, glb_st, _, shared_st = (int(t) for t in row[1:])
+        g = [tiles.index(tm), tiles.index(tn), 1, threads.index(thr), 0, 0]
+        raw, _, _ = G.features_gpu(mine, np.array([g, g], dtype=np.uint16).T.copy(), 2, 32, eck.F32)
+        assert (raw[6, 0], raw[7, 0], raw[15, 0], raw[19, 0]) == (grid, block, glb_ld, shared_st)
+        if row[0] == "K2":
+            assert raw[16, 0] == glb_st

@@ -1,0 +1,149 @@
+"""GPU parity: costmodel_update (SNR, Eq.-(1) Adam refit) against the oracle."""
+import math
+
+import numpy as np
+import pytest
+from scipy.stats import spearmanr
+
+import oracle
+from paper_2411_18873_amd import eck, synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+def _pairs(n, seed=11):
+    cfg = synth.CONFIGS["c4"]
+    ref = oracle.Space(cfg["problem"], oracle.SPACE_SPLIT)
+    genes = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, n, seed=seed)
+    _, f32, b16, _ = oracle.features(ref, genes, 64)
+    e = synth.measured_energy(f32, cfg["label_seed"])
+    return f32, b16, e
+
+
+def _oracle_state(theta):
+    P = theta.size
+    return np.concatenate([theta.astype(np.float64), np.zeros(2 * P + 1)])
+
+
+def test_fp32_trajectory(G):
+    widths = [64, 256, 256, 1]
+    P = synth.param_count(widths)
+    f32, _, e = _pairs(2048)
+    theta = synth.mlp_theta(widths, 3, bias_scale=0.1)
+    model = G.make_model(widths, eck.F32, theta)
+    st = _oracle_state(theta)
+    feat = G.to_dev(f32)
+    # one step
+    snr_g, loss_g = G.update_gpu(model, feat, e, 1, 512)
+    snr_o, loss_o = oracle.update(widths, st, f32, e, 1, 512)
+    assert abs(snr_g - snr_o) <= 1e-4 * snr_o and abs(loss_g - loss_o) <= 1e-4 * loss_o
+    got = model.get_state().cpu().numpy().astype(np.float64)
+    # first Adam step is lr*sign(g): exact wherever the gradient is not vanishing
+    d = np.abs(got[:P] - st[:P])
+    assert np.mean(d > 1e-5) < 1e-3 and d.max() <= 2.001e-3
+    assert np.allclose(got[P:2 * P], st[P:2 * P], rtol=2e-3, atol=1e-7)      # first moment = 0.1 g
+    assert got[3 * P] == 1.0
+    # 19 more steps, minibatches wrap around the 4 blocks of the buffer
+    snr_g, loss_g = G.update_gpu(model, feat, e, 19, 512)
+    snr_o, loss_o = oracle.update(widths, st, f32, e, 19, 512)
+    assert abs(snr_g - snr_o) <= 2e-3 * snr_o and abs(loss_g - loss_o) <= 2e-3 * loss_o
+    got = model.get_state().cpu().numpy().astype(np.float64)
+    d = np.abs(got[:P] - st[:P])
+    assert np.quantile(d, 0.999) < 2e-4 and got[3 * P] == 20.0
+    pred_g = G.score_gpu(model, feat, 2048)
+    pred_o = oracle.score(widths, st[:P].astype(np.float32), f32)
+    assert G.close_enough(pred_g, pred_o, 2e-3) <= 1.0
+
+
+def test_bf16_refit_config4(G):
+    cfg = synth.CONFIGS["c4"]
+    widths = cfg["widths"]
+    P = synth.param_count(widths)
+    f32, b16, e = _pairs(cfg["n_pairs"], cfg["pair_seed"])
+    theta = synth.mlp_theta(widths, cfg["weight_seeds"][0], bf16=True)
+    model = G.make_model(widths, eck.BF16, theta)
+    st = _oracle_state(theta)
+    feat = G.bf16_dev(b16)
+    feat_o = oracle.bf16_bits_to_f32(b16)
+    # single step: forward scalars at the bf16 tolerance
+    snr_g, loss_g = G.update_gpu(model, feat, e, 1, cfg["minibatch"], lr=cfg["lr"])
+    snr_o, loss_o = oracle.update(widths, st, feat_o, e, 1, cfg["minibatch"], lr=cfg["lr"], bf16_weights=True)
+    assert abs(snr_g - snr_o) <= 2e-2 * snr_o and abs(loss_g - loss_o) <= 2e-2 * loss_o
+    got = model.get_state().cpu().numpy().astype(np.float64)
+    d = np.abs(got[:P] - st[:P])
+    assert d.max() <= 2.001 * cfg["lr"] and np.mean(d > 0.1 * cfg["lr"]) < 0.02
+    # the remaining 99 steps
+    snr_g, loss_g = G.update_gpu(model, feat, e, cfg["n_steps"] - 1, cfg["minibatch"], lr=cfg["lr"])
+    snr_o, loss_o = oracle.update(widths, st, feat_o, e, cfg["n_steps"] - 1, cfg["minibatch"], lr=cfg["lr"],
+                                  bf16_weights=True)
+    assert abs(loss_g - loss_o) <= 0.05 * loss_o
+    assert abs(snr_g - snr_o) <= 0.05 * snr_o
+    # rescoring with the refitted model ranks candidates like the oracle's refitted model
+    ref = oracle.Space(cfg["problem"], oracle.SPACE_SPLIT)
+    genes = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, 1 << 14, seed=2024)
+    _, _, b16r, _ = oracle.features(ref, genes, 64)
+    pred_g = G.score_gpu(model, G.bf16_dev(b16r), 1 << 14)
+    eff = synth.round_to_bf16(st[:P].astype(np.float32))
+    pred_o = oracle.score(widths, eff, oracle.bf16_bits_to_f32(b16r))
+    assert spearmanr(pred_g, pred_o)[0] >= 0.99
+    assert model.get_state().cpu().numpy()[3 * P] == 100.0
+
+
+def test_resume_from_checkpoint_is_bit_identical(G):
+    widths = [64, 256, 256, 1]
+    f32, b16, e = _pairs(1024)
+    theta = synth.mlp_theta(widths, 4, bf16=True)
+    feat = G.bf16_dev(b16)
+    a = G.make_model(widths, eck.BF16, theta)
+    G.update_gpu(a, feat, e, 10, 256)
+    once = a.get_state().cpu().numpy()
+    b = G.make_model(widths, eck.BF16, theta)
+    G.update_gpu(b, feat, e, 4, 256)
+    blob = b.get_state()
+    c = eck.Model(widths, eck.BF16)
+    c.set_state(blob)
+    G.update_gpu(c, feat, e, 0, 256)  # zero steps: state untouched
+    assert np.array_equal(c.get_state().cpu().numpy(), blob.cpu().numpy())
+    # minibatch order restarts with each call: 4 + 4 + 2 steps over whole passes of the 4-block buffer
+    # equal 10 steps in one call
+    d = G.make_model(widths, eck.BF16, theta)
+    G.update_gpu(d, feat, e, 4, 256)
+    G.update_gpu(d, feat, e, 4, 256)
+    G.update_gpu(d, feat, e, 2, 256)
+    assert np.array_equal(d.get_state().cpu().numpy(), once)
+
+
+def test_data_error_leaves_the_model_alone(G):
+    widths = [64, 256, 256, 1]
+    f32, b16, e = _pairs(512)
+    theta = synth.mlp_theta(widths, 4, bf16=True)
+    model = G.make_model(widths, eck.BF16, theta)
+    before = model.get_state().cpu().numpy()
+    bad = e.copy()
+    bad[17] = 0.0
+    snr, loss = G.update_gpu(model, G.bf16_dev(b16), bad, 3, 256)
+    assert math.isnan(snr) and math.isnan(loss)
+    assert np.array_equal(model.get_state().cpu().numpy(), before)
+    bad[17] = np.nan
+    snr, loss = G.update_gpu(model, G.bf16_dev(b16), bad, 3, 256)
+    assert math.isnan(snr) and np.array_equal(model.get_state().cpu().numpy(), before)
+
+
+def test_zero_steps_reports_snr_only(G):
+    widths = [32, 64, 64, 1]
+    ref = oracle.Space(synth.CONFIGS["c1"]["problem"], oracle.SPACE_KNOB)
+    genes = oracle.enumerate_candidates(ref, oracle.MODE_EXHAUSTIVE, 1024)
+    _, f32, _, _ = oracle.features(ref, genes, 32)
+    e = synth.measured_energy(f32, 5)
+    theta = synth.mlp_theta(widths, 1)
+    model = G.make_model(widths, eck.F32, theta)
+    snr_g, loss_g = G.update_gpu(model, G.to_dev(f32), e, 0, 256)
+    st = _oracle_state(theta)
+    snr_o, _ = oracle.update(widths, st, f32, e, 0, 256)
+    assert abs(snr_g - snr_o) <= 1e-4 * snr_o and math.isnan(loss_g)
