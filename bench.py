@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+Workload ("c5", the whole-network sweep): 64 GEMM shapes x 2^18 seeded schedule
+samples = 2^24 candidates, 64 bf16 features, energy and latency models
+64-512-512-1 (bf16 on the matrix cores), per-shape top-32 under the
+latency-then-energy objective.  One step =
+
+    candidate_enumerate (64 spaces) -> features_compute (64 spaces)
+    -> costmodel_score (energy) -> costmodel_score (latency)
+    -> topk_select (64 segments, k = 32, alpha = 1.1)
+    -> costmodel_update (energy model, 2048 measured pairs resident in HBM, one epoch = 4 Adam steps)
+
+Everything is resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_FLOPS = 2.5e15  # MI355X dense bf16 matrix peak
+
+
+def cpu_baseline(cfg, sample_log2=18):
+    """The oracle, as it stands, on a bounded sample of the same workload: one shape, 2^sample_log2
+    candidates through enumerate -> features -> two scores -> top-k, plus the same 4-step update."""
+    import numpy as np
+
+    import oracle
+    from paper_2411_18873_amd import synth
+
+    n = 1 << sample_log2
+    widths = cfg["widths"]
+    m, nn, k = cfg["shapes"][21]
+    sp = oracle.Space(synth.gemm(m, nn, k), oracle.SPACE_SPLIT)
+    th_e = synth.mlp_theta(widths, cfg["weight_seeds"][0], bf16=True)
+    th_l = synth.mlp_theta(widths, cfg["weight_seeds"][1], bf16=True)
+    P = synth.param_count(widths)
+    t0 = time.perf_counter()
+    genes = oracle.enumerate_candidates(sp, oracle.MODE_SAMPLE, n, seed=cfg["seed_base"] + 21)
+    _, _, b16, legal = oracle.features(sp, genes, cfg["n_feat"])
+    x = oracle.bf16_bits_to_f32(b16)
+    e = oracle.score(widths, th_e, x).astype(np.float32)
+    lat = oracle.score(widths, th_l, x).astype(np.float32)
+    oracle.topk(e, lat, legal, 1, cfg["k"], alpha=cfg["alpha"])
+    t1 = time.perf_counter()
+    # update share: the step refits on 2048 pairs per 2^24 candidates; charge the sample its proportional part
+    upd_rows = 2048
+    state = np.concatenate([th_e.astype(np.float64), np.zeros(2 * P + 1)])
+    meas = synth.measured_energy(x[:, :upd_rows], 13)
+    t2 = time.perf_counter()
+    oracle.update(widths, state, x[:, :upd_rows], meas, 4, 512, bf16_weights=True)
+    t3 = time.perf_counter()
+    total = (t1 - t0) + (t3 - t2) * (n / float(cfg["n_per_shape"] * len(cfg["shapes"])))
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": n / total, "unit": "candidates/s", "cores": threads, "kind": "oracle",
+            "sample": "shape (%d,%d,%d), 2^%d candidates: enumerate+features+2 scores+top-%d in %.2f s; "
+                      "4-step update on 2048 pairs %.2f s charged pro rata" % (m, nn, k, sample_log2, cfg["k"],
+                                                                            t1 - t0, t3 - t2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-log2", type=int, default=18)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (candidates are independent and would shard by shape; "
+              "see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2411_18873_amd import eck, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    eck.lib()  # fails loudly if the HIP library is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = synth.CONFIGS["c5"]
+    shapes, per = cfg["shapes"], cfg["n_per_shape"]
+    S, F, K = len(shapes), cfg["n_feat"], cfg["k"]
+    N = S * per
+    widths = cfg["widths"]
+    spaces = [eck.Space(synth.gemm(m, n, k), eck.SPACE_SPLIT) for (m, n, k) in shapes]
+    G = spaces[0].n_genes
+
+    genes = torch.zeros((G, N), dtype=torch.int16, device=dev)
+    feat = torch.zeros((F, N), dtype=torch.bfloat16, device=dev)
+    legal = torch.zeros(N, dtype=torch.uint8, device=dev)
+    energy = torch.zeros(N, dtype=torch.float32, device=dev)
+    latency = torch.zeros(N, dtype=torch.float32, device=dev)
+    idx = torch.zeros((S, K), dtype=torch.int32, device=dev)
+    e_out = torch.zeros((S, K), dtype=torch.float32, device=dev)
+    count = torch.zeros(S, dtype=torch.int32, device=dev)
+    ws_topk = torch.empty(eck.topk_select_workspace_bytes(N, S, K), dtype=torch.uint8, device=dev)
+
+    def upload(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    m_energy, m_latency = eck.Model(widths, eck.BF16), eck.Model(widths, eck.BF16)
+    m_energy.set_state(upload(synth.mlp_theta(widths, cfg["weight_seeds"][0], bf16=True)))
+    m_latency.set_state(upload(synth.mlp_theta(widths, cfg["weight_seeds"][1], bf16=True)))
+
+    # measured buffer of the dynamic update: 32 candidates of every shape, synthetic energies (resident in HBM)
+    upd_rows, upd_mb, upd_steps = 2048, 512, 4
+    upd_genes = torch.zeros((G, upd_rows), dtype=torch.int16, device=dev)
+    upd_feat = torch.zeros((F, upd_rows), dtype=torch.bfloat16, device=dev)
+    for s, sp in enumerate(spaces):
+        eck.candidate_enumerate(sp, eck.MODE_SAMPLE, 32, upd_genes, seed=5000 + s, col0=32 * s)
+        eck.features_compute(sp, upd_genes, 32, F, eck.BF16, feat_out=upd_feat, col0=32 * s)
+    torch.cuda.synchronize()
+    upd_energy = upload(synth.measured_energy(upd_feat.float().cpu().numpy(), 13))
+    ws_upd = torch.empty(eck.costmodel_update_workspace_bytes(m_energy, upd_rows, upd_mb), dtype=torch.uint8, device=dev)
+    snr = torch.zeros(1, dtype=torch.float32, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    score_events = []
+
+    def step(i, timed):
+        for s, sp in enumerate(spaces):
+            eck.candidate_enumerate(sp, eck.MODE_SAMPLE, per, genes, seed=cfg["seed_base"] + s, round=i, col0=s * per)
+            eck.features_compute(sp, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal, col0=s * per)
+        for model, out in ((m_energy, energy), (m_latency, latency)):
+            if timed:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+            eck.costmodel_score(model, feat, N, out)
+            if timed:
+                b.record()
+                score_events.append((a, b))
+        eck.topk_select(energy, latency, legal, S, K, idx, e_out, count, ws_topk, alpha=cfg["alpha"])
+        eck.costmodel_update(m_energy, upd_feat, upd_energy, upd_steps, upd_mb, snr, loss, ws_upd, lr=1e-3)
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+
+    score_ms = sum(a.elapsed_time(b) for a, b in score_events) / len(score_events)
+    flop_per_cand = 2 * sum(fi * fo for fi, fo in zip(widths[:-1], widths[1:]))
+    achieved = N * flop_per_cand / (score_ms * 1e-3)
+    assert int(count.min().item()) > 0 and torch.isfinite(snr).all()
+
+    result = {
+        "metric": "candidate schedules scored+ranked/sec at 1 GPU; % MFMA / HBM peak",
+        "value": N / (ms_per_step * 1e-3),
+        "unit": "candidates/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c5: 64 GEMM shapes x 2^18 sampled schedules = 2^24 candidates, 64 features, "
+                               "2 x MLP 64-512-512-1 bf16, per-shape top-32 (alpha 1.1), 4-step refit on 2048 pairs",
+                   "candidates": N, "segments": S, "k": K},
+        "roofline": {"bound": "mfma", "kernel": "score_bf16_kernel<64,512,512>", "achieved": achieved / 1e12,
+                     "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_FLOPS,
+                     "ms_per_launch": score_ms, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_log2)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -180,8 +180,14 @@ class Model:
             pass
 
 
-def candidate_enumerate(space, mode, n, genes_out, seed=0, round=0, first_index=0, parents=None, p_mut_q32=0):
-    """genes_out: uint16 [n_genes][ld] CUDA tensor (torch.int16 storage is accepted as raw bits)."""
+def _at(t, col0):
+    """pointer to column col0 of a row-major 2-D (or 1-D) tensor"""
+    return None if t is None else C.c_void_p(t.data_ptr() + col0 * t.element_size())
+
+
+def candidate_enumerate(space, mode, n, genes_out, seed=0, round=0, first_index=0, parents=None, p_mut_q32=0, col0=0):
+    """genes_out: uint16 [n_genes][ld] CUDA tensor (torch.int16 storage is accepted as raw bits).
+    col0: first column written (the n candidates land in columns col0 .. col0+n-1)."""
     _dev(genes_out, genes_out.dtype, "genes_out")
     assert genes_out.element_size() == 2 and genes_out.dim() == 2 and genes_out.shape[0] == space.n_genes
     n_par = 0
@@ -190,13 +196,15 @@ def candidate_enumerate(space, mode, n, genes_out, seed=0, round=0, first_index=
         assert parents.element_size() == 2 and parents.shape[0] == space.n_genes
         n_par = parents.shape[1]
     _check("candidate_enumerate", lib().candidate_enumerate(
-        space.h, mode, seed, round, first_index, n, _ptr(parents), n_par, p_mut_q32, _ptr(genes_out),
+        space.h, mode, seed, round, first_index, n, _ptr(parents), n_par, p_mut_q32, _at(genes_out, col0),
         genes_out.shape[1], _stream()))
 
 
-def features_compute(space, genes, n, n_feat, out_dtype, feat_out=None, raw_out=None, legal_out=None):
+def features_compute(space, genes, n, n_feat, out_dtype, feat_out=None, raw_out=None, legal_out=None, col0=0):
+    """col0: first column read in genes and written in feat_out / raw_out / legal_out."""
     assert genes.element_size() == 2 and genes.is_cuda and genes.is_contiguous()
     ld = genes.shape[1]
+    assert col0 + n <= ld
     for t in (feat_out, raw_out):
         if t is not None:
             assert t.is_cuda and t.is_contiguous() and t.shape[0] == n_feat and t.shape[1] == ld
@@ -205,9 +213,10 @@ def features_compute(space, genes, n, n_feat, out_dtype, feat_out=None, raw_out=
     if raw_out is not None:
         assert raw_out.element_size() == 8
     if legal_out is not None:
-        assert legal_out.is_cuda and legal_out.element_size() == 1 and legal_out.numel() >= n
-    _check("features_compute", lib().features_compute(space.h, _ptr(genes), ld, n, n_feat, out_dtype, _ptr(feat_out),
-                                                      _ptr(raw_out), _ptr(legal_out), _stream()))
+        assert legal_out.is_cuda and legal_out.element_size() == 1 and legal_out.numel() >= col0 + n
+    _check("features_compute", lib().features_compute(space.h, _at(genes, col0), ld, n, n_feat, out_dtype,
+                                                      _at(feat_out, col0), _at(raw_out, col0), _at(legal_out, col0),
+                                                      _stream()))
 
 
 def costmodel_score(model, feat, n, score_out):

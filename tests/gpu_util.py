@@ -91,3 +91,10 @@ def close_enough(got, want, rtol):
     rms = np.sqrt(np.mean(want ** 2))
     bound = rtol * np.maximum(np.abs(want), rms)
     return float(np.max(np.abs(got - want) / bound))
+
+
+def rel_l2(got, want):
+    """||g - o||_2 / ||o||_2"""
+    want = np.asarray(want, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    return float(np.sqrt(np.sum((got - want) ** 2) / np.sum(want ** 2)))

@@ -1,5 +1,11 @@
 """GPU parity: costmodel_score against the fp64 oracle.
-Tolerances (relative to max(|o|, rms(o))): 1e-5 for fp32 models, 1e-2 for bf16 models."""
+
+fp32 models: |g - o| <= 1e-5 * max(|o|, rms(o)) for every candidate.
+bf16 models: relative L2 error <= 1e-2 against the exact fp64 oracle.  Element by element the bound
+against the exact oracle is 3e-2 * max(|o|, rms(o)): feeding bf16 first-hidden activations to the matrix
+cores perturbs each of them by up to 2^-9 relative, which alone moves single outputs by up to ~1.4 % of the
+output scale over 2^16 candidates (the oracle shows the same gap between its exact and its bf16-activation
+mode, see test_oracle_score.py).  Against the oracle that rounds the same activations the bound is 2e-3."""
 import numpy as np
 import pytest
 import torch
@@ -18,9 +24,10 @@ def G():
 
 def _features(cfg, n, n_feat, seed=3):
     pb = synth.CONFIGS[cfg]["problem"] if isinstance(cfg, str) else cfg
-    kind = oracle.SPACE_KNOB if cfg == "c1" else oracle.SPACE_SPLIT
+    is_c1 = isinstance(cfg, str) and cfg == "c1"
+    kind = oracle.SPACE_KNOB if is_c1 else oracle.SPACE_SPLIT
     ref = oracle.Space(pb, kind)
-    mode = oracle.MODE_EXHAUSTIVE if cfg == "c1" else oracle.MODE_SAMPLE
+    mode = oracle.MODE_EXHAUSTIVE if is_c1 else oracle.MODE_SAMPLE
     genes = oracle.enumerate_candidates(ref, mode, n, seed=seed)
     _, f32, b16, _ = oracle.features(ref, genes, n_feat)
     return f32, b16
@@ -61,11 +68,13 @@ def test_bf16_model(G, widths, cfg, n):
     want = oracle.score(widths, theta, feat_as_f32, n=n)
     got = G.score_gpu(model, G.bf16_dev(b16), n)
     assert np.isfinite(got).all()
-    worst = G.close_enough(got, want, 1e-2)
+    assert G.rel_l2(got, want) <= 1e-2
+    worst = G.close_enough(got, want, 3e-2)
     assert worst <= 1.0, worst
     # rounding the first hidden layer to bf16 is the only modelled difference: with it emulated the gap shrinks
     emu = oracle.score(widths, theta, feat_as_f32, n=n, emulate_bf16=True)
-    assert G.close_enough(got, emu, 2e-3) <= 1.0
+    worst_emu = G.close_enough(got, emu, 2e-3)
+    assert worst_emu <= 1.0, worst_emu
     # fp32 features are rounded to bf16 on load: same result as feeding the bf16 features
     got32 = G.score_gpu(model, G.to_dev(f32), n)
     assert np.array_equal(got32, got)
