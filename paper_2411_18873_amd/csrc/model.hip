@@ -4,6 +4,7 @@
 // candidates (Alg. 1: LatencyEvaAndPick, EnergyModelEvaAndPick; Sec. 5.4).
 #include <cstring>
 #include <new>
+#include <type_traits>
 
 #include "eck_internal.h"
 
@@ -277,9 +278,91 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const float *__restrict_
 // ------------------------------------------------------------ bf16 forward
 
 // One block = 4 wavefronts; a wavefront carries NC tiles of 32 candidates
-// through all three layers in registers.  W1 and the small vectors stay in LDS
-// for the block's lifetime; W2 is streamed through LDS one 32-unit output
-// chunk at a time and shared by the four wavefronts.
+// through all three layers in registers: lane (h, col) owns candidates
+// base + NC*col + c, c < NC (consecutive in memory, so one 4- or 8-byte load per
+// feature row serves all of a lane's columns).  W1 and the small vectors stay
+// in LDS for the block's lifetime.  W2 streams through two LDS buffers, one
+// 32-unit output chunk (64*H1 bytes) at a time, shared by the four wavefronts:
+// while a chunk is being multiplied the next one is already on its way, written
+// into LDS directly by the load unit (no register staging).
+//
+// With one wavefront per SIMD nothing else hides latency, so the code is
+// software-pipelined by hand: the ReLU / bf16 conversion of layer-1 chunk i-1
+// and the ReLU / w3 product of layer-2 chunk i-1 are issued in between the
+// matrix instructions of chunk i, and the next tile's features are requested
+// while the current tile is still in layer 2.
+// Move a fragment into accumulation registers.  The 256 activation registers of a wavefront do not fit
+// the 256 architectural vector registers next to everything else; matrix instructions read their A/B
+// operands from accumulation registers just as well, so the fragments are parked there once and used
+// in place (a value defined by an "a"-constrained output stays in that register file).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// max(x, 0) as one integer instruction on the float's bits: every negative float (and -0) is a negative
+// integer.  (fmaxf costs a second, canonicalising max.)
+__device__ __forceinline__ float relu(float x)
+{
+    const int bits = __float_as_int(x);
+    return __int_as_float(bits > 0 ? bits : 0);
+}
+
+__device__ __forceinline__ bf16x8 park_in_acc(bf16x8 v)
+{
+    const u32x4 in = __builtin_bit_cast(u32x4, v);
+    u32x4 out;
+    uint32_t o0, o1, o2, o3;
+    asm("v_accvgpr_write_b32 %0, %1" : "=a"(o0) : "v"(in[0]));
+    asm("v_accvgpr_write_b32 %0, %1" : "=a"(o1) : "v"(in[1]));
+    asm("v_accvgpr_write_b32 %0, %1" : "=a"(o2) : "v"(in[2]));
+    asm("v_accvgpr_write_b32 %0, %1" : "=a"(o3) : "v"(in[3]));
+    out[0] = o0;
+    out[1] = o1;
+    out[2] = o2;
+    out[3] = o3;
+    return __builtin_bit_cast(bf16x8, out);
+}
+
+template <int NC, bool FEAT_BF16>
+struct RawFeat {
+    static constexpr int WORDS = FEAT_BF16 ? NC / 2 : NC;
+    uint32_t w[WORDS];
+};
+
+template <int NC, bool FEAT_BF16>
+__device__ __forceinline__ RawFeat<NC, FEAT_BF16> load_raw(const void *feat, uint64_t elem)
+{
+    RawFeat<NC, FEAT_BF16> r;
+    if (FEAT_BF16) {
+        const uint16_t *p = reinterpret_cast<const uint16_t *>(feat) + elem;
+        if (NC == 2) r.w[0] = *reinterpret_cast<const uint32_t *>(p);
+        else {
+            const uint2 v = *reinterpret_cast<const uint2 *>(p);
+            r.w[0] = v.x;
+            r.w[NC / 2 - 1] = v.y;
+        }
+    } else {
+        const float *p = reinterpret_cast<const float *>(feat) + elem;
+        if (NC == 2) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(p);
+            r.w[0] = v.x;
+            r.w[1] = v.y;
+        } else {
+            const uint4 v = *reinterpret_cast<const uint4 *>(p);
+            r.w[0] = v.x;
+            r.w[1] = v.y;
+            r.w[NC - 2] = v.z;
+            r.w[NC - 1] = v.w;
+        }
+    }
+    return r;
+}
+
+template <int NC, bool FEAT_BF16>
+__device__ __forceinline__ __bf16 raw_element(const RawFeat<NC, FEAT_BF16> &r, int c)
+{
+    if (FEAT_BF16) return __builtin_bit_cast(__bf16, (uint16_t)(r.w[c >> 1] >> (16 * (c & 1))));
+    return (__bf16)__uint_as_float(r.w[c]);
+}
+
 template <int F, int H1, int H2, int NC, bool FEAT_BF16>
 __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__restrict__ packed, PackedLayout L,
                                                          const void *__restrict__ feat, uint64_t ld, uint64_t n,
@@ -287,17 +370,61 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
 {
     constexpr int KS1 = F / 16, OC1 = H1 / 32, KS2 = H1 / 16, OC2 = H2 / 32;
     constexpr int TILE = 4 * NC * 32;
+    constexpr int NXLOADS = KS1 * 8; // feature loads per lane per tile
     constexpr uint32_t W1_BYTES = F * H1 * 2, CHUNK_BYTES = 64 * H1; // one W2 output chunk: KS2 fragments of 1 KB
+    constexpr int FRAGS_PER_WAVE = KS2 / 4;                          // each wavefront fetches a quarter of a chunk
+    static_assert(KS2 % 4 == 0 && OC2 % 2 == 0 && (NC == 2 || NC == 4), "unsupported shape");
+    static_assert(NXLOADS < 63, "outstanding feature loads must fit the load counter");
+    using Raw = RawFeat<NC, FEAT_BF16>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     bf16x8 *lds_w1 = reinterpret_cast<bf16x8 *>(lds);
-    bf16x8 *lds_w2 = reinterpret_cast<bf16x8 *>(lds + W1_BYTES);
-    float *lds_b1 = reinterpret_cast<float *>(lds + W1_BYTES + CHUNK_BYTES);
+    unsigned char *lds_w2 = lds + W1_BYTES; // two buffers of CHUNK_BYTES; chunk oc uses buffer oc & 1
+    float *lds_b1 = reinterpret_cast<float *>(lds + W1_BYTES + 2 * CHUNK_BYTES);
     float *lds_b2 = lds_b1 + H1;
     float *lds_w3 = lds_b2 + H2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, col = lane & 31;
+    const unsigned char *w2_src = packed + L.w2;
 
+    // asynchronous fetch of W2 chunk `oc` into its buffer: every lane moves 16 bytes per call and the load
+    // unit writes them to LDS at (wave-uniform base) + 16 * lane
+    auto fetch_chunk = [&](int oc) {
+#pragma unroll
+        for (int i = 0; i < FRAGS_PER_WAVE; ++i) {
+            const uint32_t frag = wave * FRAGS_PER_WAVE + i;
+            const unsigned char *src = w2_src + (uint64_t)oc * CHUNK_BYTES + frag * 1024u + lane * 16u;
+            unsigned char *dst = lds_w2 + (oc & 1) * CHUNK_BYTES + frag * 1024u;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+        }
+    };
+    // the NC candidates of this lane in tile `tile` start at:
+    auto first_candidate = [&](uint32_t tile) { return (uint64_t)tile * TILE + (uint64_t)wave * (NC * 32) + NC * col; };
+    // request the features of one tile: rows 16*ks + 8*h + t, NC consecutive candidates each.  Lanes past
+    // the end read candidate group 0 instead (their columns are computed but never stored).
+    auto load_tile = [&](uint32_t tile, Raw(&raw)[NXLOADS]) {
+        const uint64_t cand = first_candidate(tile);
+        const uint64_t safe = cand < n ? cand : 0; // cand and ld are multiples of NC: the group is inside the row
+        constexpr uint64_t ELEM = FEAT_BF16 ? 2 : 4;
+        const uint64_t row_bytes = ld * ELEM;
+        const unsigned char *p = reinterpret_cast<const unsigned char *>(feat) + ((uint64_t)(8 * h) * ld + safe) * ELEM;
+#pragma unroll
+        for (int ks = 0; ks < KS1; ++ks) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(p, 0);
+                p += row_bytes;
+            }
+            p += 8 * row_bytes;
+        }
+    };
+
+    Raw raw[NXLOADS];
+    if (blockIdx.x < n_tiles) {
+        fetch_chunk(0);
+        load_tile(blockIdx.x, raw);
+    }
     // resident part: W1 fragments and the three vectors
     {
         const uint4 *src = reinterpret_cast<const uint4 *>(packed + L.w1);
@@ -307,110 +434,152 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         for (uint32_t i = tid; i < (uint32_t)(H1 + 2 * H2); i += 256) lds_b1[i] = vb[i]; // b1, b2, w3 are contiguous
     }
     const float b3 = *reinterpret_cast<const float *>(packed + L.b3);
-    const uint4 *w2_src = reinterpret_cast<const uint4 *>(packed + L.w2);
+    __syncthreads();
+
+    auto load_bias = [&](const float *vec, int chunk, f32x16(&acc)[NC]) {
+        const f32x4 *bias = reinterpret_cast<const f32x4 *>(vec + (chunk * 2 + h) * 16);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const f32x4 b = bias[v];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                acc[c][4 * v + 0] = b[0];
+                acc[c][4 * v + 1] = b[1];
+                acc[c][4 * v + 2] = b[2];
+                acc[c][4 * v + 3] = b[3];
+            }
+        }
+    };
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t base = (uint64_t)tile * TILE + (uint64_t)wave * (NC * 32);
+        const bool more_tiles = tile + gridDim.x < n_tiles;
 
-        // ---- layer-1 B fragments: 8 consecutive features of one candidate per lane
+        // ---- layer-1 B fragments from the words requested earlier
         bf16x8 x[NC][KS1];
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const uint64_t cand = base + 32 * c + col;
-            const bool ok = cand < n;
+        for (int c = 0; c < NC; ++c)
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks)
 #pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const uint64_t at = (uint64_t)(16 * ks + 8 * h + t) * ld + cand;
-                    if (FEAT_BF16) {
-                        const uint16_t bits = ok ? reinterpret_cast<const uint16_t *>(feat)[at] : (uint16_t)0;
-                        x[c][ks][t] = __builtin_bit_cast(__bf16, bits);
-                    } else {
-                        x[c][ks][t] = (__bf16)(ok ? reinterpret_cast<const float *>(feat)[at] : 0.0f);
-                    }
-                }
-        }
-        __syncthreads(); // resident LDS data visible (first trip); harmless afterwards
+                for (int t = 0; t < 8; ++t) x[c][ks][t] = raw_element<NC, FEAT_BF16>(raw[ks * 8 + t], c);
 
-        // ---- layer 1: h1 = relu(W1^T x + b1), kept as layer-2 B fragments
+        // ---- layer 1: h1 = relu(W1^T x + b1), kept as layer-2 B fragments; the conversion of chunk oc-1
+        // is issued behind the matrix instructions of chunk oc
         bf16x8 h1[NC][KS2];
-#pragma unroll
-        for (int oc = 0; oc < OC1; ++oc) {
-            f32x16 acc[NC];
-            const f32x4 *bias = reinterpret_cast<const f32x4 *>(lds_b1 + (oc * 2 + h) * 16);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const f32x4 b = bias[v];
-#pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    acc[c][4 * v + 0] = b[0];
-                    acc[c][4 * v + 1] = b[1];
-                    acc[c][4 * v + 2] = b[2];
-                    acc[c][4 * v + 3] = b[3];
-                }
-            }
-#pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) {
-                const bf16x8 a = lds_w1[(oc * KS1 + ks) * 64 + lane];
-#pragma unroll
-                for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, x[c][ks], acc[c], 0, 0, 0);
-            }
+        f32x16 acc1[2][NC];
+        auto convert_chunk = [&](int oc, const f32x16(&acc)[NC]) {
 #pragma unroll
             for (int c = 0; c < NC; ++c)
 #pragma unroll
-                for (int half = 0; half < 2; ++half)
+                for (int half = 0; half < 2; ++half) {
+                    bf16x8 v;
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) h1[c][2 * oc + half][t] = (__bf16)fmaxf(acc[c][8 * half + t], 0.0f);
+                    for (int t = 0; t < 8; ++t) v[t] = (__bf16)relu(acc[c][8 * half + t]);
+                    h1[c][2 * oc + half] = park_in_acc(v);
+                }
+        };
+#pragma unroll
+        for (int oc = 0; oc < OC1; ++oc) {
+            f32x16(&acc)[NC] = acc1[oc & 1];
+            load_bias(lds_b1, oc, acc);
+            bf16x8 a[KS1];
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) a[ks] = lds_w1[(oc * KS1 + ks) * 64 + lane];
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks)
+#pragma unroll
+                for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], x[c][ks], acc[c], 0, 0, 0);
+            if (oc > 0) convert_chunk(oc - 1, acc1[(oc - 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        convert_chunk(OC1 - 1, acc1[(OC1 - 1) & 1]);
 
         // ---- layer 2 + output layer, one 32-unit chunk of W2 at a time
         float y[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) y[c] = 0.0f;
-        for (int oc = 0; oc < OC2; ++oc) {
-            __syncthreads(); // everyone is done with the previous chunk
-            {
-                const uint4 *src = w2_src + (uint64_t)oc * (CHUNK_BYTES / 16);
-                uint4 *dst = reinterpret_cast<uint4 *>(lds_w2);
-#pragma unroll
-                for (uint32_t i = 0; i < CHUNK_BYTES / 16 / 256; ++i) dst[tid + 256 * i] = src[tid + 256 * i];
-            }
+        f32x16 acc2[2][NC];
+
+        // matrix work of chunk oc into acc2[oc & 1]; in between, the output-layer product of chunk oc - 1
+        auto run_chunk = [&](auto parity_tag, int oc, auto has_prev_tag, auto wait_tag) {
+            constexpr int PAR = decltype(parity_tag)::value;
+            constexpr bool has_prev = decltype(has_prev_tag)::value;
+            constexpr int wait_outstanding = decltype(wait_tag)::value;
+            // chunk `oc` has landed in its buffer (this wavefront's share: counter wait; the others': barrier),
+            // and every wavefront has finished reading the other buffer, which the next fetch overwrites
+            if (wait_outstanding == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NXLOADS) : "memory");
             __syncthreads();
-            f32x16 acc[NC];
-            const f32x4 *bias = reinterpret_cast<const f32x4 *>(lds_b2 + (oc * 2 + h) * 16);
+            if (oc + 1 < OC2) fetch_chunk(oc + 1);
+            else if (more_tiles) fetch_chunk(0);
+            // the feature loads must be issued after the chunk fetch: the partial counter wait of chunk 1
+            // relies on that order
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            if (oc == 0 && more_tiles) load_tile(tile + gridDim.x, raw);
+            const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(lds_w2 + PAR * CHUNK_BYTES);
+            f32x16(&acc)[NC] = acc2[PAR];
+            const f32x16(&prev)[NC] = acc2[PAR ^ 1];
+            load_bias(lds_b2, oc, acc);
+            f32x4 wprev[4];
+            if (has_prev) {
+                const f32x4 *wout = reinterpret_cast<const f32x4 *>(lds_w3 + ((oc - 1) * 2 + h) * 16);
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const f32x4 b = bias[v];
-#pragma unroll
-                for (int c = 0; c < NC; ++c) {
-                    acc[c][4 * v + 0] = b[0];
-                    acc[c][4 * v + 1] = b[1];
-                    acc[c][4 * v + 2] = b[2];
-                    acc[c][4 * v + 3] = b[3];
-                }
+                for (int v = 0; v < 4; ++v) wprev[v] = wout[v];
             }
+            constexpr int STEPS_PER_Q = KS2 / 16 > 0 ? KS2 / 16 : 1;
+            // weight fragments are read two k-steps ahead of their use; the scheduling fences keep the
+            // compiler from hoisting all reads to the top (which would spill the activation registers)
+            bf16x8 a[3];
+            a[0] = w2[lane];
+            a[1] = w2[64 + lane];
 #pragma unroll
             for (int ks = 0; ks < KS2; ++ks) {
-                const bf16x8 a = lds_w2[ks * 64 + lane];
+                if (ks + 2 < KS2) a[(ks + 2) % 3] = w2[(ks + 2) * 64 + lane];
 #pragma unroll
-                for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, h1[c][ks], acc[c], 0, 0, 0);
+                for (int c = 0; c < NC; ++c)
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % 3], h1[c][ks], acc[c], 0, 0, 0);
+                if (has_prev && ks % STEPS_PER_Q == 0 && ks / STEPS_PER_Q < 16) {
+                    const int q = ks / STEPS_PER_Q;
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) y[c] = fmaf(relu(prev[c][q]), wprev[q >> 2][q & 3], y[c]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            const f32x4 *wout = reinterpret_cast<const f32x4 *>(lds_w3 + (oc * 2 + h) * 16);
+            if (has_prev && KS2 < 16) {
+#pragma unroll
+                for (int q = KS2; q < 16; ++q)
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) y[c] = fmaf(relu(prev[c][q]), wprev[q >> 2][q & 3], y[c]);
+            }
+        };
+
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        run_chunk(I0{}, 0, std::false_type{}, I0{});
+        if (more_tiles) run_chunk(I1{}, 1, std::true_type{}, I1{}); // chunk 0's feature loads may stay in flight
+        else run_chunk(I1{}, 1, std::true_type{}, I0{});
+        for (int oc = 2; oc < OC2; oc += 2) {
+            run_chunk(I0{}, oc, std::true_type{}, I0{});
+            run_chunk(I1{}, oc + 1, std::true_type{}, I0{});
+        }
+        {
+            const f32x16(&last)[NC] = acc2[(OC2 - 1) & 1];
+            const f32x4 *wout = reinterpret_cast<const f32x4 *>(lds_w3 + ((OC2 - 1) * 2 + h) * 16);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const f32x4 w = wout[v];
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) y[c] = fmaf(fmaxf(acc[c][4 * v + e], 0.0f), w[e], y[c]);
+                    for (int e = 0; e < 4; ++e) y[c] = fmaf(relu(last[c][4 * v + e]), w[e], y[c]);
             }
         }
+        const uint64_t cand = first_candidate(tile);
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const float total = y[c] + __shfl_xor(y[c], 32);
-            const uint64_t cand = base + 32 * c + col;
-            if (h == 0 && cand < n) out[cand] = total + b3;
+            if (h == 0 && cand + c < n) out[cand + c] = total + b3;
         }
     }
 }
@@ -427,7 +596,7 @@ int32_t launch_bf16(const eck_model *m, const void *feat, int32_t feat_dtype, ui
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device);
     const uint32_t grid = n_tiles < (uint32_t)cus ? n_tiles : (uint32_t)cus;
-    const size_t lds = (size_t)F * H1 * 2 + 64 * H1 + (H1 + 2 * H2) * 4;
+    const size_t lds = (size_t)F * H1 * 2 + 2 * 64 * H1 + (H1 + 2 * H2) * 4;
     auto kern_b = score_bf16_kernel<F, H1, H2, NC, true>;
     auto kern_f = score_bf16_kernel<F, H1, H2, NC, false>;
     auto kern = feat_dtype == ECK_BF16 ? kern_b : kern_f;
