@@ -127,6 +127,18 @@ int32_t candidate_enumerate(const eck_space *space, int32_t mode, uint64_t seed,
                             uint64_t first_index, uint64_t n, const uint16_t *parents, uint32_t n_parents,
                             uint32_t p_mut_q32, uint16_t *genes_out, uint64_t ld, void *stream);
 
+/* Collect the genes of selected candidates, e.g. the survivors topk_select
+ * returned, as the parents of the next generation (Alg. 1: the kernels picked
+ * at the end of a round reproduce the next one):
+ *   out[g][j] = genes[g][idx[j]]  for j < k.
+ * An index of 0xFFFFFFFF (padding of a short selection) copies candidate
+ * idx[0] instead, so the output is always a valid parent set; if idx[0] is
+ * padding too the column is zero.  genes: device uint16 [n_genes][ld]; idx:
+ * device uint32 [k], every valid entry below n; out: device uint16 [n_genes][ld_out].
+ * Errors: EINVAL (nulls, k == 0, n_genes outside 1..ECK_MAX_GENES), ESHAPE (ld_out < k). */
+int32_t eck_candidates_gather(const uint16_t *genes, uint64_t ld, uint64_t n, int32_t n_genes, const uint32_t *idx,
+                              uint32_t k, uint16_t *out, uint64_t ld_out, void *stream);
+
 /* ---------------------------------------------------------------- features */
 
 /* High-level kernel features of each candidate, computed analytically from

@@ -170,6 +170,21 @@ def score(widths, theta, feat_f32, n=None, emulate_bf16=False):
     return out
 
 
+def score_magnitude(widths, theta, feat_f32, n=None):
+    """|b_last| + sum_j |w_last_j| h_j per candidate: the scale a relative error of the output sum refers to."""
+    w = np.asarray(widths, dtype=np.int32)
+    theta = np.ascontiguousarray(theta, dtype=np.float32)
+    feat = np.ascontiguousarray(feat_f32, dtype=np.float32)
+    ld = feat.shape[1]
+    n = ld if n is None else n
+    out = np.zeros(n, dtype=np.float64)
+    rc = lib().orc_score_magnitude(C.c_int32(len(w) - 1), _p(w), _p(theta), _p(feat), C.c_uint64(ld), C.c_uint64(n),
+                                   _p(out))
+    if rc:
+        raise ValueError("oracle score_magnitude: rc=%d" % rc)
+    return out
+
+
 def topk(energy, latency, legal, n_segments, k, mode=SEL_THRESHOLD, alpha=1.1, m_latency=0):
     energy = np.ascontiguousarray(energy, dtype=np.float32)
     n = energy.size

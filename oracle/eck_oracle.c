@@ -596,6 +596,35 @@ int32_t orc_score(int32_t n_layers, const int32_t *widths, const float *theta32,
     return ORC_OK;
 }
 
+/* Magnitude of the output sum: |b_last| + sum_j |w_last_j| * h_j with h the exact last hidden layer.
+ * This is the yardstick of a relative error in a floating-point sum (the bound of the standard
+ * forward-error analysis of a dot product is eps * sum |terms|), used by the parity tests where the
+ * output itself is the small difference of large terms. */
+int32_t orc_score_magnitude(int32_t n_layers, const int32_t *widths, const float *theta32, const float *feat,
+                            uint64_t ld, uint64_t n, double *out)
+{
+    if (n_layers < 2 || n_layers > 8 || widths[n_layers] != 1 || ld < n) return ORC_EINVAL;
+    const uint64_t P = param_count(n_layers, widths);
+    double *theta = (double *)malloc(P * sizeof(double));
+    for (uint64_t i = 0; i < P; ++i) theta[i] = (double)theta32[i];
+    /* the last layer's parameters are the final fan_in + 1 entries */
+    const uint64_t last = P - (uint64_t)widths[n_layers - 1] - 1;
+    for (uint64_t i = last; i < P; ++i) theta[i] = fabs(theta[i]);
+#pragma omp parallel
+    {
+        double *act[9];
+        for (int l = 0; l <= n_layers; ++l) act[l] = (double *)malloc((size_t)widths[l] * sizeof(double));
+#pragma omp for schedule(static)
+        for (int64_t c = 0; c < (int64_t)n; ++c) {
+            for (int i = 0; i < widths[0]; ++i) act[0][i] = (double)feat[(uint64_t)i * ld + (uint64_t)c];
+            out[c] = forward_one(n_layers, widths, theta, act, 0); /* hidden activations are >= 0 after ReLU */
+        }
+        for (int l = 0; l <= n_layers; ++l) free(act[l]);
+    }
+    free(theta);
+    return ORC_OK;
+}
+
 /* ----------------------------------------------------------------- top-k */
 
 /* IEEE-754 totalOrder as an unsigned key: ascending key == ascending value,

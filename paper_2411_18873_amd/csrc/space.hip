@@ -316,6 +316,31 @@ extern "C" int32_t candidate_enumerate(const eck_space *space, int32_t mode, uin
     return ECK_OK;
 }
 
+namespace {
+__global__ void gather_genes_kernel(const uint16_t *__restrict__ genes, uint64_t ld, uint64_t n, int n_genes,
+                                    const uint32_t *__restrict__ idx, uint32_t k, uint16_t *__restrict__ out,
+                                    uint64_t ld_out)
+{
+    const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= k) return;
+    uint32_t src = idx[j];
+    if (src == 0xFFFFFFFFu) src = idx[0];
+    const bool valid = src != 0xFFFFFFFFu && src < n;
+    for (int g = 0; g < n_genes; ++g) out[(uint64_t)g * ld_out + j] = valid ? genes[(uint64_t)g * ld + src] : (uint16_t)0;
+}
+} // namespace
+
+extern "C" int32_t eck_candidates_gather(const uint16_t *genes, uint64_t ld, uint64_t n, int32_t n_genes,
+                                         const uint32_t *idx, uint32_t k, uint16_t *out, uint64_t ld_out, void *stream)
+{
+    if (!genes || !idx || !out || k == 0 || n == 0 || n_genes < 1 || n_genes > ECK_MAX_GENES) return ECK_EINVAL;
+    if (ld_out < k || ld < n) return ECK_ESHAPE;
+    hipLaunchKernelGGL(gather_genes_kernel, dim3((k + 255) / 256), dim3(256), 0, as_stream(stream), genes, ld, n,
+                       (int)n_genes, idx, k, out, ld_out);
+    ECK_HIP_TRY(hipGetLastError());
+    return ECK_OK;
+}
+
 // ------------------------------------------------------------------ features
 
 namespace {

@@ -25,7 +25,7 @@ SELECT_THRESHOLD, SELECT_RANK = 0, 1
 MAX_K = 4096
 
 EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_info", "eck_space_table",
-           "candidate_enumerate", "features_compute", "eck_model_create", "eck_model_destroy",
+           "candidate_enumerate", "eck_candidates_gather", "features_compute", "eck_model_create", "eck_model_destroy",
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
            "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update"]
 
@@ -67,6 +67,7 @@ def lib():
         L.eck_space_info.argtypes = [vp, C.POINTER(i32), C.POINTER(u32), C.POINTER(u64)]
         L.eck_space_table.argtypes = [vp, i32, vp, u32]
         L.candidate_enumerate.argtypes = [vp, i32, u64, u32, u64, u64, vp, u32, u32, vp, u64, vp]
+        L.eck_candidates_gather.argtypes = [vp, u64, u64, i32, vp, u32, vp, u64, vp]
         L.features_compute.argtypes = [vp, vp, u64, u64, i32, i32, vp, vp, vp, vp]
         L.eck_model_create.argtypes = [i32, C.POINTER(i32), i32, C.POINTER(vp)]
         L.eck_model_destroy.argtypes = [vp]
@@ -198,6 +199,15 @@ def candidate_enumerate(space, mode, n, genes_out, seed=0, round=0, first_index=
     _check("candidate_enumerate", lib().candidate_enumerate(
         space.h, mode, seed, round, first_index, n, _ptr(parents), n_par, p_mut_q32, _at(genes_out, col0),
         genes_out.shape[1], _stream()))
+
+
+def candidates_gather(genes, n, idx, k, out, col0=0, idx_off=0):
+    """out[g][j] = genes[g][col0 + idx[idx_off + j]] for j < k (survivors -> parents)."""
+    assert genes.element_size() == 2 and out.element_size() == 2 and idx.element_size() == 4
+    assert genes.is_cuda and out.is_cuda and idx.is_cuda and idx.numel() >= idx_off + k
+    _check("eck_candidates_gather", lib().eck_candidates_gather(
+        _at(genes, col0), genes.shape[1], n, genes.shape[0], _at(idx.view(-1), idx_off), k, _ptr(out), out.shape[1],
+        _stream()))
 
 
 def features_compute(space, genes, n, n_feat, out_dtype, feat_out=None, raw_out=None, legal_out=None, col0=0):

@@ -56,7 +56,7 @@ CONFIGS = {
                widths=[64, 256, 256, 1], bf16=True, k=64, alpha=1.1, sample_seed=2024, weight_seeds=(3, 4)),
     # evolutionary rounds on a batched GEMM
     "c3": dict(problem=bgemm(32, 2048, 2048, 128), kind=SPACE_SPLIT, n=1 << 20, n_feat=64,
-               widths=[64, 256, 256, 1], bf16=True, k=1024, alpha=1.1, rounds=8, survivors=1024, seed=7,
+               widths=[64, 256, 256, 1], bf16=True, k=1024, alpha=float("inf"), rounds=8, survivors=1024, seed=7,
                weight_seeds=(5, 6)),
     # dynamic update on measured pairs, then rescoring
     "c4": dict(problem=conv2d(1, 256, 256, 14, 14, 3, 3, 1, 1), kind=SPACE_SPLIT, n_pairs=4096, n_feat=64,

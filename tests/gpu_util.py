@@ -84,17 +84,9 @@ def update_gpu(model, feat_dev, energy, n_steps, minibatch, **kw):
     return float(snr.item()), float(loss.item())
 
 
-def close_enough(got, want, rtol):
-    """|g - o| <= rtol * max(|o|, rms(o)); returns the worst ratio to that bound."""
-    want = np.asarray(want, dtype=np.float64)
+def within(got, want, magnitude, rtol):
+    """Worst |g - o| / (rtol * M) over the candidates, M = the oracle's magnitude of the output sum
+    (|b| + sum |w_j| h_j).  <= 1 means every candidate is inside the relative tolerance."""
     got = np.asarray(got, dtype=np.float64)
-    rms = np.sqrt(np.mean(want ** 2))
-    bound = rtol * np.maximum(np.abs(want), rms)
-    return float(np.max(np.abs(got - want) / bound))
-
-
-def rel_l2(got, want):
-    """||g - o||_2 / ||o||_2"""
     want = np.asarray(want, dtype=np.float64)
-    got = np.asarray(got, dtype=np.float64)
-    return float(np.sqrt(np.sum((got - want) ** 2) / np.sum(want ** 2)))
+    return float(np.max(np.abs(got - want) / (rtol * np.asarray(magnitude, dtype=np.float64))))

@@ -1,11 +1,12 @@
 """GPU parity: costmodel_score against the fp64 oracle.
 
-fp32 models: |g - o| <= 1e-5 * max(|o|, rms(o)) for every candidate.
-bf16 models: relative L2 error <= 1e-2 against the exact fp64 oracle.  Element by element the bound
-against the exact oracle is 3e-2 * max(|o|, rms(o)): feeding bf16 first-hidden activations to the matrix
-cores perturbs each of them by up to 2^-9 relative, which alone moves single outputs by up to ~1.4 % of the
-output scale over 2^16 candidates (the oracle shows the same gap between its exact and its bf16-activation
-mode, see test_oracle_score.py).  Against the oracle that rounds the same activations the bound is 2e-3."""
+Tolerance: |g - o| <= rtol * M per candidate, rtol = 1e-5 for fp32 models and 1e-2 for bf16 models, where
+M = |b3| + sum_j |w3_j| h2_j is the magnitude of the output sum (from the oracle).  The output of these
+networks is a small difference of large terms (|o| is often 10-60x below M, and for some weight seeds its
+mean over the space is ~0), so relating the error to |o| or to rms(o) would measure the cancellation, not the
+arithmetic; M is what a relative error of a floating-point sum refers to.  A second, tighter check compares with
+the oracle mode that rounds the first hidden layer to bf16 exactly where the kernel does: 1e-4 * M
+(what remains is fp32 accumulation order and rare rounding flips of single activations; measured < 1e-6 * M)."""
 import numpy as np
 import pytest
 import torch
@@ -41,7 +42,7 @@ def test_fp32_model_c1(G):
         model = G.make_model(widths, eck.F32, theta)
         got = G.score_gpu(model, G.to_dev(f32), 6400)
         want = oracle.score(widths, theta, f32)
-        assert G.close_enough(got, want, 1e-5) <= 1.0
+        assert G.within(got, want, oracle.score_magnitude(widths, theta, f32), 1e-5) <= 1.0
         assert np.isfinite(got).all()
 
 
@@ -53,7 +54,7 @@ def test_fp32_model_wide_and_ragged(G):
     n = 1987  # ld = 2000 > n, last block partly empty
     got = G.score_gpu(model, G.to_dev(f32), n)
     want = oracle.score(widths, theta, f32, n=n)
-    assert G.close_enough(got, want, 1e-5) <= 1.0
+    assert G.within(got, want, oracle.score_magnitude(widths, theta, f32, n=n), 1e-5) <= 1.0
 
 
 @pytest.mark.parametrize("widths,cfg,n", [([64, 256, 256, 1], "c2", 5000), ([64, 512, 512, 1], None, 4133),
@@ -68,13 +69,14 @@ def test_bf16_model(G, widths, cfg, n):
     want = oracle.score(widths, theta, feat_as_f32, n=n)
     got = G.score_gpu(model, G.bf16_dev(b16), n)
     assert np.isfinite(got).all()
-    assert G.rel_l2(got, want) <= 1e-2
-    worst = G.close_enough(got, want, 3e-2)
+    mag = oracle.score_magnitude(widths, theta, feat_as_f32, n=n)
+    worst = G.within(got, want, mag, 1e-2)
     assert worst <= 1.0, worst
     # rounding the first hidden layer to bf16 is the only modelled difference: with it emulated the gap shrinks
     emu = oracle.score(widths, theta, feat_as_f32, n=n, emulate_bf16=True)
-    worst_emu = G.close_enough(got, emu, 2e-3)
+    worst_emu = G.within(got, emu, mag, 1e-4)
     assert worst_emu <= 1.0, worst_emu
+    print("bf16 score parity %s: worst/1e-2 = %.3f, vs bf16-activation oracle worst/1e-4 = %.4f" % (widths, worst, worst_emu))
     # fp32 features are rounded to bf16 on load: same result as feeding the bf16 features
     got32 = G.score_gpu(model, G.to_dev(f32), n)
     assert np.array_equal(got32, got)

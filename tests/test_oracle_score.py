@@ -86,21 +86,40 @@ def test_bf16_emulation_rounds_only_the_first_hidden_layer():
     assert np.allclose(emu, h2 @ w3 + b3, rtol=1e-12, atol=1e-12)
 
 
-def test_bf16_activations_alone_cost_about_one_percent_on_single_outputs():
-    """Why the element-wise bound for bf16 models is 3e-2 and the 1e-2 bound is on the L2 error: the
-    oracle's own two modes (exact, first hidden layer rounded to bf16) already differ by more than 1e-2
-    of the output scale on single candidates, with identical weights and inputs."""
+def test_output_magnitude_yardstick():
+    # hand-worked 2-2-1 network of test_hand_worked_two_layer_network with a negative output weight:
+    # x = (1, 2): h = (2, 0) -> o = 2*2 - 3*0 - 1 = 3, magnitude |2|*2 + |-3|*0 + |-1| = 5
+    theta = np.array([1, -1, 0.5, 1, 0, -2, 2, -3, -1], dtype=np.float32)
+    feat = np.array([[1.0, 4.0], [2.0, 0.0]], dtype=np.float32)
+    assert list(oracle.score([2, 2, 1], theta, feat)) == [3.0, 7.0]
+    assert list(oracle.score_magnitude([2, 2, 1], theta, feat)) == [5.0, 9.0]
+    # with non-negative output weights and bias the magnitude is the score itself
+    widths = [32, 64, 64, 1]
+    t = synth.mlp_theta(widths, 2, bias_scale=0.3)
+    t[-65:] = np.abs(t[-65:])
+    x = (np.random.default_rng(0).random((32, 50)) * 30).astype(np.float32)
+    assert np.allclose(oracle.score(widths, t, x), oracle.score_magnitude(widths, t, x), rtol=1e-14)
+
+
+def test_why_the_tolerance_refers_to_the_magnitude_of_the_sum():
+    """The outputs of these random networks are small differences of large terms: relative to |o| or
+    rms(o) the unavoidable bf16-activation rounding looks like anything from 0.1 % to 6 % depending on the
+    weight seed, relative to the magnitude M of the sum it is a stable ~1e-3."""
     import oracle as orc
     widths = [64, 256, 256, 1]
     sp = orc.Space(synth.CONFIGS["c2"]["problem"], orc.SPACE_SPLIT)
-    genes = orc.enumerate_candidates(sp, orc.MODE_SAMPLE, 1 << 14, seed=3)
+    genes = orc.enumerate_candidates(sp, orc.MODE_SAMPLE, 1 << 13, seed=2024)
     _, _, b16, _ = orc.features(sp, genes, 64)
     x = orc.bf16_bits_to_f32(b16)
-    theta = synth.mlp_theta(widths, 8, bf16=True)
-    exact = orc.score(widths, theta, x)
-    emu = orc.score(widths, theta, x, emulate_bf16=True)
-    rms = np.sqrt((exact ** 2).mean())
-    worst = (np.abs(emu - exact) / np.maximum(np.abs(exact), rms)).max()
-    l2 = np.sqrt(((emu - exact) ** 2).sum() / (exact ** 2).sum())
-    assert 0.8e-2 < worst < 3e-2
-    assert 1e-3 < l2 < 5e-3
+    vs_rms, vs_mag = [], []
+    for seed in (3, 4):
+        theta = synth.mlp_theta(widths, seed, bf16=True)
+        exact = orc.score(widths, theta, x)
+        emu = orc.score(widths, theta, x, emulate_bf16=True)
+        mag = orc.score_magnitude(widths, theta, x)
+        rms = np.sqrt((exact ** 2).mean())
+        vs_rms.append((np.abs(emu - exact) / np.maximum(np.abs(exact), rms)).max())
+        vs_mag.append((np.abs(emu - exact) / mag).max())
+        assert mag.min() > 3 * np.abs(exact).max() or seed == 3
+    assert vs_rms[1] > 10 * vs_rms[0]          # same arithmetic, wildly different "relative" error
+    assert max(vs_mag) < 2e-3 and max(vs_mag) < 2 * min(vs_mag)
