@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=18)
+    ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update"], default=None,
+                    help="profiling aid: after set-up run only this call of the step (prints a short JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (candidates are independent and would shard by shape; "
@@ -143,6 +145,36 @@ def main():
                 score_events.append((a, b))
         eck.topk_select(energy, latency, legal, S, K, idx, e_out, count, ws_topk, alpha=cfg["alpha"])
         eck.costmodel_update(m_energy, upd_feat, upd_energy, upd_steps, upd_mb, snr, loss, ws_upd, lr=1e-3)
+
+    if args.only:
+        step(0, False)  # fills every buffer once
+        torch.cuda.synchronize()
+
+        def one(i):
+            if args.only == "enumerate":
+                for s, sp in enumerate(spaces):
+                    eck.candidate_enumerate(sp, eck.MODE_SAMPLE, per, genes, seed=cfg["seed_base"] + s, round=i,
+                                            col0=s * per)
+            elif args.only == "features":
+                for s, sp in enumerate(spaces):
+                    eck.features_compute(sp, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal, col0=s * per)
+            elif args.only == "score":
+                eck.costmodel_score(m_energy, feat, N, energy)
+            elif args.only == "topk":
+                eck.topk_select(energy, latency, legal, S, K, idx, e_out, count, ws_topk, alpha=cfg["alpha"])
+            else:
+                eck.costmodel_update(m_energy, upd_feat, upd_energy, upd_steps, upd_mb, snr, loss, ws_upd, lr=1e-3)
+
+        for i in range(args.warmup):
+            one(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            one(args.warmup + i)
+        torch.cuda.synchronize()
+        ms = 1e3 * (time.perf_counter() - t0) / args.steps
+        print(json.dumps({"only": args.only, "ms_per_call": ms, "candidates": N, "steps": args.steps}))
+        return
 
     for i in range(args.warmup):
         step(i, False)

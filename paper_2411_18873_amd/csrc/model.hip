@@ -31,9 +31,12 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // So activations never leave registers between layers.
 //
 // Packed buffer of a BF16 model (byte offsets 16-aligned):
-//   W1 fragments [H1/32][F/16][64 lanes][8 bf16]
-//   W2 fragments [H2/32][H1/16][64 lanes][8 bf16]   (k permuted as above)
-//   b1 [H1/32][2][16] fp32, b2 [H2/32][2][16], w3 [H2/32][2][16]  (D-register order), b3 (1 float, padded to 4)
+//   W1 fragments   [H1/32][F/16][64 lanes][8 bf16]
+//   b1 fragments   [H1/32][64 lanes][8 bf16]: one extra k-step of layer 1 whose only non-zero k slot
+//                  (lane half 0, slot 0) holds b1 -- multiplied by a constant-one activation it adds the
+//                  bias inside the matrix unit instead of with 32 vector moves per tile
+//   W2 fragments   [H2/32][H1/16][64 lanes][8 bf16]   (k permuted as above)
+//   b2 [H2/32][2][16] fp32, w3 [H2/32][2][16] fp32   (D-register order), b3 (1 float, padded to 4)
 
 __host__ __device__ inline uint32_t unit_of_dreg(uint32_t chunk, uint32_t h, uint32_t q)
 {
@@ -41,16 +44,16 @@ __host__ __device__ inline uint32_t unit_of_dreg(uint32_t chunk, uint32_t h, uin
 }
 
 struct PackedLayout {
-    uint64_t w1, w2, b1, b2, w3, b3, total; // byte offsets
+    uint64_t w1, w1b, w2, b2, w3, b3, total; // byte offsets
 };
 
 PackedLayout packed_layout(int F, int H1, int H2)
 {
     PackedLayout L;
     L.w1 = 0;
-    L.w2 = L.w1 + (uint64_t)F * H1 * 2;
-    L.b1 = L.w2 + (uint64_t)H1 * H2 * 2;
-    L.b2 = L.b1 + (uint64_t)H1 * 4;
+    L.w1b = L.w1 + (uint64_t)F * H1 * 2;
+    L.w2 = L.w1b + (uint64_t)(H1 / 32) * 1024;
+    L.b2 = L.w2 + (uint64_t)H1 * H2 * 2;
     L.w3 = L.b2 + (uint64_t)H2 * 4;
     L.b3 = L.w3 + (uint64_t)H2 * 4;
     L.total = L.b3 + 16;
@@ -76,8 +79,8 @@ __global__ void pack_kernel(const float *__restrict__ theta, int F, int H1, int 
                             uint64_t off_w2, uint64_t off_b2, uint64_t off_w3, uint64_t off_b3,
                             unsigned char *__restrict__ packed, PackedLayout L)
 {
-    const uint32_t n_w1 = F * H1, n_w2 = H1 * H2;
-    const uint32_t total = n_w1 + n_w2 + H1 + 2 * H2 + 1;
+    const uint32_t n_w1 = F * H1, n_w1b = (H1 / 32) * 512, n_w2 = H1 * H2;
+    const uint32_t total = n_w1 + n_w1b + n_w2 + 2 * H2 + 1;
     for (uint32_t e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
         if (e < n_w1) {
             // [oc][ks][lane][t]
@@ -86,19 +89,21 @@ __global__ void pack_kernel(const float *__restrict__ theta, int F, int H1, int 
             const uint32_t h = lane >> 5, r = lane & 31;
             const uint32_t k = 16 * ks + 8 * h + t, unit = 32 * oc + r;
             reinterpret_cast<uint16_t *>(packed + L.w1)[e] = bf16_bits(theta[off_w1 + (uint64_t)k * H1 + unit]);
-        } else if (e < n_w1 + n_w2) {
+        } else if (e < n_w1 + n_w1b) {
             const uint32_t x = e - n_w1;
+            const uint32_t t = x & 7, lane = (x >> 3) & 63, oc = x >> 9;
+            const bool holds_bias = t == 0 && lane < 32;
+            reinterpret_cast<uint16_t *>(packed + L.w1b)[x] = holds_bias ? bf16_bits(theta[off_b1 + 32 * oc + lane]) : (uint16_t)0;
+        } else if (e < n_w1 + n_w1b + n_w2) {
+            const uint32_t x = e - n_w1 - n_w1b;
             const uint32_t t = x & 7, lane = (x >> 3) & 63, frag = x >> 9;
             const uint32_t ksteps = H1 / 16, ks = frag % ksteps, oc = frag / ksteps;
             const uint32_t h = lane >> 5, r = lane & 31;
             const uint32_t k = unit_of_dreg(ks >> 1, h, 8 * (ks & 1) + t), unit = 32 * oc + r;
             reinterpret_cast<uint16_t *>(packed + L.w2)[x] = bf16_bits(theta[off_w2 + (uint64_t)k * H2 + unit]);
         } else {
-            uint32_t x = e - n_w1 - n_w2;
-            if (x < (uint32_t)H1) {
-                const uint32_t q = x & 15, h = (x >> 4) & 1, chunk = x >> 5;
-                reinterpret_cast<float *>(packed + L.b1)[x] = round_through_bf16(theta[off_b1 + unit_of_dreg(chunk, h, q)]);
-            } else if ((x -= H1) < (uint32_t)H2) {
+            uint32_t x = e - n_w1 - n_w1b - n_w2;
+            if (x < (uint32_t)H2) {
                 const uint32_t q = x & 15, h = (x >> 4) & 1, chunk = x >> 5;
                 reinterpret_cast<float *>(packed + L.b2)[x] = round_through_bf16(theta[off_b2 + unit_of_dreg(chunk, h, q)]);
             } else if ((x -= H2) < (uint32_t)H2) {
@@ -124,7 +129,7 @@ int32_t eck::model_repack(eck_model *m, hipStream_t stream)
     if (m->dtype != ECK_BF16) return ECK_OK;
     const int F = m->widths[0], H1 = m->widths[1], H2 = m->widths[2];
     const PackedLayout L = packed_layout(F, H1, H2);
-    const uint32_t total = F * H1 + H1 * H2 + H1 + 2 * H2 + 1;
+    const uint32_t total = F * H1 + (H1 / 32) * 512 + H1 * H2 + 2 * H2 + 1;
     hipLaunchKernelGGL(pack_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, m->d_state, F, H1, H2,
                        m->off_w[0], m->off_b[0], m->off_w[1], m->off_b[1], m->off_w[2], m->off_b[2],
                        (unsigned char *)m->d_packed, L);
@@ -277,25 +282,10 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const float *__restrict_
 
 // ------------------------------------------------------------ bf16 forward
 
-// One block = 4 wavefronts; a wavefront carries NC tiles of 32 candidates
-// through all three layers in registers: lane (h, col) owns candidates
-// base + NC*col + c, c < NC (consecutive in memory, so one 4- or 8-byte load per
-// feature row serves all of a lane's columns).  W1 and the small vectors stay
-// in LDS for the block's lifetime.  W2 streams through two LDS buffers, one
-// 32-unit output chunk (64*H1 bytes) at a time, shared by the four wavefronts:
-// while a chunk is being multiplied the next one is already on its way, written
-// into LDS directly by the load unit (no register staging).
-//
-// With one wavefront per SIMD nothing else hides latency, so the code is
-// software-pipelined by hand: the ReLU / bf16 conversion of layer-1 chunk i-1
-// and the ReLU / w3 product of layer-2 chunk i-1 are issued in between the
-// matrix instructions of chunk i, and the next tile's features are requested
-// while the current tile is still in layer 2.
-// Move a fragment into accumulation registers.  The 256 activation registers of a wavefront do not fit
-// the 256 architectural vector registers next to everything else; matrix instructions read their A/B
-// operands from accumulation registers just as well, so the fragments are parked there once and used
-// in place (a value defined by an "a"-constrained output stays in that register file).
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // max(x, 0) as one integer instruction on the float's bits: every negative float (and -0) is a negative
 // integer.  (fmaxf costs a second, canonicalising max.)
@@ -305,6 +295,10 @@ __device__ __forceinline__ float relu(float x)
     return __int_as_float(bits > 0 ? bits : 0);
 }
 
+// Move a fragment into accumulation registers.  The 256 activation registers of a wavefront do not fit
+// the 256 architectural vector registers next to everything else; matrix instructions read their A/B
+// operands from accumulation registers just as well, so the fragments are parked there once and used
+// in place (a value defined by an "a"-constrained output stays in that register file).
 __device__ __forceinline__ bf16x8 park_in_acc(bf16x8 v)
 {
     const u32x4 in = __builtin_bit_cast(u32x4, v);
@@ -321,6 +315,27 @@ __device__ __forceinline__ bf16x8 park_in_acc(bf16x8 v)
     return __builtin_bit_cast(bf16x8, out);
 }
 
+// One block = 4 wavefronts; a wavefront carries NC tiles of 32 candidates
+// through all three layers in registers: lane (h, col) owns candidates
+// base + NC*col + c, c < NC (consecutive in memory, so one 4- or 8-byte load per
+// feature row serves all of a lane's columns).  W1 (with its bias fragments) and
+// the b2 / w3 vectors stay in LDS for the block's lifetime.  W2 streams through
+// a ring of four LDS slots in pieces of half an output chunk (32 units x H1/2
+// inputs), shared by the four wavefronts and written into LDS directly by the
+// load unit (no register staging), three pieces ahead of their use.
+//
+// Ring protocol, piece g (numbered along the block's whole run): at its top a
+// wavefront waits until its own share of piece g+1 has landed, then the block
+// barrier -- after which (i) all of piece g+1 is visible to everyone, so the
+// weight fragments can be read ahead across the piece boundary without exposing
+// LDS latency, and (ii) everyone has finished piece g-1, whose slot the fetch of
+// piece g+3 may now overwrite.
+//
+// With one wavefront per SIMD nothing else hides latency, so the code is
+// software-pipelined by hand: the ReLU / bf16 conversion of layer-1 chunk i-1
+// and the bias / ReLU / w3 product of layer-2 chunk i-1 are issued in between the
+// matrix instructions of chunk i, and the next tile's features are requested
+// while the current tile is still in layer 2.
 template <int NC, bool FEAT_BF16>
 struct RawFeat {
     static constexpr int WORDS = FEAT_BF16 ? NC / 2 : NC;
@@ -328,25 +343,23 @@ struct RawFeat {
 };
 
 template <int NC, bool FEAT_BF16>
-__device__ __forceinline__ RawFeat<NC, FEAT_BF16> load_raw(const void *feat, uint64_t elem)
+__device__ __forceinline__ RawFeat<NC, FEAT_BF16> load_raw(const void *ptr)
 {
     RawFeat<NC, FEAT_BF16> r;
     if (FEAT_BF16) {
-        const uint16_t *p = reinterpret_cast<const uint16_t *>(feat) + elem;
-        if (NC == 2) r.w[0] = *reinterpret_cast<const uint32_t *>(p);
+        if (NC == 2) r.w[0] = *reinterpret_cast<const uint32_t *>(ptr);
         else {
-            const uint2 v = *reinterpret_cast<const uint2 *>(p);
+            const uint2 v = *reinterpret_cast<const uint2 *>(ptr);
             r.w[0] = v.x;
             r.w[NC / 2 - 1] = v.y;
         }
     } else {
-        const float *p = reinterpret_cast<const float *>(feat) + elem;
         if (NC == 2) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(p);
+            const uint2 v = *reinterpret_cast<const uint2 *>(ptr);
             r.w[0] = v.x;
             r.w[1] = v.y;
         } else {
-            const uint4 v = *reinterpret_cast<const uint4 *>(p);
+            const uint4 v = *reinterpret_cast<const uint4 *>(ptr);
             r.w[0] = v.x;
             r.w[1] = v.y;
             r.w[NC - 2] = v.z;
@@ -363,6 +376,34 @@ __device__ __forceinline__ __bf16 raw_element(const RawFeat<NC, FEAT_BF16> &r, i
     return (__bf16)__uint_as_float(r.w[c]);
 }
 
+// One direct-to-LDS load: every lane moves 16 bytes from its own global address and the load unit
+// writes them to LDS at lds_byte_address (wave-uniform, handed over in M0) + 16 * lane.  Written as
+// assembly on purpose: issued through the compiler's own intrinsic, a load of this kind in flight makes
+// the compiler drain *all* LDS reads at every dependency (it may no longer wait for just the oldest),
+// which stalls the matrix pipeline at every weight fragment.  Completion is tracked by hand instead:
+// the s_waitcnt vmcnt(...) + barrier protocol of the caller.
+__device__ __forceinline__ void lds_dma_16(const void *global_src, uint32_t lds_byte_address)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_byte_address)), "v"(global_src)
+                 : "memory", "m0");
+}
+
+// wait until only the operations issued after the fetch in question may still be outstanding:
+// one later piece fetch (N_DMA loads) and / or the NX feature loads of the next tile
+template <int N_DMA, int NX>
+__device__ __forceinline__ void wait_vm(bool dma_after, bool x_after)
+{
+    if (dma_after) {
+        if (x_after) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_DMA + NX) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_DMA) : "memory");
+    } else {
+        if (x_after) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NX) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+}
+
 template <int F, int H1, int H2, int NC, bool FEAT_BF16>
 __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__restrict__ packed, PackedLayout L,
                                                          const void *__restrict__ feat, uint64_t ld, uint64_t n,
@@ -370,33 +411,40 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
 {
     constexpr int KS1 = F / 16, OC1 = H1 / 32, KS2 = H1 / 16, OC2 = H2 / 32;
     constexpr int TILE = 4 * NC * 32;
-    constexpr int NXLOADS = KS1 * 8; // feature loads per lane per tile
-    constexpr uint32_t W1_BYTES = F * H1 * 2, CHUNK_BYTES = 64 * H1; // one W2 output chunk: KS2 fragments of 1 KB
-    constexpr int FRAGS_PER_WAVE = KS2 / 4;                          // each wavefront fetches a quarter of a chunk
-    static_assert(KS2 % 4 == 0 && OC2 % 2 == 0 && (NC == 2 || NC == 4), "unsupported shape");
-    static_assert(NXLOADS < 63, "outstanding feature loads must fit the load counter");
+    constexpr int NXLOADS = KS1 * 8;                 // feature loads per lane per tile
+    constexpr int KSP = KS2 / 2;                     // k-steps (= 1 KB fragments) per piece
+    constexpr int PIECES = 2 * OC2;                  // pieces per tile
+    constexpr int RING = KSP < 4 ? KSP : 4;          // weight fragments held in registers
+    constexpr int PF = RING - 1;                     // LDS read-ahead in k-steps
+    constexpr int N_DMA = KSP / 4 > 0 ? KSP / 4 : 1; // 1 KB fetches per wavefront per piece
+    constexpr uint32_t W1_BYTES = F * H1 * 2, W1B_BYTES = OC1 * 1024, PIECE_BYTES = KSP * 1024;
+    static_assert(KS2 % 2 == 0 && KSP % RING == 0 && OC2 % 2 == 0 && PIECES % 4 == 0, "unsupported shape");
+    static_assert(NC == 2 || NC == 4, "unsupported tile width");
+    static_assert(N_DMA + NXLOADS < 63, "outstanding loads must fit the load counter");
     using Raw = RawFeat<NC, FEAT_BF16>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    bf16x8 *lds_w1 = reinterpret_cast<bf16x8 *>(lds);
-    unsigned char *lds_w2 = lds + W1_BYTES; // two buffers of CHUNK_BYTES; chunk oc uses buffer oc & 1
-    float *lds_b1 = reinterpret_cast<float *>(lds + W1_BYTES + 2 * CHUNK_BYTES);
-    float *lds_b2 = lds_b1 + H1;
+    const bf16x8 *lds_w1 = reinterpret_cast<const bf16x8 *>(lds);
+    const bf16x8 *lds_w1b = reinterpret_cast<const bf16x8 *>(lds + W1_BYTES);
+    unsigned char *lds_ring = lds + W1_BYTES + W1B_BYTES; // four slots of PIECE_BYTES; piece p uses slot p & 3
+    float *lds_b2 = reinterpret_cast<float *>(lds_ring + 4 * PIECE_BYTES);
     float *lds_w3 = lds_b2 + H2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, col = lane & 31;
     const unsigned char *w2_src = packed + L.w2;
+    const uint32_t ring_lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds_ring;
 
-    // asynchronous fetch of W2 chunk `oc` into its buffer: every lane moves 16 bytes per call and the load
-    // unit writes them to LDS at (wave-uniform base) + 16 * lane
-    auto fetch_chunk = [&](int oc) {
+    // asynchronous fetch of piece p (0 <= p < PIECES, the same for every tile) into slot p & 3: every lane
+    // moves 16 bytes per call, the load unit writes them to LDS at (wave-uniform base) + 16 * lane
+    auto fetch_piece = [&](int p) {
 #pragma unroll
-        for (int i = 0; i < FRAGS_PER_WAVE; ++i) {
-            const uint32_t frag = wave * FRAGS_PER_WAVE + i;
-            const unsigned char *src = w2_src + (uint64_t)oc * CHUNK_BYTES + frag * 1024u + lane * 16u;
-            unsigned char *dst = lds_w2 + (oc & 1) * CHUNK_BYTES + frag * 1024u;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+        for (int i = 0; i < N_DMA; ++i) {
+            const uint32_t frag = wave * N_DMA + i;
+            if (KSP >= 4 || frag < (uint32_t)KSP) {
+                const unsigned char *src = w2_src + (uint64_t)p * PIECE_BYTES + frag * 1024u + lane * 16u;
+                const uint32_t dst = ring_lds_addr + (p & 3) * PIECE_BYTES + frag * 1024u;
+                lds_dma_16(src, dst);
+            }
         }
     };
     // the NC candidates of this lane in tile `tile` start at:
@@ -413,7 +461,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         for (int ks = 0; ks < KS1; ++ks) {
 #pragma unroll
             for (int t = 0; t < 8; ++t) {
-                raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(p, 0);
+                raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(p);
                 p += row_bytes;
             }
             p += 8 * row_bytes;
@@ -422,34 +470,29 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
 
     Raw raw[NXLOADS];
     if (blockIdx.x < n_tiles) {
-        fetch_chunk(0);
+        fetch_piece(0);
+        fetch_piece(1);
+        fetch_piece(2);
         load_tile(blockIdx.x, raw);
     }
-    // resident part: W1 fragments and the three vectors
+    // resident part: W1 fragments, bias fragments and the two vectors
     {
-        const uint4 *src = reinterpret_cast<const uint4 *>(packed + L.w1);
+        const uint4 *src = reinterpret_cast<const uint4 *>(packed + L.w1); // w1 and its bias fragments are contiguous
         uint4 *dst = reinterpret_cast<uint4 *>(lds);
-        for (uint32_t i = tid; i < W1_BYTES / 16; i += 256) dst[i] = src[i];
-        const float *vb = reinterpret_cast<const float *>(packed + L.b1);
-        for (uint32_t i = tid; i < (uint32_t)(H1 + 2 * H2); i += 256) lds_b1[i] = vb[i]; // b1, b2, w3 are contiguous
+        for (uint32_t i = tid; i < (W1_BYTES + W1B_BYTES) / 16; i += 256) dst[i] = src[i];
+        const float *vb = reinterpret_cast<const float *>(packed + L.b2);
+        for (uint32_t i = tid; i < (uint32_t)(2 * H2); i += 256) lds_b2[i] = vb[i]; // b2 and w3 are contiguous
     }
     const float b3 = *reinterpret_cast<const float *>(packed + L.b3);
+    // the constant-one activation that multiplies the bias fragments: k slot 0 of lane half 0
+    bf16x8 x_one;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x_one[t] = (__bf16)0.0f;
+    if (h == 0) x_one[0] = (__bf16)1.0f;
+    f32x16 zero16;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) zero16[j] = 0.0f;
     __syncthreads();
-
-    auto load_bias = [&](const float *vec, int chunk, f32x16(&acc)[NC]) {
-        const f32x4 *bias = reinterpret_cast<const f32x4 *>(vec + (chunk * 2 + h) * 16);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const f32x4 b = bias[v];
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                acc[c][4 * v + 0] = b[0];
-                acc[c][4 * v + 1] = b[1];
-                acc[c][4 * v + 2] = b[2];
-                acc[c][4 * v + 3] = b[3];
-            }
-        }
-    };
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const bool more_tiles = tile + gridDim.x < n_tiles;
@@ -472,19 +515,28 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
             for (int c = 0; c < NC; ++c)
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
-                    bf16x8 v;
+                    // two floats -> one register of two bf16, then ReLU on the packed bits: a negative bf16 is
+                    // a negative 16-bit integer, so one packed integer max clamps both halves
+                    u32x4 words;
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) v[t] = (__bf16)relu(acc[c][8 * half + t]);
-                    h1[c][2 * oc + half] = park_in_acc(v);
+                    for (int d = 0; d < 4; ++d) {
+                        const f32x2 pair = {acc[c][8 * half + 2 * d], acc[c][8 * half + 2 * d + 1]};
+                        const bf16x2 cv = __builtin_convertvector(pair, bf16x2);
+                        const s16x2 clamped = __builtin_elementwise_max(__builtin_bit_cast(s16x2, cv), (s16x2)(0));
+                        words[d] = __builtin_bit_cast(uint32_t, clamped);
+                    }
+                    h1[c][2 * oc + half] = park_in_acc(__builtin_bit_cast(bf16x8, words));
                 }
         };
 #pragma unroll
         for (int oc = 0; oc < OC1; ++oc) {
             f32x16(&acc)[NC] = acc1[oc & 1];
-            load_bias(lds_b1, oc, acc);
-            bf16x8 a[KS1];
+            bf16x8 a[KS1 + 1];
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks) a[ks] = lds_w1[(oc * KS1 + ks) * 64 + lane];
+            a[KS1] = lds_w1b[oc * 64 + lane];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[KS1], x_one, zero16, 0, 0, 0);
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks)
 #pragma unroll
@@ -494,85 +546,103 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         }
         convert_chunk(OC1 - 1, acc1[(OC1 - 1) & 1]);
 
-        // ---- layer 2 + output layer, one 32-unit chunk of W2 at a time
+        // ---- layer 2 + output layer
         float y[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) y[c] = 0.0f;
         f32x16 acc2[2][NC];
+        bf16x8 a[RING]; // weight fragments in flight; fragment j of the tile's piece stream sits in a[j % RING]
 
-        // matrix work of chunk oc into acc2[oc & 1]; in between, the output-layer product of chunk oc - 1
-        auto run_chunk = [&](auto parity_tag, int oc, auto has_prev_tag, auto wait_tag) {
-            constexpr int PAR = decltype(parity_tag)::value;
-            constexpr bool has_prev = decltype(has_prev_tag)::value;
-            constexpr int wait_outstanding = decltype(wait_tag)::value;
-            // chunk `oc` has landed in its buffer (this wavefront's share: counter wait; the others': barrier),
-            // and every wavefront has finished reading the other buffer, which the next fetch overwrites
-            if (wait_outstanding == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NXLOADS) : "memory");
+        // piece p = 2 * oc + HALF of this tile: matrix work into acc2[PAR] (PAR = oc & 1); in between, the
+        // output-layer terms of chunk oc - 1 (held in acc2[PAR ^ 1]) for 8 of its 16 accumulator registers
+        auto run_piece = [&](auto par_tag, auto half_tag, auto has_prev_tag, int oc) {
+            constexpr int PAR = decltype(par_tag)::value, HALF = decltype(half_tag)::value;
+            constexpr bool HAS_PREV = decltype(has_prev_tag)::value;
+            constexpr int SLOT = 2 * PAR + HALF; // (2 * oc + HALF) & 3
+            const int p = 2 * oc + HALF;
+            // piece p+1 must have landed.  Operations issued after its fetch: the fetch of piece p+2 (if
+            // there is one) and, for p = 2 and 3, the feature loads of the next tile (issued in piece 1).
+            wait_vm<N_DMA, NXLOADS>(p + 2 < PIECES || more_tiles, p == 2 || p == 3);
             __syncthreads();
-            if (oc + 1 < OC2) fetch_chunk(oc + 1);
-            else if (more_tiles) fetch_chunk(0);
-            // the feature loads must be issued after the chunk fetch: the partial counter wait of chunk 1
-            // relies on that order
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_sched_barrier(0);
-            if (oc == 0 && more_tiles) load_tile(tile + gridDim.x, raw);
-            const bf16x8 *w2 = reinterpret_cast<const bf16x8 *>(lds_w2 + PAR * CHUNK_BYTES);
+            if (p + 3 < PIECES) fetch_piece(p + 3);
+            else if (more_tiles) fetch_piece(p + 3 - PIECES);
+            if (p == 1) {
+                // the feature loads must be issued after the piece fetch: the counter waits rely on that order
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                load_tile(more_tiles ? tile + gridDim.x : tile, raw);
+            }
+            const bf16x8 *mine = reinterpret_cast<const bf16x8 *>(lds_ring + SLOT * PIECE_BYTES);
+            const bf16x8 *next = reinterpret_cast<const bf16x8 *>(lds_ring + ((SLOT + 1) & 3) * PIECE_BYTES);
+            if (p == 0) {
+#pragma unroll
+                for (int i = 0; i < PF; ++i) a[i] = mine[i * 64 + lane];
+            }
             f32x16(&acc)[NC] = acc2[PAR];
             const f32x16(&prev)[NC] = acc2[PAR ^ 1];
-            load_bias(lds_b2, oc, acc);
-            f32x4 wprev[4];
-            if (has_prev) {
-                const f32x4 *wout = reinterpret_cast<const f32x4 *>(lds_w3 + ((oc - 1) * 2 + h) * 16);
-#pragma unroll
-                for (int v = 0; v < 4; ++v) wprev[v] = wout[v];
+            f32x4 bprev[2], wprev[2];
+            if (HAS_PREV) {
+                const f32x4 *bsrc = reinterpret_cast<const f32x4 *>(lds_b2 + ((oc - 1) * 2 + h) * 16 + 8 * HALF);
+                const f32x4 *wsrc = reinterpret_cast<const f32x4 *>(lds_w3 + ((oc - 1) * 2 + h) * 16 + 8 * HALF);
+                bprev[0] = bsrc[0];
+                bprev[1] = bsrc[1];
+                wprev[0] = wsrc[0];
+                wprev[1] = wsrc[1];
             }
-            constexpr int STEPS_PER_Q = KS2 / 16 > 0 ? KS2 / 16 : 1;
-            // weight fragments are read two k-steps ahead of their use; the scheduling fences keep the
-            // compiler from hoisting all reads to the top (which would spill the activation registers)
-            bf16x8 a[3];
-            a[0] = w2[lane];
-            a[1] = w2[64 + lane];
+            constexpr int STEPS_PER_Q = KSP / 8 > 0 ? KSP / 8 : 1;
 #pragma unroll
-            for (int ks = 0; ks < KS2; ++ks) {
-                if (ks + 2 < KS2) a[(ks + 2) % 3] = w2[(ks + 2) * 64 + lane];
+            for (int ks = 0; ks < KSP; ++ks) {
+                // read ahead, across the piece boundary if need be
+                if (PF > 0) {
+                    if (ks + PF < KSP) a[(ks + PF) % RING] = mine[(ks + PF) * 64 + lane];
+                    else a[(ks + PF) % RING] = next[(ks + PF - KSP) * 64 + lane];
+                } else {
+                    a[0] = mine[ks * 64 + lane];
+                }
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % 3], h1[c][ks], acc[c], 0, 0, 0);
-                if (has_prev && ks % STEPS_PER_Q == 0 && ks / STEPS_PER_Q < 16) {
-                    const int q = ks / STEPS_PER_Q;
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % RING], h1[c][HALF * KSP + ks],
+                                                                     (HALF == 0 && ks == 0) ? zero16 : acc[c], 0, 0, 0);
+                if (HAS_PREV && ks % STEPS_PER_Q == 0 && ks / STEPS_PER_Q < 8) {
+                    const int j = ks / STEPS_PER_Q, q = 8 * HALF + j;
 #pragma unroll
-                    for (int c = 0; c < NC; ++c) y[c] = fmaf(relu(prev[c][q]), wprev[q >> 2][q & 3], y[c]);
+                    for (int c = 0; c < NC; ++c)
+                        y[c] = fmaf(relu(prev[c][q] + bprev[j >> 2][j & 3]), wprev[j >> 2][j & 3], y[c]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (has_prev && KS2 < 16) {
+            if (HAS_PREV && KSP < 8) {
 #pragma unroll
-                for (int q = KS2; q < 16; ++q)
+                for (int j = KSP; j < 8; ++j)
 #pragma unroll
-                    for (int c = 0; c < NC; ++c) y[c] = fmaf(relu(prev[c][q]), wprev[q >> 2][q & 3], y[c]);
+                    for (int c = 0; c < NC; ++c)
+                        y[c] = fmaf(relu(prev[c][8 * HALF + j] + bprev[j >> 2][j & 3]), wprev[j >> 2][j & 3], y[c]);
             }
         };
 
         using I0 = std::integral_constant<int, 0>;
         using I1 = std::integral_constant<int, 1>;
-        run_chunk(I0{}, 0, std::false_type{}, I0{});
-        if (more_tiles) run_chunk(I1{}, 1, std::true_type{}, I1{}); // chunk 0's feature loads may stay in flight
-        else run_chunk(I1{}, 1, std::true_type{}, I0{});
-        for (int oc = 2; oc < OC2; oc += 2) {
-            run_chunk(I0{}, oc, std::true_type{}, I0{});
-            run_chunk(I1{}, oc + 1, std::true_type{}, I0{});
+        run_piece(I0{}, I0{}, std::false_type{}, 0);
+        run_piece(I0{}, I1{}, std::false_type{}, 0);
+        for (int oc = 1; oc + 1 < OC2; oc += 2) {
+            run_piece(I1{}, I0{}, std::true_type{}, oc);
+            run_piece(I1{}, I1{}, std::true_type{}, oc);
+            run_piece(I0{}, I0{}, std::true_type{}, oc + 1);
+            run_piece(I0{}, I1{}, std::true_type{}, oc + 1);
         }
+        run_piece(I1{}, I0{}, std::true_type{}, OC2 - 1);
+        run_piece(I1{}, I1{}, std::true_type{}, OC2 - 1);
         {
             const f32x16(&last)[NC] = acc2[(OC2 - 1) & 1];
-            const f32x4 *wout = reinterpret_cast<const f32x4 *>(lds_w3 + ((OC2 - 1) * 2 + h) * 16);
+            const f32x4 *bsrc = reinterpret_cast<const f32x4 *>(lds_b2 + ((OC2 - 1) * 2 + h) * 16);
+            const f32x4 *wsrc = reinterpret_cast<const f32x4 *>(lds_w3 + ((OC2 - 1) * 2 + h) * 16);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const f32x4 w = wout[v];
+                const f32x4 bb = bsrc[v], w = wsrc[v];
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) y[c] = fmaf(relu(last[c][4 * v + e]), w[e], y[c]);
+                    for (int e = 0; e < 4; ++e) y[c] = fmaf(relu(last[c][4 * v + e] + bb[e]), w[e], y[c]);
             }
         }
         const uint64_t cand = first_candidate(tile);
@@ -596,7 +666,8 @@ int32_t launch_bf16(const eck_model *m, const void *feat, int32_t feat_dtype, ui
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device);
     const uint32_t grid = n_tiles < (uint32_t)cus ? n_tiles : (uint32_t)cus;
-    const size_t lds = (size_t)F * H1 * 2 + 2 * 64 * H1 + (H1 + 2 * H2) * 4;
+    // W1 + its bias fragments, four ring slots of half a W2 chunk, b2 and w3
+    const size_t lds = (size_t)F * H1 * 2 + (H1 / 32) * 1024 + 4 * (size_t)(H1 / 32) * 1024 + 2 * H2 * 4;
     auto kern_b = score_bf16_kernel<F, H1, H2, NC, true>;
     auto kern_f = score_bf16_kernel<F, H1, H2, NC, false>;
     auto kern = feat_dtype == ECK_BF16 ? kern_b : kern_f;
