@@ -33,6 +33,7 @@ struct SpaceParams {
     uint32_t hw_num_cu, hw_wave, hw_lds_bytes, hw_max_threads_cu, hw_max_blocks_cu;
     int32_t vec_axis;          // spatial axis whose innermost level is contiguous in memory
     uint64_t true_out, true_red, flop_useful, compulsory_bytes, compulsory_in_bytes;
+    uint32_t const_q10[6];     // transformed per-space constants: features 0, 22, 60, 61, 62, 63
 };
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }

@@ -48,6 +48,21 @@ uint32_t append_factorisations(uint32_t n, std::vector<uint16_t> *out)
 
 bool pow2_leq(uint64_t v, int bits) { return v < (1ull << bits); }
 
+// floor(log2) fixed point with 10 mantissa bits, as 1024*e + m  (v >= 1)
+__host__ __device__ inline uint32_t log2_q10(uint64_t v)
+{
+    int e = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+    e = 63 - __clzll((long long)v);
+#else
+    while ((v >> e) > 1) ++e;
+#endif
+    const uint64_t frac = v ^ (1ull << e);
+    const uint32_t m = e >= 10 ? (uint32_t)(frac >> (e - 10)) : (uint32_t)(frac << (10 - e));
+    return ((uint32_t)e << 10) + m;
+}
+
+
 int32_t ensure_device_tables(eck_space *sp)
 {
     if (sp->prm.kind != ECK_SPACE_SPLIT || sp->d_tables) return ECK_OK;
@@ -140,7 +155,7 @@ extern "C" int32_t eck_space_create(const eck_problem *pb, int32_t kind, eck_spa
         out_pad *= e;
     }
     const uint64_t red_pad = (uint64_t)(p.ext[RED_AXIS] + pad_red) * p.R * p.S;
-    if (!pow2_leq(out_pad, 32) || !pow2_leq(red_pad, 24) || !pow2_leq(out_pad * red_pad, 47))
+    if (!pow2_leq(out_pad + 1, 32) || !pow2_leq(red_pad, 24) || !pow2_leq(out_pad * red_pad, 47))
         return ECK_EUNSUPPORTED;
     if (pb->op == ECK_OP_CONV2D) {
         opA_bound = (uint64_t)p.ext[0] * p.ext[4] * ((uint64_t)(p.ext[2] - 1) * p.stride + p.R) *
@@ -158,6 +173,11 @@ extern "C" int32_t eck_space_create(const eck_problem *pb, int32_t kind, eck_spa
     p.flop_useful = 2 * p.true_out * p.true_red;
     p.compulsory_in_bytes = (in_elems + w_elems) * p.elem_bytes;
     p.compulsory_bytes = (in_elems + w_elems + p.true_out) * p.elem_bytes;
+    {
+        const uint64_t constants[6] = {p.flop_useful, p.compulsory_bytes, p.elem_bytes, (uint64_t)p.op, p.true_out,
+                                       p.true_red};
+        for (int c = 0; c < 6; ++c) p.const_q10[c] = log2_q10(constants[c] + 1);
+    }
 
     eck_space *sp = new (std::nothrow) eck_space();
     if (!sp) return ECK_EDEVICE;
@@ -374,27 +394,29 @@ __device__ __forceinline__ void levels_from_knobs(const SpaceParams &p, const ui
     lv->log2_vec = g[5];
 }
 
-// floor(log2) fixed point with 10 mantissa bits, as 1024*e + m  (v >= 1)
-__device__ __forceinline__ uint32_t log2_q10(uint64_t v)
+__device__ __forceinline__ uint32_t log2_q10_u32(uint32_t v)
 {
-    const int e = 63 - __clzll((long long)v);
-    const uint64_t frac = v ^ (1ull << e);
-    const uint32_t m = e >= 10 ? (uint32_t)(frac >> (e - 10)) : (uint32_t)(frac << (10 - e));
+    const int e = 31 - __clz((int)v);
+    const uint32_t frac = v ^ (1u << e);
+    const uint32_t m = e >= 10 ? frac >> (e - 10) : frac << (10 - e);
     return ((uint32_t)e << 10) + m;
 }
 
-__device__ __forceinline__ uint16_t bf16_bits_rne(float x)
+// floor(a / b) for a < 2^53, 0 < b < 2^53 through one IEEE double division: both conversions are exact
+// and the correctly rounded quotient can exceed the true one only by rounding up across an integer, so
+// one downward correction suffices.  (A 64-bit integer division costs several times more instructions.)
+__device__ __forceinline__ uint64_t floor_div_f64(uint64_t a, uint64_t b)
 {
-    uint32_t u = __float_as_uint(x);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    uint64_t q = (uint64_t)((double)a / (double)b);
+    if (q * b > a) --q;
+    return q;
 }
 
-template <int OUT_DTYPE, bool TABLES_IN_LDS>
+template <int OUT_DTYPE, bool TABLES_IN_LDS, int N_FEAT, bool WANT_RAW>
 __global__ __launch_bounds__(256) void features_kernel(SpaceParams p, const uint16_t *__restrict__ tables,
                                                        const uint16_t *__restrict__ genes, uint64_t ld, uint64_t n,
-                                                       int n_feat, void *__restrict__ feat_out,
-                                                       uint64_t *__restrict__ raw_out, uint8_t *__restrict__ legal_out)
+                                                       void *__restrict__ feat_out, uint64_t *__restrict__ raw_out,
+                                                       uint8_t *__restrict__ legal_out)
 {
     extern __shared__ uint2 lds_tables[];
     const uint2 *tab = reinterpret_cast<const uint2 *>(tables);
@@ -480,7 +502,7 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceParams p, const uint
         fp_b = tile[1] * tile[4] * rs;
         thr_a = per_thread[0] * per_thread[2] * per_thread[3];
         thr_b = per_thread[1];
-        halo_q8 = ((uint64_t)patch << 8) / (tile[2] * tile[3]);
+        halo_q8 = floor_div_f64((uint64_t)patch << 8, tile[2] * tile[3]); // numerator < 2^40
     } else {
         fp_a = tile[0] * tile[1] * tile[4];
         fp_b = tile[0] * tile[2] * tile[4];
@@ -523,65 +545,87 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceParams p, const uint
                        vec * p.elem_bytes <= 16 && (contiguous & (vec - 1)) == 0;
     if (legal_out) legal_out[i] = legal ? 1 : 0;
 
-    auto emit = [&](int f, uint64_t raw) {
-        if (f >= n_feat) return;
+    // ---- transform and store.  Three flavours: per-space constants (transformed on the host), values
+    // known to stay below 2^32 (32-bit log2) and the rest (64-bit log2).
+    auto store_q10 = [&](int f, uint32_t q10) {
+        if (!feat_out) return;
         const uint64_t at = (uint64_t)f * ld + i;
-        if (raw_out) raw_out[at] = raw;
-        if (feat_out) {
-            const uint64_t v = raw == ~0ull ? raw : raw + 1;
-            const float x = (float)log2_q10(v) * (1.0f / 1024.0f);
-            if (OUT_DTYPE == ECK_F32) reinterpret_cast<float *>(feat_out)[at] = x;
-            else reinterpret_cast<uint16_t *>(feat_out)[at] = bf16_bits_rne(x);
-        }
+        const float x = (float)q10 * (1.0f / 1024.0f); // exact: q10 < 2^16
+        if (OUT_DTYPE == ECK_F32) reinterpret_cast<float *>(feat_out)[at] = x;
+        else reinterpret_cast<__bf16 *>(feat_out)[at] = (__bf16)x; // round to nearest even
+    };
+    auto store_raw = [&](int f, uint64_t raw) {
+        if (WANT_RAW) raw_out[(uint64_t)f * ld + i] = raw;
+    };
+    auto emit_const = [&](int f, int slot, uint64_t raw) {
+        if (f >= N_FEAT) return;
+        store_raw(f, raw);
+        store_q10(f, p.const_q10[slot]);
+    };
+    auto emit32 = [&](int f, uint32_t raw) {
+        if (f >= N_FEAT) return;
+        store_raw(f, raw);
+        store_q10(f, log2_q10_u32(raw + 1)); // raw <= 2^32 - 2 by the limits checked at space creation
+    };
+    auto emit64 = [&](int f, uint64_t raw) {
+        if (f >= N_FEAT) return;
+        store_raw(f, raw);
+        store_q10(f, log2_q10(raw == ~0ull ? raw : raw + 1));
     };
 
-    emit(0, p.flop_useful);
-    emit(1, flop_exec);
-    emit(2, (uint64_t)outs_thread * red);
-    emit(3, (uint64_t)grid_threads *
-                ((uint64_t)stages * (4ull * loads_thread_stage + 2) + 2ull * ((red + unroll - 1) >> lu)));
-    emit(4, outs_thread);
-    emit(5, (uint64_t)outs_thread + thr_a + thr_b);
-    emit(6, grid);
-    emit(7, threads);
-    emit(8, ceil_div_u32(threads, p.hw_wave));
-    emit(9, blocks_cu);
-    emit(10, active);
-    emit(11, p.hw_num_cu - active);
-    emit(12, waves + (tail != 0));
-    emit(13, tail);
-    emit(14, (uint64_t)grid_threads * stages * loads_thread_stage);
-    emit(15, ld_sectors);
-    emit(16, st_sectors);
-    emit(17, (uint64_t)grid_threads * ((outs_thread + vec - 1) >> lvv));
-    emit(18, smem_bytes);
-    emit(19, (ld_bytes + 127) >> 7);
-    emit(20, (uint64_t)grid_threads * ((uint64_t)thr_a + thr_b) * red);
-    emit(21, (flop_exec << 3) / (ld_sectors + st_sectors));
-    emit(22, p.compulsory_bytes);
-    emit(23, (ld_bytes << 8) / p.compulsory_in_bytes);
-    emit(24, stages);
-    emit(25, stage_red);
-    emit(26, inner_trip);
-    emit(27, unroll);
-    emit(28, (uint64_t)(unroll < inner_trip ? unroll : inner_trip) * outs_thread);
-    emit(29, depth);
-    emit(30, vec);
-    emit(31, vec_contig);
-    if (n_feat > 32) {
+    emit_const(0, 0, p.flop_useful);
+    emit64(1, flop_exec);
+    emit64(2, (uint64_t)outs_thread * red);
+    emit64(3, (uint64_t)grid_threads *
+                  ((uint64_t)stages * (4ull * loads_thread_stage + 2) + 2ull * ((red + unroll - 1) >> lu)));
+    emit32(4, outs_thread);
+    emit64(5, (uint64_t)outs_thread + thr_a + thr_b);
+    emit32(6, grid);
+    emit32(7, threads);
+    emit32(8, ceil_div_u32(threads, p.hw_wave));
+    emit32(9, blocks_cu);
+    emit32(10, active);
+    emit32(11, p.hw_num_cu - active);
+    emit32(12, waves + (tail != 0));
+    emit32(13, tail);
+    emit64(14, (uint64_t)grid_threads * stages * loads_thread_stage);
+    emit64(15, ld_sectors);
+    emit64(16, st_sectors);
+    emit64(17, (uint64_t)grid_threads * ((outs_thread + vec - 1) >> lvv));
+    emit64(18, smem_bytes);
+    emit64(19, (ld_bytes + 127) >> 7);
+    emit64(20, (uint64_t)grid_threads * ((uint64_t)thr_a + thr_b) * red);
+    emit64(21, floor_div_f64(flop_exec << 3, ld_sectors + st_sectors)); // numerator < 2^51
+    emit_const(22, 1, p.compulsory_bytes);
+    {
+        // (ld_bytes * 256) / c with ld_bytes < 2^50 and c < 2^34, as two exact steps
+        const uint64_t c = p.compulsory_in_bytes;
+        const uint64_t q1 = floor_div_f64(ld_bytes, c);
+        const uint64_t r1 = ld_bytes - q1 * c;
+        emit64(23, (q1 << 8) + floor_div_f64(r1 << 8, c));
+    }
+    emit32(24, stages);
+    emit32(25, stage_red);
+    emit32(26, inner_trip);
+    emit32(27, unroll);
+    emit64(28, (uint64_t)(unroll < inner_trip ? unroll : inner_trip) * outs_thread);
+    emit32(29, depth);
+    emit32(30, vec);
+    emit32(31, vec_contig);
+    if (N_FEAT > 32) {
 #pragma unroll
         for (int a = 0; a < NAX; ++a)
 #pragma unroll
-            for (int l = 0; l < 4; ++l) emit(32 + 4 * a + l, lv.f[a][l]);
+            for (int l = 0; l < 4; ++l) emit32(32 + 4 * a + l, lv.f[a][l]);
 #pragma unroll
-        for (int a = 0; a < NAX; ++a) emit(52 + a, tile[a]);
-        emit(57, fp_a);
-        emit(58, fp_b);
-        emit(59, halo_q8);
-        emit(60, p.elem_bytes);
-        emit(61, (uint64_t)p.op);
-        emit(62, p.true_out);
-        emit(63, p.true_red);
+        for (int a = 0; a < NAX; ++a) emit32(52 + a, tile[a]);
+        emit32(57, fp_a);
+        emit32(58, fp_b);
+        emit64(59, halo_q8);
+        emit_const(60, 2, p.elem_bytes);
+        emit_const(61, 3, (uint64_t)p.op);
+        emit_const(62, 4, p.true_out);
+        emit_const(63, 5, p.true_red);
     }
 }
 
@@ -607,16 +651,29 @@ extern "C" int32_t features_compute(const eck_space *space, const uint16_t *gene
     hipStream_t st = as_stream(stream);
     const bool in_lds = p.kind == ECK_SPACE_SPLIT && p.table_total <= 6144;
     const size_t lds = in_lds ? (size_t)p.table_total * 8 : 0;
-#define ECK_LAUNCH_FEATURES(DT, INLDS)                                                                       \
-    hipLaunchKernelGGL((features_kernel<DT, INLDS>), grid, block, lds, st, p, sp->d_tables, genes, ld, n,   \
-                       (int)n_feat, feat_out, raw_out, legal_out)
+    const bool raw = raw_out != nullptr;
+#define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW)                                                                    \
+    hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW>), grid, block, lds, st, p, sp->d_tables, genes, ld, n, \
+                       feat_out, raw_out, legal_out)
+#define ECK_PICK_RAW(DT, INLDS, NF)                    \
+    do {                                               \
+        if (raw) ECK_LAUNCH_FEATURES(DT, INLDS, NF, true); \
+        else ECK_LAUNCH_FEATURES(DT, INLDS, NF, false);    \
+    } while (0)
+#define ECK_PICK_NF(DT, INLDS)                          \
+    do {                                                \
+        if (n_feat == 32) ECK_PICK_RAW(DT, INLDS, 32);  \
+        else ECK_PICK_RAW(DT, INLDS, 64);               \
+    } while (0)
     if (out_dtype == ECK_F32) {
-        if (in_lds) ECK_LAUNCH_FEATURES(ECK_F32, true);
-        else ECK_LAUNCH_FEATURES(ECK_F32, false);
+        if (in_lds) ECK_PICK_NF(ECK_F32, true);
+        else ECK_PICK_NF(ECK_F32, false);
     } else {
-        if (in_lds) ECK_LAUNCH_FEATURES(ECK_BF16, true);
-        else ECK_LAUNCH_FEATURES(ECK_BF16, false);
+        if (in_lds) ECK_PICK_NF(ECK_BF16, true);
+        else ECK_PICK_NF(ECK_BF16, false);
     }
+#undef ECK_PICK_NF
+#undef ECK_PICK_RAW
 #undef ECK_LAUNCH_FEATURES
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
