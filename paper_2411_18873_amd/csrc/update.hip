@@ -5,8 +5,11 @@
 // One optimisation step is a short chain of launches of one strided tile GEMM
 // (forward, the three weight-gradient products with the bias gradient folded
 // in as an extra all-ones row, the two back-propagated deltas), a one-block
-// loss/delta kernel and an element-wise Adam kernel.  All reductions have a
-// fixed order, so a run is reproducible bit for bit.
+// loss/delta kernel and an element-wise Adam kernel.  For BF16 models the five
+// large products run on the matrix cores with bf16 operands (weights,
+// activations and back-propagated deltas rounded as they are staged) and fp32
+// accumulation; the width-1 products of the output layer stay in fp32.  All
+// reductions have a fixed order, so a run is reproducible bit for bit.
 #include <cmath>
 
 #include "eck_internal.h"
@@ -111,6 +114,104 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
         }
 }
 
+// The same product on the matrix cores for BF16 models: both operands are rounded to bf16 while they
+// are staged into LDS, accumulation is fp32 (v_mfma_f32_32x32x16_bf16).  64 x 64 output tile per block,
+// one 32 x 32 quadrant per wavefront, 64-deep stages; the next stage's operands are already in
+// flight (in registers) while the current one is multiplied.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+constexpr int MK = 64;      // stage depth
+constexpr int MLD = MK + 8; // LDS row stride in bf16: 144 bytes keeps the 16-byte fragment reads conflict-free
+
+__device__ __forceinline__ uint16_t to_bf16_bits(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t As[TM * MLD]; // [m][k]
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[TN * MLD]; // [n][k]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, c = lane & 31;
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32; // quadrant of this wavefront
+    const bool a_k_fast = g.sa_k == 1, b_k_fast = g.sb_k == 1;
+    constexpr int PER = TM * MK / 256; // elements per thread per operand per stage
+
+    float ra[PER], rb[PER];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = tid + 256 * q;
+            {
+                const int m = a_k_fast ? e / MK : e % TM, k = a_k_fast ? e % MK : e / TM;
+                const int gm = m0 + m, gk = k0 + k;
+                float v = 0.0f;
+                if (gm < g.M && gk < g.K) {
+                    if (gm == g.a_ones_row) v = 1.0f;
+                    else {
+                        const int64_t at = (int64_t)gm * g.sa_m + (int64_t)gk * g.sa_k;
+                        v = g.a_is_bf16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(g.A)[at] << 16)
+                                        : reinterpret_cast<const float *>(g.A)[at];
+                    }
+                }
+                ra[q] = v;
+            }
+            {
+                const int n = b_k_fast ? e / MK : e % TN, k = b_k_fast ? e % MK : e / TN;
+                const int gn = n0 + n, gk = k0 + k;
+                float v = 0.0f;
+                if (gn < g.N && gk < g.K) v = g.B[(int64_t)gk * g.sb_k + (int64_t)gn * g.sb_n];
+                rb[q] = v;
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = tid + 256 * q;
+            const int m = a_k_fast ? e / MK : e % TM, ka = a_k_fast ? e % MK : e / TM;
+            As[m * MLD + ka] = to_bf16_bits(ra[q]);
+            const int n = b_k_fast ? e / MK : e % TN, kb = b_k_fast ? e % MK : e / TN;
+            Bs[n * MLD + kb] = to_bf16_bits(rb[q]);
+        }
+    };
+
+    f32x16 acc;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+    fetch(0);
+    for (int k0 = 0; k0 < g.K; k0 += MK) {
+        stage();
+        __syncthreads();
+        if (k0 + MK < g.K) fetch(k0 + MK);
+#pragma unroll
+        for (int ks = 0; ks < MK / 16; ++ks) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&As[(wm + c) * MLD + 16 * ks + 8 * h]);
+            const bf16x8 b = *reinterpret_cast<const bf16x8 *>(&Bs[(wn + c) * MLD + 16 * ks + 8 * h]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // accumulator register q of lane (h, c): row 8*(q/4) + 4h + q%4, column c of the quadrant
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int m = m0 + wm + 8 * (q >> 2) + 4 * h + (q & 3), n = n0 + wn + c;
+        if (m >= g.M || n >= g.N) continue;
+        float v = acc[q];
+        if (g.bias) v += g.round_b ? through_bf16(g.bias[n]) : g.bias[n];
+        if (g.relu) v = fmaxf(v, 0.0f);
+        const int64_t at = (int64_t)m * g.ldc + n;
+        if (g.mask && !(g.mask[at] > 0.0f)) v = 0.0f;
+        if (g.round_c) v = through_bf16(v);
+        g.C[at] = v;
+    }
+}
+
 struct Scalars {
     float emax;
     uint32_t bad;
@@ -179,22 +280,6 @@ __global__ __launch_bounds__(1024) void snr_kernel(const float *__restrict__ pre
     if (threadIdx.x == 0 && !sc->bad) sc->snr = (float)(sig / noise);
 }
 
-// per-sample Eq. (1) loss, its mean, and dL/dpred = 2 (p - y) / (y * rows)   (one block)
-__global__ __launch_bounds__(1024) void loss_kernel(const float *__restrict__ pred, const float *__restrict__ y,
-                                                    int rows, float *__restrict__ dy, Scalars *sc, int is_last)
-{
-    __shared__ double scratch[1024];
-    double sum = 0.0;
-    for (int r = threadIdx.x; r < rows; r += 1024) {
-        const float p = pred[r], t = y[r];
-        const float d = p - t;
-        sum += (double)d * d / t;
-        dy[r] = 2.0f * d / (t * (float)rows);
-    }
-    sum = block_sum(sum, scratch);
-    if (threadIdx.x == 0 && is_last && !sc->bad) sc->loss = (float)(sum / rows);
-}
-
 __global__ void adam_kernel(float *__restrict__ state, const float *__restrict__ grad, uint64_t P, int step_in_call,
                             float lr, float beta1, float beta2, float eps, const Scalars *sc)
 {
@@ -219,8 +304,88 @@ __global__ void finish_kernel(float *state, uint64_t P, int n_steps, const Scala
     *loss_out = sc->loss;
 }
 
+// Output layer, forward and backward, fused and row-local: one wavefront per minibatch row computes
+//   pred = h2 . w3 + b3,  the row's Eq.-(1) loss term,  dy = 2 (pred - y) / (y * rows),
+//   d2[row][j] = dy * w3[j] where h2[row][j] > 0.
+// The dot product is a fixed-order tree (per-lane strided partial sums, then a butterfly).
+__global__ __launch_bounds__(256) void output_layer_kernel(const float *__restrict__ h2, const float *__restrict__ theta_w3,
+                                                           const float *__restrict__ theta_b3, int H2, int rows,
+                                                           const float *__restrict__ y, int round_w,
+                                                           float *__restrict__ pred, float *__restrict__ dy,
+                                                           float *__restrict__ loss_terms, float *__restrict__ d2)
+{
+    const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const float *row = h2 + (int64_t)r * H2;
+    float part = 0.0f;
+    for (int j = lane; j < H2; j += 64) {
+        const float w = round_w ? through_bf16(theta_w3[j]) : theta_w3[j];
+        part = fmaf(row[j], w, part);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off);
+    const float b3 = round_w ? through_bf16(theta_b3[0]) : theta_b3[0];
+    const float p = part + b3, t = y[r], d = p - t;
+    const float g = 2.0f * d / (t * (float)rows);
+    if (lane == 0) {
+        pred[r] = p;
+        dy[r] = g;
+        loss_terms[r] = d * d / t;
+    }
+    for (int j = lane; j < H2; j += 64) {
+        const float w = round_w ? through_bf16(theta_w3[j]) : theta_w3[j];
+        d2[(int64_t)r * H2 + j] = row[j] > 0.0f ? g * w : 0.0f;
+    }
+}
+
+// [gW3 ; gb3] = [h2 ; 1]^T dy.  A block owns 64 columns; its 16 wavefronts each sum a contiguous
+// range of rows (rows in order, loads batched eight at a time) and the 16 partial sums are added in
+// wavefront order, so the result does not depend on scheduling.  Block 0 also reduces the loss terms
+// (fixed order, double) when this is the step whose loss is reported.
+__global__ __launch_bounds__(1024) void output_grad_kernel(const float *__restrict__ h2, const float *__restrict__ dy,
+                                                           int H2, int rows, float *__restrict__ grad_w3b3,
+                                                           const float *__restrict__ loss_terms, Scalars *sc, int is_last)
+{
+    __shared__ float partial[16][64];
+    const int cg = threadIdx.x & 63, rg = threadIdx.x >> 6;
+    const int j = blockIdx.x * 64 + cg;
+    const int per = (rows + 15) / 16, r0 = rg * per, r1 = min(rows, r0 + per);
+    float acc = 0.0f;
+    if (j < H2) {
+        int r = r0;
+        for (; r + 8 <= r1; r += 8) {
+            float v[8], d[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                v[u] = h2[(int64_t)(r + u) * H2 + j];
+                d[u] = dy[r + u];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc = fmaf(v[u], d[u], acc);
+        }
+        for (; r < r1; ++r) acc = fmaf(h2[(int64_t)r * H2 + j], dy[r], acc);
+    } else if (j == H2) {
+        for (int r = r0; r < r1; ++r) acc += dy[r];
+    }
+    partial[rg][cg] = acc;
+    __syncthreads();
+    if (rg == 0 && j <= H2) {
+        float total = partial[0][cg];
+#pragma unroll
+        for (int g = 1; g < 16; ++g) total += partial[g][cg];
+        grad_w3b3[j] = total;
+    }
+    if (blockIdx.x == 0 && is_last) {
+        __shared__ double scratch[1024];
+        double sum = 0.0;
+        for (int r = threadIdx.x; r < rows; r += 1024) sum += (double)loss_terms[r];
+        sum = block_sum(sum, scratch);
+        if (threadIdx.x == 0 && !sc->bad) sc->loss = (float)(sum / rows);
+    }
+}
+
 struct UpdWs {
-    uint64_t scalars, y, pred, h1, h2, dy, d2, d1, grad, total;
+    uint64_t scalars, y, pred, h1, h2, dy, lterm, d2, d1, grad, total;
 };
 
 UpdWs upd_layout(const eck_model *m, uint64_t n_pairs, int mb)
@@ -234,6 +399,7 @@ UpdWs upd_layout(const eck_model *m, uint64_t n_pairs, int mb)
     w.h1 = o;      o = align(o + (uint64_t)mb * m->widths[1] * 4);
     w.h2 = o;      o = align(o + (uint64_t)mb * m->widths[2] * 4);
     w.dy = o;      o = align(o + (uint64_t)mb * 4);
+    w.lterm = o;   o = align(o + (uint64_t)mb * 4);
     w.d2 = o;      o = align(o + (uint64_t)mb * m->widths[2] * 4);
     w.d1 = o;      o = align(o + (uint64_t)mb * m->widths[1] * 4);
     w.grad = o;    o = align(o + m->n_params * 4);
@@ -241,9 +407,11 @@ UpdWs upd_layout(const eck_model *m, uint64_t n_pairs, int mb)
     return w;
 }
 
-void launch_gemm(const GemmArgs &g, hipStream_t st)
+void launch_gemm(const GemmArgs &g, hipStream_t st, bool matrix_cores = false)
 {
-    hipLaunchKernelGGL(gemm_kernel, dim3((g.N + TN - 1) / TN, (g.M + TM - 1) / TM), dim3(256), 0, st, g);
+    const dim3 grid((g.N + TN - 1) / TN, (g.M + TM - 1) / TM);
+    if (matrix_cores) hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, st, g);
 }
 
 } // namespace
@@ -276,6 +444,7 @@ extern "C" int32_t costmodel_update(eck_model *m, const void *feat, int32_t feat
     float *y = reinterpret_cast<float *>(base + w.y), *pred = reinterpret_cast<float *>(base + w.pred);
     float *h1 = reinterpret_cast<float *>(base + w.h1), *h2 = reinterpret_cast<float *>(base + w.h2);
     float *dy = reinterpret_cast<float *>(base + w.dy), *d2 = reinterpret_cast<float *>(base + w.d2);
+    float *lterm = reinterpret_cast<float *>(base + w.lterm);
     float *d1 = reinterpret_cast<float *>(base + w.d1), *grad = reinterpret_cast<float *>(base + w.grad);
     const int F = m->widths[0], H1 = m->widths[1], H2 = m->widths[2], B = minibatch;
     const uint64_t P = m->n_params;
@@ -297,32 +466,26 @@ extern "C" int32_t costmodel_update(eck_model *m, const void *feat, int32_t feat
         // h1 = relu(X W1 + b1)
         g = GemmArgs{x, elem == 2, 1, (int64_t)ld, -1, theta + m->off_w[0], H1, 1, h1, H1, B, H1, F,
                      theta + m->off_b[0], 1, nullptr, bf, bf, bf};
-        launch_gemm(g, st);
+        launch_gemm(g, st, bf);
         // h2 = relu(h1 W2 + b2)
         g = GemmArgs{h1, 0, H1, 1, -1, theta + m->off_w[1], H2, 1, h2, H2, B, H2, H1,
                      theta + m->off_b[1], 1, nullptr, 0, bf, 0};
-        launch_gemm(g, st);
-        // pred = h2 w3 + b3
-        g = GemmArgs{h2, 0, H2, 1, -1, theta + m->off_w[2], 1, 1, pred, 1, B, 1, H2,
-                     theta + m->off_b[2], 0, nullptr, 0, bf, 0};
-        launch_gemm(g, st);
-        hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(1024), 0, st, pred, y + row0, B, dy, sc, s == n_steps - 1);
-        // [gW3 ; gb3] = [h2 ; 1]^T dy
-        g = GemmArgs{h2, 0, 1, H2, H2, dy, 1, 1, grad + m->off_w[2], 1, H2 + 1, 1, B, nullptr, 0, nullptr, 0, 0, 0};
-        launch_gemm(g, st);
-        // d2 = (dy w3^T) where h2 > 0
-        g = GemmArgs{dy, 0, 1, 1, -1, theta + m->off_w[2], 1, 1, d2, H2, B, H2, 1, nullptr, 0, h2, 0, bf, 0};
-        launch_gemm(g, st);
+        launch_gemm(g, st, bf);
+        // output layer forward + loss + backward into d2, then its weight gradient
+        hipLaunchKernelGGL(output_layer_kernel, dim3((B + 3) / 4), dim3(256), 0, st, h2, theta + m->off_w[2],
+                           theta + m->off_b[2], H2, B, y + row0, bf, pred, dy, lterm, d2);
+        hipLaunchKernelGGL(output_grad_kernel, dim3((H2 + 1 + 63) / 64), dim3(1024), 0, st, h2, dy, H2, B,
+                           grad + m->off_w[2], lterm, sc, s == n_steps - 1);
         // [gW2 ; gb2] = [h1 ; 1]^T d2
         g = GemmArgs{h1, 0, 1, H1, H1, d2, H2, 1, grad + m->off_w[1], H2, H1 + 1, H2, B, nullptr, 0, nullptr, 0, 0, 0};
-        launch_gemm(g, st);
+        launch_gemm(g, st, bf);
         // d1 = (d2 W2^T) where h1 > 0
         g = GemmArgs{d2, 0, H2, 1, -1, theta + m->off_w[1], 1, H2, d1, H1, B, H1, H2, nullptr, 0, h1, 0, bf, 0};
-        launch_gemm(g, st);
+        launch_gemm(g, st, bf);
         // [gW1 ; gb1] = [X ; 1]^T d1
         g = GemmArgs{x, elem == 2, (int64_t)ld, 1, F, d1, H1, 1, grad + m->off_w[0], H1, F + 1, H1, B, nullptr, 0, nullptr,
                      bf, 0, 0};
-        launch_gemm(g, st);
+        launch_gemm(g, st, bf);
         hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, st, theta, grad, P, s, lr, beta1,
                            beta2, eps, sc);
     }
