@@ -71,7 +71,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=18)
-    ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update"], default=None,
+    ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update", "copy"], default=None,
                     help="profiling aid: after set-up run only this call of the step (prints a short JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -147,6 +147,7 @@ def main():
         eck.costmodel_update(m_energy, upd_feat, upd_energy, upd_steps, upd_mb, snr, loss, ws_upd, lr=1e-3)
 
     if args.only:
+        feat_copy = torch.empty_like(feat) if args.only == "copy" else None
         step(0, False)  # fills every buffer once
         torch.cuda.synchronize()
 
@@ -160,6 +161,10 @@ def main():
                     eck.features_compute(sp, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal, col0=s * per)
             elif args.only == "score":
                 eck.costmodel_score(m_energy, feat, N, energy)
+            elif args.only == "copy":
+                # plain device copy of known size (2^24 x 64 bf16 = 2 GiB read + 2 GiB written): calibrates
+                # the FETCH_SIZE / WRITE_SIZE counters
+                feat_copy.copy_(feat)
             elif args.only == "topk":
                 eck.topk_select(energy, latency, legal, S, K, idx, e_out, count, ws_topk, alpha=cfg["alpha"])
             else:
@@ -209,7 +214,11 @@ def main():
                    "candidates": N, "segments": S, "k": K},
         "roofline": {"bound": "mfma", "kernel": "score_bf16_kernel<64,512,512>", "achieved": achieved / 1e12,
                      "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_FLOPS,
-                     "ms_per_launch": score_ms, "traffic": None},
+                     "ms_per_launch": score_ms,
+                     # HBM bytes per launch from FETCH_SIZE x 2.0 + WRITE_SIZE (rocprofv3 --pmc, calibrated with a
+                     # plain copy; profiles/c5_hbm_traffic_pmc.txt); algorithmic: 2^24 x (128 B in + 4 B out)
+                     "traffic": 2.155e9 + 0.0692e9 if (F, N) == (64, 1 << 24) else None,
+                     "traffic_unit": "bytes/launch"},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_log2)
