@@ -120,9 +120,8 @@ def main():
     upd_rows, upd_mb, upd_steps = 2048, 512, 4
     upd_genes = torch.zeros((G, upd_rows), dtype=torch.int16, device=dev)
     upd_feat = torch.zeros((F, upd_rows), dtype=torch.bfloat16, device=dev)
-    for s, sp in enumerate(spaces):
-        eck.candidate_enumerate(sp, eck.MODE_SAMPLE, 32, upd_genes, seed=5000 + s, col0=32 * s)
-        eck.features_compute(sp, upd_genes, 32, F, eck.BF16, feat_out=upd_feat, col0=32 * s)
+    eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, 32, upd_genes, [5000 + s for s in range(S)])
+    eck.features_compute_batch(spaces, upd_genes, 32, F, eck.BF16, feat_out=upd_feat)
     torch.cuda.synchronize()
     upd_energy = upload(synth.measured_energy(upd_feat.float().cpu().numpy(), 13))
     ws_upd = torch.empty(eck.costmodel_update_workspace_bytes(m_energy, upd_rows, upd_mb), dtype=torch.uint8, device=dev)
@@ -131,10 +130,11 @@ def main():
 
     score_events = []
 
+    seeds = [cfg["seed_base"] + s for s in range(S)]
+
     def step(i, timed):
-        for s, sp in enumerate(spaces):
-            eck.candidate_enumerate(sp, eck.MODE_SAMPLE, per, genes, seed=cfg["seed_base"] + s, round=i, col0=s * per)
-            eck.features_compute(sp, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal, col0=s * per)
+        eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, per, genes, seeds, round=i)
+        eck.features_compute_batch(spaces, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal)
         for model, out in ((m_energy, energy), (m_latency, latency)):
             if timed:
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -153,12 +153,9 @@ def main():
 
         def one(i):
             if args.only == "enumerate":
-                for s, sp in enumerate(spaces):
-                    eck.candidate_enumerate(sp, eck.MODE_SAMPLE, per, genes, seed=cfg["seed_base"] + s, round=i,
-                                            col0=s * per)
+                eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, per, genes, seeds, round=i)
             elif args.only == "features":
-                for s, sp in enumerate(spaces):
-                    eck.features_compute(sp, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal, col0=s * per)
+                eck.features_compute_batch(spaces, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal)
             elif args.only == "score":
                 eck.costmodel_score(m_energy, feat, N, energy)
             elif args.only == "copy":

@@ -71,6 +71,7 @@ extern "C" {
 
 #define ECK_MAX_GENES 16
 #define ECK_MAX_K 4096 /* largest k topk_select accepts */
+#define ECK_MAX_BATCH 128 /* most spaces one *_batch call takes */
 
 /* The tensor operator being compiled plus the parameters of the GPU the
  * candidate kernels are meant for (they enter the occupancy features; the
@@ -111,7 +112,8 @@ int32_t eck_space_table(const eck_space *space, int32_t gene, uint32_t *out, uin
 /* -------------------------------------------------------------- candidates */
 
 /* Generate the genes of candidates first_index .. first_index+n-1
- * (Sec. 6.4: "randomly generate numerous kernels"; Alg. 1: GeneticReproduction).
+ * (Sec. 6.4: the search starts from many randomly generated kernels; Alg. 1:
+ * the reproduction step of the genetic search).
  *   EXHAUSTIVE: candidate index -> genes by mixed radix, first gene most
  *               significant; first_index+n must not exceed the space size.
  *   SAMPLE:     gene g of candidate c = (low32(u) * radix_g) >> 32 with
@@ -126,6 +128,21 @@ int32_t eck_space_table(const eck_space *space, int32_t gene, uint32_t *out, uin
 int32_t candidate_enumerate(const eck_space *space, int32_t mode, uint64_t seed, uint32_t round,
                             uint64_t first_index, uint64_t n, const uint16_t *parents, uint32_t n_parents,
                             uint32_t p_mut_q32, uint16_t *genes_out, uint64_t ld, void *stream);
+
+/* candidate_enumerate for several spaces in one launch (many operator
+ * shapes searched side by side; Sec. 7.1 lists the shapes the paper evaluates).  Space s
+ * draws from stream (seeds[s], round) and writes its n_per_space candidates to
+ * columns [s*n_per_space, (s+1)*n_per_space) of genes_out; in MUTATE its
+ * parents are columns [s*n_parents_per_space, ...) of parents, uint16
+ * [n_genes][n_spaces*n_parents_per_space].  Every space must have the same
+ * kind, operator class and number of genes (ESHAPE otherwise).
+ * spaces, seeds: host arrays of n_spaces entries, 1 <= n_spaces <=
+ * ECK_MAX_BATCH (EUNSUPPORTED above).  ld >= n_spaces*n_per_space.
+ * Other arguments and errors as candidate_enumerate. */
+int32_t candidate_enumerate_batch(const eck_space *const *spaces, uint32_t n_spaces, int32_t mode,
+                                  const uint64_t *seeds, uint32_t round, uint64_t first_index, uint64_t n_per_space,
+                                  const uint16_t *parents, uint32_t n_parents_per_space, uint32_t p_mut_q32,
+                                  uint16_t *genes_out, uint64_t ld, void *stream);
 
 /* Collect the genes of selected candidates, e.g. the survivors topk_select
  * returned, as the parents of the next generation (Alg. 1: the kernels picked
@@ -160,6 +177,14 @@ int32_t eck_candidates_gather(const uint16_t *genes, uint64_t ld, uint64_t n, in
 int32_t features_compute(const eck_space *space, const uint16_t *genes, uint64_t ld, uint64_t n,
                          int32_t n_feat, int32_t out_dtype, void *feat_out, uint64_t *raw_out,
                          uint8_t *legal_out, void *stream);
+
+/* features_compute for several spaces in one launch: columns
+ * [s*n_per_space, (s+1)*n_per_space) of genes, feat_out, raw_out and legal_out
+ * belong to spaces[s].  Same restrictions on the batch as
+ * candidate_enumerate_batch; ld >= n_spaces*n_per_space. */
+int32_t features_compute_batch(const eck_space *const *spaces, uint32_t n_spaces, const uint16_t *genes,
+                               uint64_t ld, uint64_t n_per_space, int32_t n_feat, int32_t out_dtype,
+                               void *feat_out, uint64_t *raw_out, uint8_t *legal_out, void *stream);
 
 /* ------------------------------------------------------------------ models */
 

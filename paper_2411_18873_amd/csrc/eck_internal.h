@@ -36,6 +36,9 @@ struct SpaceParams {
     uint32_t const_q10[6];     // transformed per-space constants: features 0, 22, 60, 61, 62, 63
 };
 
+// bytes before the tables in a space's device copy
+constexpr size_t kDevHeader = (sizeof(SpaceParams) + 15) & ~(size_t)15;
+
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 } // namespace eck
@@ -46,7 +49,7 @@ struct eck_space {
     std::vector<uint16_t> tables; // [table_total][4]
     uint32_t table_n[eck::NAX];
     uint64_t size;                // 0 when it overflows
-    uint16_t *d_tables = nullptr; // device copy, made on first use
+    unsigned char *d_blob = nullptr; // device copy [SpaceParams, padded to kDevHeader | tables], made on first use
     int device = -1;
 };
 

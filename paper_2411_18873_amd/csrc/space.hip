@@ -63,16 +63,20 @@ __host__ __device__ inline uint32_t log2_q10(uint64_t v)
 }
 
 
-int32_t ensure_device_tables(eck_space *sp)
+// Upload the space once: its parameters, then its factorisation tables.
+int32_t ensure_device_copy(eck_space *sp)
 {
-    if (sp->prm.kind != ECK_SPACE_SPLIT || sp->d_tables) return ECK_OK;
+    if (sp->d_blob) return ECK_OK;
     int dev = 0;
     ECK_HIP_TRY(hipGetDevice(&dev));
-    const size_t bytes = sp->tables.size() * sizeof(uint16_t);
-    ECK_HIP_TRY(hipMalloc((void **)&sp->d_tables, bytes));
-    if (hipMemcpy(sp->d_tables, sp->tables.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
-        (void)hipFree(sp->d_tables);
-        sp->d_tables = nullptr;
+    const size_t table_bytes = sp->tables.size() * sizeof(uint16_t);
+    std::vector<unsigned char> host(kDevHeader + table_bytes, 0);
+    memcpy(host.data(), &sp->prm, sizeof(SpaceParams));
+    if (table_bytes) memcpy(host.data() + kDevHeader, sp->tables.data(), table_bytes);
+    ECK_HIP_TRY(hipMalloc((void **)&sp->d_blob, host.size()));
+    if (hipMemcpy(sp->d_blob, host.data(), host.size(), hipMemcpyHostToDevice) != hipSuccess) {
+        (void)hipFree(sp->d_blob);
+        sp->d_blob = nullptr;
         return ECK_EDEVICE;
     }
     sp->device = dev;
@@ -222,9 +226,9 @@ extern "C" int32_t eck_space_create(const eck_problem *pb, int32_t kind, eck_spa
 extern "C" void eck_space_destroy(eck_space *sp)
 {
     if (!sp) return;
-    if (sp->d_tables) {
+    if (sp->d_blob) {
         (void)hipDeviceSynchronize();
-        (void)hipFree(sp->d_tables);
+        (void)hipFree(sp->d_blob);
     }
     delete sp;
 }
@@ -263,37 +267,124 @@ __device__ __forceinline__ uint64_t splitmix_finalise(uint64_t z)
 
 constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
 
+// Kernel arguments of a batch: where each space's device copy lives, and the
+// SplitMix64 state its stream starts from.  Block row y works on space y, whose
+// candidates occupy columns [y*n, (y+1)*n) of the gene / feature matrices.
+struct SpaceBatch {
+    const unsigned char *dev[ECK_MAX_BATCH];
+};
+struct StreamBatch {
+    uint64_t state[ECK_MAX_BATCH];
+};
+
 template <int MODE>
-__global__ __launch_bounds__(256) void enumerate_kernel(SpaceParams p, uint64_t stream_state, uint64_t first,
+__global__ __launch_bounds__(256) void enumerate_kernel(SpaceBatch spaces, StreamBatch streams, uint64_t first,
                                                         uint64_t n, const uint16_t *__restrict__ parents,
-                                                        uint32_t n_parents, uint32_t p_mut,
+                                                        uint32_t n_parents, uint64_t ld_parents, uint32_t p_mut,
                                                         uint16_t *__restrict__ genes, uint64_t ld)
 {
+    const uint32_t s = blockIdx.y;
+    const SpaceParams &p = *reinterpret_cast<const SpaceParams *>(spaces.dev[s]);
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const uint64_t c = first + i;
+    const uint64_t col = (uint64_t)s * n + i;
     if (MODE == ECK_MODE_EXHAUSTIVE) {
         uint64_t rest = c;
         for (int g = p.n_genes - 1; g >= 0; --g) {
             const uint64_t q = rest / p.radix[g];
-            genes[(uint64_t)g * ld + i] = (uint16_t)(rest - q * p.radix[g]);
+            genes[(uint64_t)g * ld + col] = (uint16_t)(rest - q * p.radix[g]);
             rest = q;
         }
     } else {
-        // generator state before the first gene's word: stream_state + gamma * 16c
-        uint64_t state = stream_state + kGamma * (c << 4);
-        const uint32_t parent = MODE == ECK_MODE_MUTATE ? (uint32_t)(c % n_parents) : 0;
+        // generator state before the first gene's word: stream state + gamma * 16c
+        uint64_t state = streams.state[s] + kGamma * (c << 4);
+        const uint64_t parent = MODE == ECK_MODE_MUTATE ? (uint64_t)s * n_parents + (uint32_t)(c % n_parents) : 0;
         for (int g = 0; g < p.n_genes; ++g) {
             state += kGamma;
             const uint64_t u = splitmix_finalise(state);
             uint32_t value = __umulhi((uint32_t)u, p.radix[g]);
             if (MODE == ECK_MODE_MUTATE) {
-                const uint32_t inherited = parents[(uint64_t)g * n_parents + parent];
+                const uint32_t inherited = parents[(uint64_t)g * ld_parents + parent];
                 value = ((uint32_t)(u >> 32) < p_mut) ? value : inherited;
             }
-            genes[(uint64_t)g * ld + i] = (uint16_t)value;
+            genes[(uint64_t)g * ld + col] = (uint16_t)value;
         }
     }
+}
+
+// SplitMix64 state of stream (seed, round)
+uint64_t stream_state(uint64_t seed, uint32_t round)
+{
+    uint64_t z = seed + kGamma * ((uint64_t)round + 1);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// The spaces of one launch must agree in what the kernels' template and loop bounds depend on.
+int32_t check_batch(const eck_space *const *spaces, uint32_t n_spaces)
+{
+    if (!spaces || n_spaces == 0) return ECK_EINVAL;
+    if (n_spaces > ECK_MAX_BATCH) return ECK_EUNSUPPORTED;
+    for (uint32_t s = 0; s < n_spaces; ++s) {
+        if (!spaces[s]) return ECK_EINVAL;
+        const SpaceParams &a = spaces[s]->prm, &b = spaces[0]->prm;
+        if (a.kind != b.kind || a.op != b.op || a.n_genes != b.n_genes) return ECK_ESHAPE;
+    }
+    return ECK_OK;
+}
+
+// Makes sure every space is resident on the device and fills the kernels' batch argument.
+int32_t upload_batch(const eck_space *const *spaces, uint32_t n_spaces, SpaceBatch *batch)
+{
+    for (uint32_t s = 0; s < n_spaces; ++s) {
+        eck_space *sp = const_cast<eck_space *>(spaces[s]);
+        const int32_t rc = ensure_device_copy(sp);
+        if (rc != ECK_OK) return rc;
+        batch->dev[s] = sp->d_blob;
+    }
+    return ECK_OK;
+}
+
+int32_t enumerate_launch(const eck_space *const *spaces, uint32_t n_spaces, int32_t mode, const uint64_t *seeds,
+                         uint32_t round, uint64_t first_index, uint64_t n, const uint16_t *parents,
+                         uint32_t n_parents, uint32_t p_mut_q32, uint16_t *genes_out, uint64_t ld, void *stream)
+{
+    if (!seeds || !genes_out || n == 0) return ECK_EINVAL;
+    int32_t rc = check_batch(spaces, n_spaces);
+    if (rc != ECK_OK) return rc;
+    if (mode != ECK_MODE_EXHAUSTIVE && mode != ECK_MODE_SAMPLE && mode != ECK_MODE_MUTATE) return ECK_EINVAL;
+    if (n > (1ull << 40) || first_index > UINT64_MAX - n) return ECK_EINVAL;
+    if (ld / n_spaces < n) return ECK_ESHAPE;
+    if ((ld & 1) || ((uintptr_t)genes_out & 3)) return ECK_EALIGN;
+    if (mode == ECK_MODE_MUTATE && (!parents || n_parents == 0)) return ECK_EINVAL;
+    SpaceBatch batch;
+    StreamBatch streams;
+    for (uint32_t s = 0; s < n_spaces; ++s) {
+        if (mode == ECK_MODE_EXHAUSTIVE) {
+            if (spaces[s]->size == 0) return ECK_EUNSUPPORTED;
+            if (first_index + n > spaces[s]->size) return ECK_EINVAL;
+        }
+        streams.state[s] = stream_state(seeds[s], round);
+    }
+    rc = upload_batch(spaces, n_spaces, &batch);
+    if (rc != ECK_OK) return rc;
+
+    const dim3 block(256), grid((unsigned)((n + 255) / 256), n_spaces);
+    hipStream_t st = as_stream(stream);
+    const uint64_t ld_parents = (uint64_t)n_parents * n_spaces;
+    if (mode == ECK_MODE_EXHAUSTIVE)
+        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_EXHAUSTIVE>, grid, block, 0, st, batch, streams, first_index, n,
+                           parents, n_parents, ld_parents, p_mut_q32, genes_out, ld);
+    else if (mode == ECK_MODE_SAMPLE)
+        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_SAMPLE>, grid, block, 0, st, batch, streams, first_index, n,
+                           parents, n_parents, ld_parents, p_mut_q32, genes_out, ld);
+    else
+        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_MUTATE>, grid, block, 0, st, batch, streams, first_index, n,
+                           parents, n_parents, ld_parents, p_mut_q32, genes_out, ld);
+    ECK_HIP_TRY(hipGetLastError());
+    return ECK_OK;
 }
 
 } // namespace
@@ -303,37 +394,19 @@ extern "C" int32_t candidate_enumerate(const eck_space *space, int32_t mode, uin
                                        uint32_t n_parents, uint32_t p_mut_q32, uint16_t *genes_out, uint64_t ld,
                                        void *stream)
 {
-    if (!space || !genes_out || n == 0) return ECK_EINVAL;
-    if (mode != ECK_MODE_EXHAUSTIVE && mode != ECK_MODE_SAMPLE && mode != ECK_MODE_MUTATE) return ECK_EINVAL;
-    if (ld < n) return ECK_ESHAPE;
-    if ((ld & 1) || ((uintptr_t)genes_out & 3)) return ECK_EALIGN;
-    if (n > (1ull << 40) || first_index > UINT64_MAX - n) return ECK_EINVAL;
-    if (mode == ECK_MODE_EXHAUSTIVE) {
-        if (space->size == 0) return ECK_EUNSUPPORTED;
-        if (first_index + n > space->size) return ECK_EINVAL;
-    }
-    if (mode == ECK_MODE_MUTATE && (!parents || n_parents == 0)) return ECK_EINVAL;
+    if (!space) return ECK_EINVAL;
+    return enumerate_launch(&space, 1, mode, &seed, round, first_index, n, parents, n_parents, p_mut_q32, genes_out,
+                            ld, stream);
+}
 
-    // SplitMix64 state of stream (seed, round); done once on the host
-    uint64_t z = seed + kGamma * ((uint64_t)round + 1);
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    z ^= z >> 31;
-
-    const dim3 block(256), grid((unsigned)((n + 255) / 256));
-    hipStream_t st = as_stream(stream);
-    const SpaceParams &p = space->prm;
-    if (mode == ECK_MODE_EXHAUSTIVE)
-        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_EXHAUSTIVE>, grid, block, 0, st, p, z, first_index, n, parents,
-                           n_parents, p_mut_q32, genes_out, ld);
-    else if (mode == ECK_MODE_SAMPLE)
-        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_SAMPLE>, grid, block, 0, st, p, z, first_index, n, parents,
-                           n_parents, p_mut_q32, genes_out, ld);
-    else
-        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_MUTATE>, grid, block, 0, st, p, z, first_index, n, parents,
-                           n_parents, p_mut_q32, genes_out, ld);
-    ECK_HIP_TRY(hipGetLastError());
-    return ECK_OK;
+extern "C" int32_t candidate_enumerate_batch(const eck_space *const *spaces, uint32_t n_spaces, int32_t mode,
+                                             const uint64_t *seeds, uint32_t round, uint64_t first_index,
+                                             uint64_t n_per_space, const uint16_t *parents,
+                                             uint32_t n_parents_per_space, uint32_t p_mut_q32, uint16_t *genes_out,
+                                             uint64_t ld, void *stream)
+{
+    return enumerate_launch(spaces, n_spaces, mode, seeds, round, first_index, n_per_space, parents,
+                            n_parents_per_space, p_mut_q32, genes_out, ld, stream);
 }
 
 namespace {
@@ -413,20 +486,23 @@ __device__ __forceinline__ uint64_t floor_div_f64(uint64_t a, uint64_t b)
 }
 
 template <int OUT_DTYPE, bool TABLES_IN_LDS, int N_FEAT, bool WANT_RAW>
-__global__ __launch_bounds__(256) void features_kernel(SpaceParams p, const uint16_t *__restrict__ tables,
-                                                       const uint16_t *__restrict__ genes, uint64_t ld, uint64_t n,
-                                                       void *__restrict__ feat_out, uint64_t *__restrict__ raw_out,
+__global__ __launch_bounds__(256) void features_kernel(SpaceBatch spaces, const uint16_t *__restrict__ genes,
+                                                       uint64_t ld, uint64_t n, void *__restrict__ feat_out,
+                                                       uint64_t *__restrict__ raw_out,
                                                        uint8_t *__restrict__ legal_out)
 {
     extern __shared__ uint2 lds_tables[];
-    const uint2 *tab = reinterpret_cast<const uint2 *>(tables);
+    const unsigned char *blob = spaces.dev[blockIdx.y];
+    const SpaceParams p = *reinterpret_cast<const SpaceParams *>(blob);
+    const uint2 *tab = reinterpret_cast<const uint2 *>(blob + kDevHeader);
     if (TABLES_IN_LDS) {
         for (uint32_t t = threadIdx.x; t < p.table_total; t += blockDim.x) lds_tables[t] = tab[t];
         __syncthreads();
         tab = lds_tables;
     }
-    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
+    const uint64_t in_space = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (in_space >= n) return;
+    const uint64_t i = (uint64_t)blockIdx.y * n + in_space; // column in the matrices
 
     uint32_t g[8];
 #pragma unroll
@@ -631,30 +707,35 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceParams p, const uint
 
 } // namespace
 
-extern "C" int32_t features_compute(const eck_space *space, const uint16_t *genes, uint64_t ld, uint64_t n,
-                                    int32_t n_feat, int32_t out_dtype, void *feat_out, uint64_t *raw_out,
-                                    uint8_t *legal_out, void *stream)
+namespace {
+int32_t features_launch(const eck_space *const *spaces, uint32_t n_spaces, const uint16_t *genes, uint64_t ld,
+                        uint64_t n, int32_t n_feat, int32_t out_dtype, void *feat_out, uint64_t *raw_out,
+                        uint8_t *legal_out, void *stream)
 {
-    if (!space || !genes || n == 0) return ECK_EINVAL;
+    if (!genes || n == 0) return ECK_EINVAL;
     if (!feat_out && !raw_out && !legal_out) return ECK_EINVAL;
+    int32_t rc = check_batch(spaces, n_spaces);
+    if (rc != ECK_OK) return rc;
     if (out_dtype != ECK_F32 && out_dtype != ECK_BF16) return ECK_EINVAL;
     if (n_feat != 32 && n_feat != 64) return ECK_EUNSUPPORTED;
-    if (ld < n) return ECK_ESHAPE;
-    if (ld & 1) return ECK_EALIGN;
     if (n > (1ull << 40)) return ECK_EINVAL;
-    eck_space *sp = const_cast<eck_space *>(space);
-    const int32_t rc = ensure_device_tables(sp);
+    if (ld / n_spaces < n) return ECK_ESHAPE;
+    if (ld & 1) return ECK_EALIGN;
+    SpaceBatch batch;
+    rc = upload_batch(spaces, n_spaces, &batch);
     if (rc != ECK_OK) return rc;
 
-    const SpaceParams &p = sp->prm;
-    const dim3 block(256), grid((unsigned)((n + 255) / 256));
+    // the tables go to the LDS when those of every space in the batch fit
+    uint32_t largest = 0;
+    for (uint32_t s = 0; s < n_spaces; ++s) largest = std::max(largest, spaces[s]->prm.table_total);
+    const bool in_lds = spaces[0]->prm.kind == ECK_SPACE_SPLIT && largest <= 6144;
+    const size_t lds = in_lds ? (size_t)largest * 8 : 0;
+    const dim3 block(256), grid((unsigned)((n + 255) / 256), n_spaces);
     hipStream_t st = as_stream(stream);
-    const bool in_lds = p.kind == ECK_SPACE_SPLIT && p.table_total <= 6144;
-    const size_t lds = in_lds ? (size_t)p.table_total * 8 : 0;
     const bool raw = raw_out != nullptr;
-#define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW)                                                                    \
-    hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW>), grid, block, lds, st, p, sp->d_tables, genes, ld, n, \
-                       feat_out, raw_out, legal_out)
+#define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW)                                                                \
+    hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW>), grid, block, lds, st, batch, genes, ld, n, feat_out, \
+                       raw_out, legal_out)
 #define ECK_PICK_RAW(DT, INLDS, NF)                    \
     do {                                               \
         if (raw) ECK_LAUNCH_FEATURES(DT, INLDS, NF, true); \
@@ -677,4 +758,21 @@ extern "C" int32_t features_compute(const eck_space *space, const uint16_t *gene
 #undef ECK_LAUNCH_FEATURES
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
+}
+} // namespace
+
+extern "C" int32_t features_compute(const eck_space *space, const uint16_t *genes, uint64_t ld, uint64_t n,
+                                    int32_t n_feat, int32_t out_dtype, void *feat_out, uint64_t *raw_out,
+                                    uint8_t *legal_out, void *stream)
+{
+    if (!space) return ECK_EINVAL;
+    return features_launch(&space, 1, genes, ld, n, n_feat, out_dtype, feat_out, raw_out, legal_out, stream);
+}
+
+extern "C" int32_t features_compute_batch(const eck_space *const *spaces, uint32_t n_spaces, const uint16_t *genes,
+                                          uint64_t ld, uint64_t n_per_space, int32_t n_feat, int32_t out_dtype,
+                                          void *feat_out, uint64_t *raw_out, uint8_t *legal_out, void *stream)
+{
+    return features_launch(spaces, n_spaces, genes, ld, n_per_space, n_feat, out_dtype, feat_out, raw_out, legal_out,
+                           stream);
 }

@@ -23,9 +23,11 @@ MODE_EXHAUSTIVE, MODE_SAMPLE, MODE_MUTATE = 0, 1, 2
 F32, BF16 = 0, 1
 SELECT_THRESHOLD, SELECT_RANK = 0, 1
 MAX_K = 4096
+MAX_BATCH = 128
 
 EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_info", "eck_space_table",
-           "candidate_enumerate", "eck_candidates_gather", "features_compute", "eck_model_create", "eck_model_destroy",
+           "candidate_enumerate", "candidate_enumerate_batch", "eck_candidates_gather", "features_compute",
+           "features_compute_batch", "eck_model_create", "eck_model_destroy",
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
            "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update"]
 
@@ -67,6 +69,8 @@ def lib():
         L.eck_space_info.argtypes = [vp, C.POINTER(i32), C.POINTER(u32), C.POINTER(u64)]
         L.eck_space_table.argtypes = [vp, i32, vp, u32]
         L.candidate_enumerate.argtypes = [vp, i32, u64, u32, u64, u64, vp, u32, u32, vp, u64, vp]
+        L.candidate_enumerate_batch.argtypes = [vp, u32, i32, vp, u32, u64, u64, vp, u32, u32, vp, u64, vp]
+        L.features_compute_batch.argtypes = [vp, u32, vp, u64, u64, i32, i32, vp, vp, vp, vp]
         L.eck_candidates_gather.argtypes = [vp, u64, u64, i32, vp, u32, vp, u64, vp]
         L.features_compute.argtypes = [vp, vp, u64, u64, i32, i32, vp, vp, vp, vp]
         L.eck_model_create.argtypes = [i32, C.POINTER(i32), i32, C.POINTER(vp)]
@@ -199,6 +203,50 @@ def candidate_enumerate(space, mode, n, genes_out, seed=0, round=0, first_index=
     _check("candidate_enumerate", lib().candidate_enumerate(
         space.h, mode, seed, round, first_index, n, _ptr(parents), n_par, p_mut_q32, _at(genes_out, col0),
         genes_out.shape[1], _stream()))
+
+
+def _handles(spaces):
+    return (C.c_void_p * len(spaces))(*[sp.h for sp in spaces])
+
+
+def candidate_enumerate_batch(spaces, mode, n_per_space, genes_out, seeds, round=0, first_index=0, parents=None,
+                              p_mut_q32=0):
+    """One launch for all spaces: space s writes columns [s*n_per_space, (s+1)*n_per_space) of genes_out and, in
+    MUTATE, inherits from columns [s*P, (s+1)*P) of parents (P = parents.shape[1] / len(spaces))."""
+    _dev(genes_out, genes_out.dtype, "genes_out")
+    assert genes_out.element_size() == 2 and genes_out.dim() == 2 and genes_out.shape[0] == spaces[0].n_genes
+    assert len(seeds) == len(spaces)
+    n_par = 0
+    if parents is not None:
+        _dev(parents, parents.dtype, "parents")
+        assert parents.element_size() == 2 and parents.shape[0] == spaces[0].n_genes
+        assert parents.shape[1] % len(spaces) == 0
+        n_par = parents.shape[1] // len(spaces)
+    seed_arr = (C.c_uint64 * len(seeds))(*[int(x) for x in seeds])
+    _check("candidate_enumerate_batch", lib().candidate_enumerate_batch(
+        _handles(spaces), len(spaces), mode, seed_arr, round, first_index, n_per_space, _ptr(parents), n_par,
+        p_mut_q32, _ptr(genes_out), genes_out.shape[1], _stream()))
+
+
+def features_compute_batch(spaces, genes, n_per_space, n_feat, out_dtype, feat_out=None, raw_out=None,
+                           legal_out=None):
+    """One launch for all spaces; columns [s*n_per_space, (s+1)*n_per_space) belong to spaces[s]."""
+    assert genes.element_size() == 2 and genes.is_cuda and genes.is_contiguous()
+    ld = genes.shape[1]
+    total = n_per_space * len(spaces)
+    assert total <= ld
+    for t in (feat_out, raw_out):
+        if t is not None:
+            assert t.is_cuda and t.is_contiguous() and t.shape[0] == n_feat and t.shape[1] == ld
+    if feat_out is not None:
+        assert feat_out.dtype == (torch.float32 if out_dtype == F32 else torch.bfloat16)
+    if raw_out is not None:
+        assert raw_out.element_size() == 8
+    if legal_out is not None:
+        assert legal_out.is_cuda and legal_out.element_size() == 1 and legal_out.numel() >= total
+    _check("features_compute_batch", lib().features_compute_batch(
+        _handles(spaces), len(spaces), _ptr(genes), ld, n_per_space, n_feat, out_dtype, _ptr(feat_out),
+        _ptr(raw_out), _ptr(legal_out), _stream()))
 
 
 def candidates_gather(genes, n, idx, k, out, col0=0, idx_off=0):

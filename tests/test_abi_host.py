@@ -103,6 +103,31 @@ def test_enumerate_and_features_validate_before_launch():
     assert F(sp.h, FAKE, 16, 16, 32, 5, FAKE, None, None, None) == eck.EINVAL
 
 
+def test_batched_calls_validate_before_launch():
+    L = eck.lib()
+    knob = eck.Space(synth.CONFIGS["c1"]["problem"], eck.SPACE_KNOB)
+    split = [eck.Space(synth.gemm(*s), eck.SPACE_SPLIT) for s in synth.CONFIGS["c5"]["shapes"][:3]]
+    conv = eck.Space(synth.CONFIGS["c2"]["problem"], eck.SPACE_SPLIT)
+    H = lambda *sp: (C.c_void_p * len(sp))(*[x.h if x is not None else None for x in sp])
+    seeds = (C.c_uint64 * 200)(*range(200))
+    E = L.candidate_enumerate_batch
+    assert E(None, 3, 1, seeds, 0, 0, 16, None, 0, 0, FAKE, 64, None) == eck.EINVAL
+    assert E(H(*split), 0, 1, seeds, 0, 0, 16, None, 0, 0, FAKE, 64, None) == eck.EINVAL
+    assert E(H(*split), 3, 1, None, 0, 0, 16, None, 0, 0, FAKE, 64, None) == eck.EINVAL
+    assert E(H(split[0], None, split[2]), 3, 1, seeds, 0, 0, 16, None, 0, 0, FAKE, 64, None) == eck.EINVAL
+    assert E(H(*([split[0]] * 129)), 129, 1, seeds, 0, 0, 16, None, 0, 0, FAKE, 4096, None) == eck.EUNSUPPORTED
+    assert E(H(split[0], knob), 2, 1, seeds, 0, 0, 16, None, 0, 0, FAKE, 64, None) == eck.ESHAPE   # kinds differ
+    assert E(H(split[0], conv), 2, 1, seeds, 0, 0, 16, None, 0, 0, FAKE, 64, None) == eck.ESHAPE   # operators differ
+    assert E(H(*split), 3, 1, seeds, 0, 0, 16, None, 0, 0, FAKE, 46, None) == eck.ESHAPE           # ld < 3*16
+    assert E(H(*split), 3, 2, seeds, 0, 0, 16, None, 0, 0, FAKE, 64, None) == eck.EINVAL           # no parents
+    F = L.features_compute_batch
+    assert F(None, 3, FAKE, 64, 16, 64, 1, FAKE, None, None, None) == eck.EINVAL
+    assert F(H(*split), 3, FAKE, 64, 16, 64, 1, None, None, None, None) == eck.EINVAL
+    assert F(H(split[0], conv), 2, FAKE, 64, 16, 64, 1, FAKE, None, None, None) == eck.ESHAPE
+    assert F(H(*split), 3, FAKE, 46, 16, 64, 1, FAKE, None, None, None) == eck.ESHAPE
+    assert F(H(*split), 3, FAKE, 64, 16, 48, 1, FAKE, None, None, None) == eck.EUNSUPPORTED
+
+
 def test_model_and_score_validation():
     L = eck.lib()
     W = lambda *w: (C.c_int32 * len(w))(*w)

@@ -176,9 +176,9 @@ def test_config5_sweep_full_size_as_benchmarked(G):
     genes = torch.zeros((5, N), dtype=torch.int16, device="cuda")
     feat = torch.zeros((64, N), dtype=torch.bfloat16, device="cuda")
     legal = torch.zeros(N, dtype=torch.uint8, device="cuda")
-    for s, sp in enumerate(spaces):
-        eck.candidate_enumerate(sp, eck.MODE_SAMPLE, per, genes, seed=cfg["seed_base"] + s, col0=s * per)
-        eck.features_compute(sp, genes, per, 64, eck.BF16, feat_out=feat, legal_out=legal, col0=s * per)
+    # the two batched launches bench.py times
+    eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, per, genes, [cfg["seed_base"] + s for s in range(S)])
+    eck.features_compute_batch(spaces, genes, per, 64, eck.BF16, feat_out=feat, legal_out=legal)
     thetas = [synth.mlp_theta(widths, s, bf16=True) for s in cfg["weight_seeds"]]
     energy = torch.zeros(N, dtype=torch.float32, device="cuda")
     latency = torch.zeros(N, dtype=torch.float32, device="cuda")

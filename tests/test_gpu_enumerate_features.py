@@ -148,3 +148,68 @@ def test_table5_counters_on_gpu(G, golden):
         assert (raw[6, 0], raw[7, 0], raw[15, 0], raw[19, 0]) == (grid, block, glb_ld, shared_st)
         if row[0] == "K2":
             assert raw[16, 0] == glb_st
+
+
+@pytest.mark.parametrize("mode", [eck.MODE_SAMPLE, eck.MODE_MUTATE])
+def test_batched_spaces_match_the_oracle_space_by_space(G, mode):
+    """One launch over several spaces: each space's column block equals the oracle's output for that space,
+    seed and parent block; the padding columns beyond n_spaces*n stay untouched."""
+    import torch
+    problems = [synth.gemm(*s) for s in synth.sweep_shapes()[::13]] + [synth.gemm(100, 77, 130)]
+    mine = [eck.Space(pb, eck.SPACE_SPLIT) for pb in problems]
+    refs = [oracle.Space(pb, oracle.SPACE_SPLIT) for pb in problems]
+    S, n, P = len(problems), 1537, 24      # n spans several blocks with a ragged tail; odd on purpose
+    ld = S * n + 5
+    ld += ld & 1
+    seeds = [900 + 17 * s for s in range(S)]
+    parents = None
+    if mode == eck.MODE_MUTATE:
+        parents = np.concatenate([oracle.enumerate_candidates(r, oracle.MODE_SAMPLE, P, seed=3 + s)
+                                  for s, r in enumerate(refs)], axis=1)
+    genes = torch.full((mine[0].n_genes, ld), -1, dtype=torch.int16, device="cuda")
+    eck.candidate_enumerate_batch(mine, mode, n, genes, seeds, round=2, first_index=77,
+                                  parents=None if parents is None else G.to_dev(parents),
+                                  p_mut_q32=synth.P_MUT_Q32)
+    feat = torch.zeros((64, ld), dtype=torch.bfloat16, device="cuda")
+    raw = torch.zeros((64, ld), dtype=torch.int64, device="cuda")
+    legal = torch.full((ld,), 7, dtype=torch.uint8, device="cuda")
+    eck.features_compute_batch(mine, genes, n, 64, eck.BF16, feat_out=feat, raw_out=raw, legal_out=legal)
+    torch.cuda.synchronize()
+    genes_h = genes.cpu().numpy().view(np.uint16)
+    feat_h = feat.view(torch.int16).cpu().numpy().view(np.uint16)
+    raw_h, legal_h = raw.cpu().numpy().view(np.uint64), legal.cpu().numpy()
+    for s, ref in enumerate(refs):
+        cols = slice(s * n, (s + 1) * n)
+        want = oracle.enumerate_candidates(ref, mode, n, seed=seeds[s], rnd=2, first_index=77,
+                                           parents=None if parents is None else parents[:, s * P:(s + 1) * P],
+                                           p_mut_q32=synth.P_MUT_Q32)
+        assert np.array_equal(genes_h[:, cols], want), "space %d" % s
+        padded = np.concatenate([want, want[:, :1]], axis=1)
+        raw_o, _, b16_o, legal_o = oracle.features(ref, padded, 64, n=n)
+        assert np.array_equal(raw_h[:, cols], raw_o[:, :n]), "space %d" % s
+        assert np.array_equal(feat_h[:, cols], b16_o[:, :n]), "space %d" % s
+        assert np.array_equal(legal_h[cols], legal_o), "space %d" % s
+    assert np.all(genes_h[:, S * n:] == 0xFFFF) and np.all(legal_h[S * n:] == 7) and np.all(raw_h[:, S * n:] == 0)
+
+
+def test_batched_knob_spaces_and_single_space_batch(G):
+    import torch
+    pbs = [synth.gemm(512, 512, 512), synth.gemm(384, 1000, 96)]
+    mine = [eck.Space(pb, eck.SPACE_KNOB) for pb in pbs]
+    refs = [oracle.Space(pb, oracle.SPACE_KNOB) for pb in pbs]
+    n = 700
+    genes = torch.zeros((mine[0].n_genes, 2 * n), dtype=torch.int16, device="cuda")
+    eck.candidate_enumerate_batch(mine, eck.MODE_EXHAUSTIVE, n, genes, [0, 0], first_index=1000)
+    feat = torch.zeros((32, 2 * n), dtype=torch.float32, device="cuda")
+    eck.features_compute_batch(mine, genes, n, 32, eck.F32, feat_out=feat)
+    one = torch.zeros((mine[0].n_genes, n), dtype=torch.int16, device="cuda")
+    eck.candidate_enumerate_batch(mine[1:], eck.MODE_SAMPLE, n, one, [5])
+    torch.cuda.synchronize()
+    genes_h = genes.cpu().numpy().view(np.uint16)
+    for s, ref in enumerate(refs):
+        want = oracle.enumerate_candidates(ref, oracle.MODE_EXHAUSTIVE, n, first_index=1000)
+        assert np.array_equal(genes_h[:, s * n:(s + 1) * n], want)
+        _, f32_o, _, _ = oracle.features(ref, want, 32, n=n)
+        assert np.array_equal(feat.cpu().numpy()[:, s * n:(s + 1) * n].view(np.uint32), f32_o[:, :n].view(np.uint32))
+    assert np.array_equal(one.cpu().numpy().view(np.uint16),
+                          oracle.enumerate_candidates(refs[1], oracle.MODE_SAMPLE, n, seed=5))
