@@ -467,12 +467,18 @@ __device__ __forceinline__ void levels_from_knobs(const SpaceParams &p, const ui
     lv->log2_vec = g[5];
 }
 
+// Device forms of the fixed-point log2 (v >= 1): shifting the leading one to the top bit leaves the ten
+// mantissa bits right below it whatever the exponent, so no case split on the exponent is needed.
 __device__ __forceinline__ uint32_t log2_q10_u32(uint32_t v)
 {
-    const int e = 31 - __clz((int)v);
-    const uint32_t frac = v ^ (1u << e);
-    const uint32_t m = e >= 10 ? frac >> (e - 10) : frac << (10 - e);
-    return ((uint32_t)e << 10) + m;
+    const uint32_t lz = (uint32_t)__clz((int)v);
+    return ((31u - lz) << 10) + (((v << lz) >> 21) & 1023u);
+}
+
+__device__ __forceinline__ uint32_t log2_q10_u64(uint64_t v)
+{
+    const uint32_t lz = (uint32_t)__clzll((long long)v);
+    return ((63u - lz) << 10) + ((uint32_t)((v << lz) >> 53) & 1023u);
 }
 
 // floor(a / b) for a < 2^53, 0 < b < 2^53 through one IEEE double division: both conversions are exact
@@ -500,9 +506,10 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceBatch spaces, const 
         __syncthreads();
         tab = lds_tables;
     }
-    const uint64_t in_space = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t in_space = (uint64_t)blockIdx.x * 256 + threadIdx.x; // blocks are 256 threads
     if (in_space >= n) return;
-    const uint64_t i = (uint64_t)blockIdx.y * n + in_space; // column in the matrices
+    const uint64_t block_col = (uint64_t)blockIdx.y * n + (uint64_t)blockIdx.x * 256; // wave-uniform
+    const uint64_t i = block_col + threadIdx.x;                                       // column in the matrices
 
     uint32_t g[8];
 #pragma unroll
@@ -623,15 +630,17 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceBatch spaces, const 
 
     // ---- transform and store.  Three flavours: per-space constants (transformed on the host), values
     // known to stay below 2^32 (32-bit log2) and the rest (64-bit log2).
+    // Row f of an output starts at a wave-uniform address (row base + first column of the block), so the
+    // per-lane part of every store address is the same small offset.
     auto store_q10 = [&](int f, uint32_t q10) {
         if (!feat_out) return;
-        const uint64_t at = (uint64_t)f * ld + i;
+        const uint64_t row = (uint64_t)f * ld + block_col;
         const float x = (float)q10 * (1.0f / 1024.0f); // exact: q10 < 2^16
-        if (OUT_DTYPE == ECK_F32) reinterpret_cast<float *>(feat_out)[at] = x;
-        else reinterpret_cast<__bf16 *>(feat_out)[at] = (__bf16)x; // round to nearest even
+        if (OUT_DTYPE == ECK_F32) (reinterpret_cast<float *>(feat_out) + row)[threadIdx.x] = x;
+        else (reinterpret_cast<__bf16 *>(feat_out) + row)[threadIdx.x] = (__bf16)x; // round to nearest even
     };
     auto store_raw = [&](int f, uint64_t raw) {
-        if (WANT_RAW) raw_out[(uint64_t)f * ld + i] = raw;
+        if (WANT_RAW) (raw_out + ((uint64_t)f * ld + block_col))[threadIdx.x] = raw;
     };
     auto emit_const = [&](int f, int slot, uint64_t raw) {
         if (f >= N_FEAT) return;
@@ -646,7 +655,7 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceBatch spaces, const 
     auto emit64 = [&](int f, uint64_t raw) {
         if (f >= N_FEAT) return;
         store_raw(f, raw);
-        store_q10(f, log2_q10(raw == ~0ull ? raw : raw + 1));
+        store_q10(f, log2_q10_u64(raw == ~0ull ? raw : raw + 1));
     };
 
     emit_const(0, 0, p.flop_useful);
