@@ -376,18 +376,53 @@ __device__ __forceinline__ __bf16 raw_element(const RawFeat<NC, FEAT_BF16> &r, i
     return (__bf16)__uint_as_float(r.w[c]);
 }
 
-// One direct-to-LDS load: every lane moves 16 bytes from its own global address and the load unit
-// writes them to LDS at lds_byte_address (wave-uniform, handed over in M0) + 16 * lane.  Written as
-// assembly on purpose: issued through the compiler's own intrinsic, a load of this kind in flight makes
-// the compiler drain *all* LDS reads at every dependency (it may no longer wait for just the oldest),
-// which stalls the matrix pipeline at every weight fragment.  Completion is tracked by hand instead:
-// the s_waitcnt vmcnt(...) + barrier protocol of the caller.
-__device__ __forceinline__ void lds_dma_16(const void *global_src, uint32_t lds_byte_address)
+// Ties an accumulator tile to the architectural register file.  The matrix instruction accepts its
+// accumulator in either file, ordinary vector instructions only read the architectural one: an
+// accumulator the compiler puts in the accumulation file costs one extra copy per register before the
+// ReLU / output-layer arithmetic can touch it.
+__device__ __forceinline__ void keep_in_vgprs(f32x16 &tile) { asm volatile("" : "+v"(tile)); }
+
+// N direct-to-LDS loads of 1 KB per wavefront each: in load i every lane moves 16 bytes from
+// (wave-uniform base) + lane_offset + 1024 i, and the load unit writes them to LDS at lds_byte_address
+// (wave-uniform, handed over in M0) + 1024 i + 16 * lane -- the instruction's immediate offset applies to
+// the global and to the LDS address alike.  The scalar-base form keeps all addressing of the weight
+// stream in one register per lane.  Written as assembly on purpose: issued through the compiler's own
+// intrinsic, a load of this kind in flight makes the compiler drain *all* LDS reads at every dependency
+// (it may no longer wait for just the oldest), which stalls the matrix pipeline at every weight fragment.
+// Completion is tracked by hand instead: the s_waitcnt vmcnt(...) + barrier protocol of the caller.
+template <int N>
+__device__ __forceinline__ void lds_dma_kb(const unsigned char *uniform_base, uint32_t lane_offset,
+                                           uint32_t lds_byte_address)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(__builtin_amdgcn_readfirstlane(lds_byte_address)), "v"(global_src)
-                 : "memory", "m0");
+    static_assert(N >= 1 && N <= 4, "immediate offsets of a global load end at 4095");
+    const uint64_t b = (uint64_t)uniform_base;
+    const uint64_t base = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                          (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_byte_address);
+    if (N == 1)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                     :
+                     : "s"(m0), "v"(lane_offset), "s"(base)
+                     : "memory", "m0");
+    else if (N == 2)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:1024"
+                     :
+                     : "s"(m0), "v"(lane_offset), "s"(base)
+                     : "memory", "m0");
+    else if (N == 3)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:1024\n\tglobal_load_lds_dwordx4 %1, %2 offset:2048"
+                     :
+                     : "s"(m0), "v"(lane_offset), "s"(base)
+                     : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:1024\n\tglobal_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+                     "global_load_lds_dwordx4 %1, %2 offset:3072"
+                     :
+                     : "s"(m0), "v"(lane_offset), "s"(base)
+                     : "memory", "m0");
 }
 
 // wait until only the operations issued after the fetch in question may still be outstanding:
@@ -436,16 +471,12 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
 
     // asynchronous fetch of piece p (0 <= p < PIECES, the same for every tile) into slot p & 3: every lane
     // moves 16 bytes per call, the load unit writes them to LDS at (wave-uniform base) + 16 * lane
+    const uint32_t dma_lane_offset = (uint32_t)wave * (N_DMA * 1024u) + (uint32_t)lane * 16u;
     auto fetch_piece = [&](int p) {
-#pragma unroll
-        for (int i = 0; i < N_DMA; ++i) {
-            const uint32_t frag = wave * N_DMA + i;
-            if (KSP >= 4 || frag < (uint32_t)KSP) {
-                const unsigned char *src = w2_src + (uint64_t)p * PIECE_BYTES + frag * 1024u + lane * 16u;
-                const uint32_t dst = ring_lds_addr + (p & 3) * PIECE_BYTES + frag * 1024u;
-                lds_dma_16(src, dst);
-            }
-        }
+        const unsigned char *src = w2_src + (uint64_t)p * PIECE_BYTES;                            // uniform
+        const uint32_t dst = ring_lds_addr + (p & 3) * PIECE_BYTES + (uint32_t)wave * (N_DMA * 1024u); // per wave
+        if (KSP >= 4) lds_dma_kb<N_DMA>(src, dma_lane_offset, dst);
+        else if (wave < KSP) lds_dma_kb<1>(src, dma_lane_offset, dst); // fewer fragments than wavefronts
     };
     // the NC candidates of this lane in tile `tile` start at:
     auto first_candidate = [&](uint32_t tile) { return (uint64_t)tile * TILE + (uint64_t)wave * (NC * 32) + NC * col; };
@@ -528,19 +559,26 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                     h1[c][2 * oc + half] = park_in_acc(__builtin_bit_cast(bf16x8, words));
                 }
         };
+        bf16x8 a1[2][KS1 + 1]; // weight + bias fragments of two chunks: one in use, one on its way from LDS
+        auto load_chunk = [&](int oc) {
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) a1[oc & 1][ks] = lds_w1[(oc * KS1 + ks) * 64 + lane];
+            a1[oc & 1][KS1] = lds_w1b[oc * 64 + lane];
+        };
+        load_chunk(0);
 #pragma unroll
         for (int oc = 0; oc < OC1; ++oc) {
             f32x16(&acc)[NC] = acc1[oc & 1];
-            bf16x8 a[KS1 + 1];
-#pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) a[ks] = lds_w1[(oc * KS1 + ks) * 64 + lane];
-            a[KS1] = lds_w1b[oc * 64 + lane];
+            const bf16x8(&a)[KS1 + 1] = a1[oc & 1];
+            if (oc + 1 < OC1) load_chunk(oc + 1);
 #pragma unroll
             for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[KS1], x_one, zero16, 0, 0, 0);
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks)
 #pragma unroll
                 for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], x[c][ks], acc[c], 0, 0, 0);
+#pragma unroll
+            for (int c = 0; c < NC; ++c) keep_in_vgprs(acc[c]);
             if (oc > 0) convert_chunk(oc - 1, acc1[(oc - 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -552,6 +590,10 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         for (int c = 0; c < NC; ++c) y[c] = 0.0f;
         f32x16 acc2[2][NC];
         bf16x8 a[RING]; // weight fragments in flight; fragment j of the tile's piece stream sits in a[j % RING]
+        // b2 of the chunk about to start, in accumulator-register order: the chunk's first matrix instruction
+        // takes it as its C operand, so the bias never costs a vector instruction
+        auto bias_fragment = [&](int oc) { return *reinterpret_cast<const f32x16 *>(lds_b2 + (oc * 2 + h) * 16); };
+        f32x16 bias_c = bias_fragment(0);
 
         // piece p = 2 * oc + HALF of this tile: matrix work into acc2[PAR] (PAR = oc & 1); in between, the
         // output-layer terms of chunk oc - 1 (held in acc2[PAR ^ 1]) for 8 of its 16 accumulator registers
@@ -580,16 +622,15 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
             }
             f32x16(&acc)[NC] = acc2[PAR];
             const f32x16(&prev)[NC] = acc2[PAR ^ 1];
-            f32x4 bprev[2], wprev[2];
+            f32x4 wprev[2];
             if (HAS_PREV) {
-                const f32x4 *bsrc = reinterpret_cast<const f32x4 *>(lds_b2 + ((oc - 1) * 2 + h) * 16 + 8 * HALF);
                 const f32x4 *wsrc = reinterpret_cast<const f32x4 *>(lds_w3 + ((oc - 1) * 2 + h) * 16 + 8 * HALF);
-                bprev[0] = bsrc[0];
-                bprev[1] = bsrc[1];
                 wprev[0] = wsrc[0];
                 wprev[1] = wsrc[1];
             }
-            constexpr int STEPS_PER_Q = KSP / 8 > 0 ? KSP / 8 : 1;
+            // the eight output-layer steps of a piece sit in consecutive k-steps, started late enough for the
+            // bias / weight vectors requested above to have arrived from LDS
+            constexpr int EPI_FIRST = KSP >= 16 ? (KSP - 8) / 2 : 0;
 #pragma unroll
             for (int ks = 0; ks < KSP; ++ks) {
                 // read ahead, across the piece boundary if need be
@@ -602,13 +643,22 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
                     acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % RING], h1[c][HALF * KSP + ks],
-                                                                     (HALF == 0 && ks == 0) ? zero16 : acc[c], 0, 0, 0);
-                if (HAS_PREV && ks % STEPS_PER_Q == 0 && ks / STEPS_PER_Q < 8) {
-                    const int j = ks / STEPS_PER_Q, q = 8 * HALF + j;
+                                                                     (HALF == 0 && ks == 0) ? bias_c : acc[c], 0, 0, 0);
+                if (HAS_PREV && ks >= EPI_FIRST && ks < EPI_FIRST + 8) {
+                    const int j = ks - EPI_FIRST, q = 8 * HALF + j;
 #pragma unroll
-                    for (int c = 0; c < NC; ++c)
-                        y[c] = fmaf(relu(prev[c][q] + bprev[j >> 2][j & 3]), wprev[j >> 2][j & 3], y[c]);
+                    for (int c = 0; c < NC; ++c) {
+                        y[c] = fmaf(relu(prev[c][q]), wprev[j >> 2][j & 3], y[c]);
+                        // an empty statement that "uses" the sum: without it the compiler gathers the output
+                        // terms of several chunks into one stretch of vector work that no matrix
+                        // instruction overlaps
+                        asm volatile("" : "+v"(y[c]));
+                    }
                 }
+                // the next chunk's bias, once the output-layer steps are through (its registers are free
+                // again after that chunk's first matrix instructions)
+                if (HALF == 1 && ks == (EPI_FIRST + 8 < KSP ? EPI_FIRST + 8 : KSP - 1))
+                    bias_c = bias_fragment(oc + 1 < OC2 ? oc + 1 : oc);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (HAS_PREV && KSP < 8) {
@@ -616,7 +666,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                 for (int j = KSP; j < 8; ++j)
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
-                        y[c] = fmaf(relu(prev[c][8 * HALF + j] + bprev[j >> 2][j & 3]), wprev[j >> 2][j & 3], y[c]);
+                        y[c] = fmaf(relu(prev[c][8 * HALF + j]), wprev[j >> 2][j & 3], y[c]);
             }
         };
 
@@ -634,15 +684,14 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         run_piece(I1{}, I1{}, std::true_type{}, OC2 - 1);
         {
             const f32x16(&last)[NC] = acc2[(OC2 - 1) & 1];
-            const f32x4 *bsrc = reinterpret_cast<const f32x4 *>(lds_b2 + ((OC2 - 1) * 2 + h) * 16);
             const f32x4 *wsrc = reinterpret_cast<const f32x4 *>(lds_w3 + ((OC2 - 1) * 2 + h) * 16);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const f32x4 bb = bsrc[v], w = wsrc[v];
+                const f32x4 w = wsrc[v];
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) y[c] = fmaf(relu(last[c][4 * v + e] + bb[e]), w[e], y[c]);
+                    for (int e = 0; e < 4; ++e) y[c] = fmaf(relu(last[c][4 * v + e]), w[e], y[c]);
             }
         }
         const uint64_t cand = first_candidate(tile);
