@@ -439,7 +439,7 @@ __device__ __forceinline__ void wait_vm(bool dma_after, bool x_after)
     }
 }
 
-template <int F, int H1, int H2, int NC, bool FEAT_BF16>
+template <int F, int H1, int H2, int NC, bool FEAT_BF16, bool WIDE_ROWS>
 __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__restrict__ packed, PackedLayout L,
                                                          const void *__restrict__ feat, uint64_t ld, uint64_t n,
                                                          float *__restrict__ out, uint32_t n_tiles)
@@ -481,21 +481,38 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     // the NC candidates of this lane in tile `tile` start at:
     auto first_candidate = [&](uint32_t tile) { return (uint64_t)tile * TILE + (uint64_t)wave * (NC * 32) + NC * col; };
     // request the features of one tile: rows 16*ks + 8*h + t, NC consecutive candidates each.  Lanes past
-    // the end read candidate group 0 instead (their columns are computed but never stored).
+    // the end read the tile's first candidate group instead (their columns are computed but never stored).
+    // Row addresses are wave-uniform (scalar base, one scalar add per row); the per-lane part -- half-wave
+    // row block plus position inside the tile -- is one 32-bit offset that only changes in a ragged last
+    // tile.  Matrices too large for that offset to fit (WIDE_ROWS) take per-lane 64-bit pointers.
     auto load_tile = [&](uint32_t tile, Raw(&raw)[NXLOADS]) {
-        const uint64_t cand = first_candidate(tile);
-        const uint64_t safe = cand < n ? cand : 0; // cand and ld are multiples of NC: the group is inside the row
         constexpr uint64_t ELEM = FEAT_BF16 ? 2 : 4;
         const uint64_t row_bytes = ld * ELEM;
-        const unsigned char *p = reinterpret_cast<const unsigned char *>(feat) + ((uint64_t)(8 * h) * ld + safe) * ELEM;
+        // cand and ld are multiples of NC, so a group that starts below n lies inside its row
+        const uint32_t in_tile = first_candidate(tile) < n ? (uint32_t)((wave * (NC * 32) + NC * col) * ELEM) : 0u;
+        const unsigned char *row = reinterpret_cast<const unsigned char *>(feat) + (uint64_t)tile * (TILE * ELEM);
+        if (!WIDE_ROWS) {
+            const uint32_t lane_off = (uint32_t)h * (uint32_t)(8 * row_bytes) + in_tile;
 #pragma unroll
-        for (int ks = 0; ks < KS1; ++ks) {
+            for (int ks = 0; ks < KS1; ++ks) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(p);
-                p += row_bytes;
+                for (int t = 0; t < 8; ++t) {
+                    raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(row + lane_off);
+                    row += row_bytes;
+                }
+                row += 8 * row_bytes;
             }
-            p += 8 * row_bytes;
+        } else {
+            const unsigned char *p = row + (uint64_t)h * (8 * row_bytes) + in_tile;
+#pragma unroll
+            for (int ks = 0; ks < KS1; ++ks) {
+#pragma unroll
+                for (int t = 0; t < 8; ++t) {
+                    raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(p);
+                    p += row_bytes;
+                }
+                p += 8 * row_bytes;
+            }
         }
     };
 
@@ -717,9 +734,12 @@ int32_t launch_bf16(const eck_model *m, const void *feat, int32_t feat_dtype, ui
     const uint32_t grid = n_tiles < (uint32_t)cus ? n_tiles : (uint32_t)cus;
     // W1 + its bias fragments, four ring slots of half a W2 chunk, b2 and w3
     const size_t lds = (size_t)F * H1 * 2 + (H1 / 32) * 1024 + 4 * (size_t)(H1 / 32) * 1024 + 2 * H2 * 4;
-    auto kern_b = score_bf16_kernel<F, H1, H2, NC, true>;
-    auto kern_f = score_bf16_kernel<F, H1, H2, NC, false>;
-    auto kern = feat_dtype == ECK_BF16 ? kern_b : kern_f;
+    // the per-lane part of a feature address is a 32-bit offset unless eight rows exceed it
+    const uint64_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
+    const bool wide = 8 * ld * elem > 0xFFFFFFFFull - TILE * elem;
+    auto kern = feat_dtype == ECK_BF16
+                    ? (wide ? score_bf16_kernel<F, H1, H2, NC, true, true> : score_bf16_kernel<F, H1, H2, NC, true, false>)
+                    : (wide ? score_bf16_kernel<F, H1, H2, NC, false, true> : score_bf16_kernel<F, H1, H2, NC, false, false>);
     ECK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, (const unsigned char *)m->d_packed, L, feat, ld, n, out,

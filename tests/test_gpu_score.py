@@ -101,6 +101,25 @@ def test_bf16_model_determinism_and_tail_tiles(G):
     assert np.all(out.cpu().numpy()[257:] == 123.0)
 
 
+def test_bf16_model_rows_wider_than_a_32bit_lane_offset(G):
+    """A leading dimension so large that eight feature rows span more than 4 GiB selects the kernel variant
+    with 64-bit per-lane addresses; the scores must be those of the compact matrix.  (17 GB of device memory,
+    of which only the first columns are written and read.)"""
+    widths = [32, 64, 64, 1]
+    n = 1500
+    _, b16 = _features("c1", n, 32)
+    theta = synth.mlp_theta(widths, 4, bf16=True, bias_scale=0.5)
+    model = G.make_model(widths, eck.BF16, theta)
+    compact = G.score_gpu(model, G.bf16_dev(b16), n)
+    ld = (1 << 28) + 2
+    wide = torch.empty((32, ld), dtype=torch.bfloat16, device="cuda")
+    wide[:, :n] = G.bf16_dev(b16)[:, :n]
+    got = G.score_gpu(model, wide, n)
+    del wide
+    torch.cuda.empty_cache()
+    assert np.array_equal(got, compact)
+
+
 def test_set_get_state_roundtrip(G):
     widths = [64, 256, 256, 1]
     P = synth.param_count(widths)
