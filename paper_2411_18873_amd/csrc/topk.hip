@@ -17,7 +17,7 @@ namespace {
 
 constexpr int DIGIT_BITS = 12;
 constexpr int BINS = 1 << DIGIT_BITS;
-constexpr int ITEMS = 16; // candidates per thread in the streaming kernels
+constexpr int MAX_ITEMS = 64; // most candidates per thread in the streaming kernels (a multiple of 4)
 constexpr int BLOCK = 256;
 
 enum Pred { PRED_PLAIN = 0, PRED_THRESHOLD = 1, PRED_RANK_STAGE_A = 2, PRED_RANK_STAGE_B = 3 };
@@ -30,7 +30,8 @@ struct SegState {
     uint64_t prefix;      // composite bits fixed so far (in place, low bits zero)
     uint64_t threshold;   // final: take composites <= threshold
     uint64_t lat_threshold; // RANK: composite threshold of stage A
-    uint64_t pad;
+    uint32_t arrived;       // blocks of the running histogram pass that have merged their bins
+    uint32_t pad;
 };
 
 __device__ __forceinline__ uint32_t order_key(float x)
@@ -56,6 +57,7 @@ struct SelectArgs {
     uint32_t *hist;      // [S][BINS]
     uint64_t *gather;    // [S][k]
     uint32_t k;
+    uint32_t items;      // candidates per thread in the streaming kernels (multiple of 4)
 };
 
 __device__ __forceinline__ float threshold_tau(const SelectArgs &a, const SegState &st)
@@ -63,31 +65,6 @@ __device__ __forceinline__ float threshold_tau(const SelectArgs &a, const SegSta
     if (a.alpha_inf || st.lat_min_key == 0xFFFFFFFFu) return __builtin_inff();
     const float lmin = key_to_float(st.lat_min_key);
     return __fadd_rn(lmin, __fmul_rn(a.slack_factor, fabsf(lmin)));
-}
-
-// composite of candidate i of this segment under predicate PRED, or false if infeasible
-template <int PRED>
-__device__ __forceinline__ bool composite_of(const SelectArgs &a, uint64_t seg_base, uint32_t i, float tau,
-                                             uint64_t lat_thr, uint64_t *comp)
-{
-    const uint64_t g = seg_base + i;
-    if (a.legal && !a.legal[g]) return false;
-    float value;
-    if (PRED == PRED_RANK_STAGE_A) {
-        value = a.latency[g];
-    } else {
-        value = a.energy[g];
-        if (PRED == PRED_THRESHOLD) {
-            if (!(a.latency[g] <= tau)) return false;
-        } else if (PRED == PRED_RANK_STAGE_B) {
-            const float l = a.latency[g];
-            if (l != l) return false;
-            if ((((uint64_t)order_key(l) << a.idx_bits) | i) > lat_thr) return false;
-        }
-    }
-    if (value != value) return false;
-    *comp = ((uint64_t)order_key(value) << a.idx_bits) | i;
-    return true;
 }
 
 __global__ void init_kernel(SegState *state, uint32_t n_seg, uint32_t *hist, uint32_t k)
@@ -103,6 +80,7 @@ __global__ void init_kernel(SegState *state, uint32_t n_seg, uint32_t *hist, uin
         st.prefix = 0;
         st.threshold = 0;
         st.lat_threshold = ~0ull;
+        st.arrived = 0;
         st.pad = 0;
         state[s] = st;
     }
@@ -122,21 +100,74 @@ __global__ void restart_kernel(SegState *state, uint32_t k)
     }
 }
 
+// Streaming order of the three full passes: a thread takes items / 4 groups of four consecutive candidates,
+// consecutive lanes consecutive groups (16-byte loads of the float arrays, 4-byte loads of the flags).  The
+// host launches the VEC form when segment length and pointers allow it, the scalar form otherwise.
+template <bool VEC, class Visit>
+__device__ __forceinline__ void stream_segment(const SelectArgs &a, uint64_t seg_base, bool want_energy,
+                                               bool want_latency, Visit visit)
+{
+    const uint64_t start = (uint64_t)blockIdx.x * ((uint64_t)BLOCK * a.items);
+    if (VEC) {
+#pragma unroll 4
+        for (uint32_t j = 0; j < a.items / 4; ++j) {
+            const uint64_t i = start + ((uint64_t)j * BLOCK + threadIdx.x) * 4;
+            if (i >= a.seg_len) break;
+            const uint64_t g = seg_base + i;
+            uint32_t flags = 0x01010101u;
+            if (a.legal) flags = *reinterpret_cast<const uint32_t *>(a.legal + g);
+            float4 e = {0, 0, 0, 0}, l = {0, 0, 0, 0};
+            if (flags) {
+                if (want_energy) e = *reinterpret_cast<const float4 *>(a.energy + g);
+                if (want_latency) l = *reinterpret_cast<const float4 *>(a.latency + g);
+            }
+            const float ev[4] = {e.x, e.y, e.z, e.w}, lv[4] = {l.x, l.y, l.z, l.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if ((flags >> (8 * t)) & 0xFFu) visit((uint32_t)i + t, ev[t], lv[t]);
+        }
+    } else {
+#pragma unroll 4
+        for (uint32_t j = 0; j < a.items; ++j) {
+            const uint64_t i = start + (uint64_t)j * BLOCK + threadIdx.x;
+            if (i >= a.seg_len) break;
+            const uint64_t g = seg_base + i;
+            if (a.legal && !a.legal[g]) continue;
+            visit((uint32_t)i, want_energy ? a.energy[g] : 0.0f, want_latency ? a.latency[g] : 0.0f);
+        }
+    }
+}
+
+// composite of a legal candidate with scores (e, l) under predicate PRED, or false if infeasible
+template <int PRED>
+__device__ __forceinline__ bool composite_from(const SelectArgs &a, uint32_t i, float e, float l, float tau,
+                                               uint64_t lat_thr, uint64_t *comp)
+{
+    float value;
+    if (PRED == PRED_RANK_STAGE_A) {
+        value = l;
+    } else {
+        value = e;
+        if (PRED == PRED_THRESHOLD) {
+            if (!(l <= tau)) return false;
+        } else if (PRED == PRED_RANK_STAGE_B) {
+            if (l != l) return false;
+            if ((((uint64_t)order_key(l) << a.idx_bits) | i) > lat_thr) return false;
+        }
+    }
+    if (value != value) return false;
+    *comp = ((uint64_t)order_key(value) << a.idx_bits) | i;
+    return true;
+}
+
+template <bool VEC>
 __global__ __launch_bounds__(BLOCK) void latmin_kernel(SelectArgs a)
 {
     const uint32_t s = blockIdx.y;
-    const uint64_t seg_base = (uint64_t)s * a.seg_len;
-    const uint64_t start = (uint64_t)blockIdx.x * (BLOCK * ITEMS);
     uint32_t best = 0xFFFFFFFFu;
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const uint64_t i = start + (uint64_t)j * BLOCK + threadIdx.x;
-        if (i < a.seg_len) {
-            const uint64_t g = seg_base + i;
-            const float l = a.latency[g];
-            if ((!a.legal || a.legal[g]) && l == l) best = min(best, order_key(l));
-        }
-    }
+    stream_segment<VEC>(a, (uint64_t)s * a.seg_len, false, true, [&](uint32_t, float, float l) {
+        if (l == l) best = min(best, order_key(l));
+    });
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) best = min(best, (uint32_t)__shfl_xor((int)best, off));
     __shared__ uint32_t wave_best[BLOCK / 64];
@@ -148,9 +179,13 @@ __global__ __launch_bounds__(BLOCK) void latmin_kernel(SelectArgs a)
     }
 }
 
-// histogram of the digit at `shift` (width `bits`) over feasible composites that match the prefix above it
-template <int PRED>
-__global__ __launch_bounds__(BLOCK) void hist_kernel(SelectArgs a, uint32_t shift, uint32_t bits)
+__device__ void scan_segment(const SelectArgs &a, uint32_t s, uint32_t shift, uint32_t bits, int first_pass);
+
+// histogram of the digit at `shift` (width `bits`) over feasible composites that match the prefix above
+// it.  The block that finishes a segment last (a ticket from an integer atomic, after a device-wide
+// fence) also locates the bin of the wanted rank and prepares the next pass.
+template <int PRED, bool VEC>
+__global__ __launch_bounds__(BLOCK) void hist_kernel(SelectArgs a, uint32_t shift, uint32_t bits, int first_pass)
 {
     const uint32_t s = blockIdx.y;
     const SegState st = a.state[s];
@@ -159,32 +194,38 @@ __global__ __launch_bounds__(BLOCK) void hist_kernel(SelectArgs a, uint32_t shif
     for (uint32_t b = threadIdx.x; b < BINS; b += BLOCK) bins[b] = 0;
     __syncthreads();
     const float tau = PRED == PRED_THRESHOLD ? threshold_tau(a, st) : 0.0f;
-    const uint64_t seg_base = (uint64_t)s * a.seg_len;
-    const uint64_t start = (uint64_t)blockIdx.x * (BLOCK * ITEMS);
     const uint32_t top = shift + bits; // bits at and above `top` must equal the prefix
     const uint32_t mask = (1u << bits) - 1;
-#pragma unroll 4
-    for (int j = 0; j < ITEMS; ++j) {
-        const uint64_t i = start + (uint64_t)j * BLOCK + threadIdx.x;
-        if (i >= a.seg_len) break;
+    constexpr bool NEED_E = PRED != PRED_RANK_STAGE_A, NEED_L = PRED != PRED_PLAIN;
+    stream_segment<VEC>(a, (uint64_t)s * a.seg_len, NEED_E, NEED_L, [&](uint32_t i, float e, float l) {
         uint64_t comp;
-        if (!composite_of<PRED>(a, seg_base, (uint32_t)i, tau, st.lat_threshold, &comp)) continue;
-        if (top < 64 && (comp >> top) != (st.prefix >> top)) continue;
+        if (!composite_from<PRED>(a, i, e, l, tau, st.lat_threshold, &comp)) return;
+        if (top < 64 && (comp >> top) != (st.prefix >> top)) return;
         atomicAdd(&bins[(uint32_t)(comp >> shift) & mask], 1u);
-    }
+    });
     __syncthreads();
     uint32_t *out = a.hist + (uint64_t)s * BINS;
     for (uint32_t b = threadIdx.x; b < BINS; b += BLOCK)
         if (bins[b]) atomicAdd(&out[b], bins[b]);
+    // Last block of the segment?  Every merge above is a device-scope atomic, complete (performed where
+    // all compute units see it) once this wavefront's memory counter has drained, which the barrier's
+    // release makes every wavefront do; the ticket is drawn after that, and the block that draws the last
+    // one reads the bins with device-scope atomic loads.  No cache write-back is involved, so no
+    // device-wide fence (which costs a full L2 write-back per block) is needed.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    __shared__ uint32_t ticket;
+    if (threadIdx.x == 0) ticket = atomicAdd(&a.state[s].arrived, 1u);
+    __syncthreads();
+    if (ticket != gridDim.x - 1) return;
+    scan_segment(a, s, shift, bits, first_pass);
 }
 
-// one block per segment: locate the bin that holds the remaining-th smallest, fix its digit,
-// clear the histogram for the next pass
-__global__ __launch_bounds__(BLOCK) void scan_kernel(SelectArgs a, uint32_t shift, uint32_t bits, int first_pass)
+// Run by one block per segment once the segment's histogram is complete: locate the bin that holds the
+// remaining-th smallest, fix its digit, clear the histogram and the arrival count for the next pass.
+__device__ void scan_segment(const SelectArgs &a, uint32_t s, uint32_t shift, uint32_t bits, int first_pass)
 {
-    const uint32_t s = blockIdx.x;
     SegState &st = a.state[s];
-    if (st.done) return;
     // read before any thread may update the state (updates happen after the barriers below)
     const uint32_t remaining = st.remaining;
     const uint64_t prefix_in = st.prefix;
@@ -192,28 +233,55 @@ __global__ __launch_bounds__(BLOCK) void scan_kernel(SelectArgs a, uint32_t shif
     const uint32_t nbins = 1u << bits;
     constexpr int PER = BINS / BLOCK; // consecutive bins per thread
     uint32_t local[PER], sum = 0;
+    (void)nbins; // bins at and above nbins were never incremented
+    // The other blocks' contributions were made by device-scope atomics and are complete; read them past
+    // every cache level that is not shared by the whole device, then leave zero behind for
+    // the next pass (a later kernel).
+    static_assert(PER == 16, "four 16-byte loads per thread");
+    {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 q0, q1, q2, q3;
+        const uint32_t *mine = h + threadIdx.x * PER;
+        // the compiler would wait for each cache-bypassing load separately; here all four are in flight
+        asm volatile("global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
+                     "global_load_dwordx4 %1, %4, off offset:16 sc0 sc1\n\t"
+                     "global_load_dwordx4 %2, %4, off offset:32 sc0 sc1\n\t"
+                     "global_load_dwordx4 %3, %4, off offset:48 sc0 sc1\n\t"
+                     "s_waitcnt vmcnt(0)"
+                     : "=&v"(q0), "=&v"(q1), "=&v"(q2), "=&v"(q3)
+                     : "v"(mine)
+                     : "memory");
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            local[e] = q0[e];
+            local[4 + e] = q1[e];
+            local[8 + e] = q2[e];
+            local[12 + e] = q3[e];
+        }
+    }
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
-        const uint32_t b = threadIdx.x * PER + j;
-        local[j] = b < nbins ? h[b] : 0;
-        h[b] = 0;
+        h[threadIdx.x * PER + j] = 0;
         sum += local[j];
     }
-    __shared__ uint32_t part[BLOCK];
-    part[threadIdx.x] = sum;
-    __syncthreads();
-    // exclusive prefix over threads (serial by one thread: 256 adds)
-    __shared__ uint32_t total;
-    if (threadIdx.x == 0) {
-        uint32_t run = 0;
-        for (int t = 0; t < BLOCK; ++t) {
-            const uint32_t v = part[t];
-            part[t] = run;
-            run += v;
-        }
-        total = run;
+    // exclusive prefix of the per-thread sums: shuffles inside a wavefront, then the four wavefront totals
+    uint32_t incl = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, off);
+        if ((threadIdx.x & 63) >= (uint32_t)off) incl += up;
     }
+    __shared__ uint32_t wave_total[BLOCK / 64];
+    if ((threadIdx.x & 63) == 63) wave_total[threadIdx.x >> 6] = incl;
     __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < BLOCK / 64; ++w) {
+        if (w < (int)(threadIdx.x >> 6)) before += wave_total[w];
+        total += wave_total[w];
+    }
+    const uint32_t first_below = before + incl - sum; // candidates in the bins of lower threads
+    if (threadIdx.x == 0) st.arrived = 0;
     if (first_pass && total < remaining) {
         // fewer feasible candidates than k: take them all
         if (threadIdx.x == 0) {
@@ -222,7 +290,7 @@ __global__ __launch_bounds__(BLOCK) void scan_kernel(SelectArgs a, uint32_t shif
         }
         return;
     }
-    uint32_t below = part[threadIdx.x];
+    uint32_t below = first_below;
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
         const uint32_t c = local[j];
@@ -242,24 +310,20 @@ __global__ __launch_bounds__(BLOCK) void scan_kernel(SelectArgs a, uint32_t shif
     }
 }
 
-template <int PRED>
+template <int PRED, bool VEC>
 __global__ __launch_bounds__(BLOCK) void gather_kernel(SelectArgs a)
 {
     const uint32_t s = blockIdx.y;
     const SegState st = a.state[s];
     const float tau = PRED == PRED_THRESHOLD ? threshold_tau(a, st) : 0.0f;
-    const uint64_t seg_base = (uint64_t)s * a.seg_len;
-    const uint64_t start = (uint64_t)blockIdx.x * (BLOCK * ITEMS);
-#pragma unroll 4
-    for (int j = 0; j < ITEMS; ++j) {
-        const uint64_t i = start + (uint64_t)j * BLOCK + threadIdx.x;
-        if (i >= a.seg_len) break;
+    constexpr bool NEED_E = PRED != PRED_RANK_STAGE_A, NEED_L = PRED != PRED_PLAIN;
+    stream_segment<VEC>(a, (uint64_t)s * a.seg_len, NEED_E, NEED_L, [&](uint32_t i, float e, float l) {
         uint64_t comp;
-        if (!composite_of<PRED>(a, seg_base, (uint32_t)i, tau, st.lat_threshold, &comp)) continue;
-        if (comp > st.threshold) continue;
+        if (!composite_from<PRED>(a, i, e, l, tau, st.lat_threshold, &comp)) return;
+        if (comp > st.threshold) return;
         const uint32_t slot = atomicAdd(&a.state[s].gathered, 1u);
         if (slot < a.k) a.gather[(uint64_t)s * a.k + slot] = comp; // never more than k qualify
-    }
+    });
 }
 
 // one block per segment: bitonic sort of the gathered composites, then unpack
@@ -323,20 +387,29 @@ bool sizes_ok(uint64_t n, uint32_t n_seg, uint32_t k)
 }
 
 template <int PRED>
-int32_t radix_rounds(const SelectArgs &a, uint32_t n_seg, hipStream_t st)
+int32_t radix_rounds(const SelectArgs &a, uint32_t n_seg, bool vec, hipStream_t st)
 {
     const uint32_t total_bits = 32 + a.idx_bits;
-    const uint32_t blocks = (uint32_t)((a.seg_len + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
+    const uint32_t blocks = (uint32_t)((a.seg_len + (uint64_t)BLOCK * a.items - 1) / ((uint64_t)BLOCK * a.items));
     int first = 1;
     for (uint32_t consumed = 0; consumed < total_bits; consumed += DIGIT_BITS) {
         const uint32_t bits = total_bits - consumed < DIGIT_BITS ? total_bits - consumed : DIGIT_BITS;
         const uint32_t shift = total_bits - consumed - bits;
-        hipLaunchKernelGGL(hist_kernel<PRED>, dim3(blocks, n_seg), dim3(BLOCK), 0, st, a, shift, bits);
-        hipLaunchKernelGGL(scan_kernel, dim3(n_seg), dim3(BLOCK), 0, st, a, shift, bits, first);
+        if (vec)
+            hipLaunchKernelGGL((hist_kernel<PRED, true>), dim3(blocks, n_seg), dim3(BLOCK), 0, st, a, shift, bits, first);
+        else
+            hipLaunchKernelGGL((hist_kernel<PRED, false>), dim3(blocks, n_seg), dim3(BLOCK), 0, st, a, shift, bits, first);
         first = 0;
     }
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
+}
+
+template <int PRED>
+void launch_gather(const SelectArgs &a, dim3 grid, bool vec, hipStream_t st)
+{
+    if (vec) hipLaunchKernelGGL((gather_kernel<PRED, true>), grid, dim3(BLOCK), 0, st, a);
+    else hipLaunchKernelGGL((gather_kernel<PRED, false>), grid, dim3(BLOCK), 0, st, a);
 }
 
 } // namespace
@@ -375,29 +448,43 @@ extern "C" int32_t topk_select(const float *energy, const float *latency, const 
     a.hist = reinterpret_cast<uint32_t *>((char *)ws + w.hist);
     a.gather = reinterpret_cast<uint64_t *>((char *)ws + w.gather);
     a.k = k;
+    // Work per block: every block pays for clearing and merging a 4096-bin histogram and for one ticket,
+    // so blocks are made as large as keeps about eight of them per compute unit.
+    {
+        int cus = 256;
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        const uint64_t per_thread = n / ((uint64_t)BLOCK * 8 * (uint64_t)cus);
+        a.items = 4;
+        while (a.items < MAX_ITEMS && a.items < per_thread) a.items *= 2;
+    }
 
     hipStream_t st = as_stream(stream);
-    const uint32_t blocks = (uint32_t)((a.seg_len + BLOCK * ITEMS - 1) / (BLOCK * ITEMS));
+    const uint32_t blocks = (uint32_t)((a.seg_len + (uint64_t)BLOCK * a.items - 1) / ((uint64_t)BLOCK * a.items));
     const dim3 stream_grid(blocks, n_segments);
     hipLaunchKernelGGL(init_kernel, dim3(n_segments), dim3(BLOCK), 0, st, a.state, n_segments, a.hist, k);
+    // four candidates per load when every group of four is aligned in all three arrays
+    const bool vec = a.seg_len % 4 == 0 && ((uintptr_t)energy & 15) == 0 && (!latency || ((uintptr_t)latency & 15) == 0) &&
+                     (!legal || ((uintptr_t)legal & 3) == 0);
     int32_t rc = ECK_OK;
     if (!latency) {
-        rc = radix_rounds<PRED_PLAIN>(a, n_segments, st);
-        if (rc == ECK_OK) hipLaunchKernelGGL(gather_kernel<PRED_PLAIN>, stream_grid, dim3(BLOCK), 0, st, a);
+        rc = radix_rounds<PRED_PLAIN>(a, n_segments, vec, st);
+        if (rc == ECK_OK) launch_gather<PRED_PLAIN>(a, stream_grid, vec, st);
     } else if (mode == ECK_SELECT_THRESHOLD) {
-        hipLaunchKernelGGL(latmin_kernel, stream_grid, dim3(BLOCK), 0, st, a);
-        rc = radix_rounds<PRED_THRESHOLD>(a, n_segments, st);
-        if (rc == ECK_OK) hipLaunchKernelGGL(gather_kernel<PRED_THRESHOLD>, stream_grid, dim3(BLOCK), 0, st, a);
+        if (vec) hipLaunchKernelGGL(latmin_kernel<true>, stream_grid, dim3(BLOCK), 0, st, a);
+        else hipLaunchKernelGGL(latmin_kernel<false>, stream_grid, dim3(BLOCK), 0, st, a);
+        rc = radix_rounds<PRED_THRESHOLD>(a, n_segments, vec, st);
+        if (rc == ECK_OK) launch_gather<PRED_THRESHOLD>(a, stream_grid, vec, st);
     } else {
         SelectArgs stage_a = a;
         stage_a.k = m_latency;
         hipLaunchKernelGGL(restart_kernel, dim3(n_segments), dim3(64), 0, st, a.state, m_latency);
-        rc = radix_rounds<PRED_RANK_STAGE_A>(stage_a, n_segments, st);
+        rc = radix_rounds<PRED_RANK_STAGE_A>(stage_a, n_segments, vec, st);
         if (rc == ECK_OK) {
             hipLaunchKernelGGL(restart_kernel, dim3(n_segments), dim3(64), 0, st, a.state, k);
-            rc = radix_rounds<PRED_RANK_STAGE_B>(a, n_segments, st);
+            rc = radix_rounds<PRED_RANK_STAGE_B>(a, n_segments, vec, st);
         }
-        if (rc == ECK_OK) hipLaunchKernelGGL(gather_kernel<PRED_RANK_STAGE_B>, stream_grid, dim3(BLOCK), 0, st, a);
+        if (rc == ECK_OK) launch_gather<PRED_RANK_STAGE_B>(a, stream_grid, vec, st);
     }
     if (rc != ECK_OK) return rc;
     const uint32_t pow2 = next_pow2(k < 2 ? 2 : k);
