@@ -242,3 +242,38 @@ def update(widths, state64, feat_f32, e_meas, n_steps, minibatch, lr=1e-3, beta1
 
 def k_step(k, snr, mu, M):
     return lib().orc_k_step(k, snr, mu, M)
+
+
+def trees_predict(n_feat, depth, node_feat, node_thr, leaf, base, feat_f32, n=None, fp32_sequential=False):
+    """node_feat uint8 [T][2^d-1], node_thr float32 [T][2^d-1], leaf float32 [T][2^d]; returns float64 [n]."""
+    node_feat = np.ascontiguousarray(node_feat, dtype=np.uint8)
+    node_thr = np.ascontiguousarray(node_thr, dtype=np.float32)
+    leaf = np.ascontiguousarray(leaf, dtype=np.float32)
+    T = leaf.shape[0] if leaf.ndim == 2 else leaf.size >> depth
+    feat = np.ascontiguousarray(feat_f32, dtype=np.float32)
+    n = feat.shape[1] if n is None else n
+    out = np.zeros(n, dtype=np.float64)
+    rc = lib().orc_trees_predict(C.c_int32(n_feat), C.c_int32(depth), C.c_int32(T), _p(node_feat), _p(node_thr),
+                                 _p(leaf), C.c_double(base), _p(feat), C.c_uint64(feat.shape[1]), C.c_uint64(n),
+                                 C.c_int32(1 if fp32_sequential else 0), _p(out))
+    if rc:
+        raise ValueError("oracle trees_predict: rc=%d" % rc)
+    return out
+
+
+def trees_boost(n_feat, depth, node_feat, node_thr, leaf, n_trees_in, n_rounds, base, feat_f32, e_meas, eta=0.3,
+                lam=1.0):
+    """Appends n_rounds trees in place (arrays hold at least n_trees_in + n_rounds trees).  Returns (snr, loss)."""
+    for a, dt in ((node_feat, np.uint8), (node_thr, np.float32), (leaf, np.float32)):
+        assert a.dtype == dt and a.flags.c_contiguous
+    assert leaf.size >> depth >= n_trees_in + n_rounds
+    feat = np.ascontiguousarray(feat_f32, dtype=np.float32)
+    e_meas = np.ascontiguousarray(e_meas, dtype=np.float32)
+    snr, ls = C.c_double(), C.c_double()
+    rc = lib().orc_trees_boost(C.c_int32(n_feat), C.c_int32(depth), C.c_int32(n_trees_in), C.c_int32(n_rounds),
+                               _p(node_feat), _p(node_thr), _p(leaf), C.c_double(base), _p(feat),
+                               C.c_uint64(feat.shape[1]), _p(e_meas), C.c_uint64(e_meas.size), C.c_double(eta),
+                               C.c_double(lam), C.byref(snr), C.byref(ls))
+    if rc:
+        raise ValueError("oracle trees_boost: rc=%d" % rc)
+    return snr.value, ls.value

@@ -25,11 +25,19 @@
  *   orc_update     -- ModelUpdate + SNR of Alg. 1 with the weighted squared
  *                     error of Eq. (1), minimised by Adam.
  *   orc_k_step     -- the k controller of Alg. 1 (the If/Else on mu).
+ *   orc_trees_predict, orc_trees_boost -- the model form the paper itself
+ *                     uses (Sec. 5.4 "Approach"): an ensemble of regression
+ *                     trees built one after another by gradient boosting on
+ *                     the weighted squared error of Eq. (1); the prediction is
+ *                     the sum of the trees' outputs.
  *
  * Pins (tests/test_oracle_*.py): Table 5 counters (grid, block, glb_ld,
  * shared_st, glb_st of K2), closed-form FLOP/byte counts, table sizes by the
  * stars-and-bars formula, brute-force top-k, Eq. (1) gradient by finite
- * differences, hand-computed first Adam step, scripted k trajectories.
+ * differences, hand-computed first Adam step, scripted k trajectories; trees:
+ * a hand-worked ensemble, the closed-form weighted means of a one-split fit,
+ * brute-force search of the best split, a library regression tree on the same
+ * weighted problem, monotone training loss.
  * parity unpinned: feature 20 (shared-load element count) -- Table 5's
  * shared_ld column is not reproduced by any simple register-tile formula; and
  * the 100-step bf16 update trajectory (checked statistically only).
@@ -857,4 +865,196 @@ double orc_k_step(double k, double snr, double mu, int64_t M)
     if (measured == 0) return k;
     if (snr < mu) return fmin(1.0, k + 0.2);
     return fmax(0.0, k - 0.2);
+}
+
+/* ---------------------------------------------------------- tree ensemble */
+
+/* Sec. 5.4: the cost model as a sum of regression trees.  Every tree is a
+ * complete binary tree of depth d stored level by level: node j has children
+ * 2j+1 (taken when x[feat_j] < thr_j) and 2j+2 (otherwise, also for NaN);
+ * after d comparisons the walk stands on node (2^d - 1) + leaf.  A node that
+ * must not split carries thr = +inf (everything goes left).
+ *   node_feat [n_trees][2^d - 1] uint8, node_thr [n_trees][2^d - 1] float,
+ *   leaf [n_trees][2^d] float, feat [n_feat][ld] float.
+ * prediction = base + sum over trees of the leaf reached, in fp64; with
+ * fp32_sequential != 0 the sum runs in fp32, base first, trees in order (the
+ * arithmetic the boosting iteration itself is defined with, see below). */
+static uint32_t tree_leaf_of(int32_t depth, const uint8_t *nf, const float *nt, const float *feat, uint64_t ld,
+                             uint64_t c)
+{
+    uint32_t j = 0;
+    for (int32_t l = 0; l < depth; ++l) {
+        const float x = feat[(uint64_t)nf[j] * ld + c];
+        j = 2 * j + ((x < nt[j]) ? 1u : 2u);
+    }
+    return j - ((1u << depth) - 1u);
+}
+
+int32_t orc_trees_predict(int32_t n_feat, int32_t depth, int32_t n_trees, const uint8_t *node_feat,
+                          const float *node_thr, const float *leaf, double base, const float *feat, uint64_t ld,
+                          uint64_t n, int32_t fp32_sequential, double *out)
+{
+    if (n_feat < 1 || n_feat > 256 || depth < 1 || depth > 8 || n_trees < 0 || ld < n) return ORC_EINVAL;
+    const uint32_t nodes = (1u << depth) - 1u, leaves = 1u << depth;
+    for (int64_t t = 0; t < (int64_t)n_trees * nodes; ++t)
+        if (node_feat[t] >= n_feat) return ORC_EINVAL;
+    for (uint64_t c = 0; c < n; ++c) {
+        double acc = base;
+        float acc32 = (float)base;
+        for (int32_t t = 0; t < n_trees; ++t) {
+            const uint32_t lf = tree_leaf_of(depth, node_feat + (uint64_t)t * nodes, node_thr + (uint64_t)t * nodes,
+                                             feat, ld, c);
+            const float w = leaf[(uint64_t)t * leaves + lf];
+            acc += (double)w;
+            acc32 = acc32 + w;
+        }
+        out[c] = fp32_sequential ? (double)acc32 : acc;
+    }
+    return ORC_OK;
+}
+
+/* Feature value -> histogram bin: 256 bins of width 1/4 on [0, 64) (the
+ * transformed features lie there); values outside are clamped, NaN falls in
+ * the last bin.  "bin(x) <= b" is the same set as "x < (b + 1) / 4" for every
+ * b < 255, which is the comparison the trees store. */
+static int tree_bin(float x)
+{
+    if (!(x >= 0.0f)) return x != x ? 255 : 0;
+    const float s = x * 4.0f;
+    return s >= 255.0f ? 255 : (int)s;
+}
+
+#define ORC_TREE_FIX 1048576.0 /* 2^20: gradient statistics are summed as integers of this resolution */
+
+static int64_t tree_quantise(double v)
+{
+    const double lim = 1048576.0; /* |g|, h are clamped to 2^20 so that 2^20 samples cannot overflow 63 bits */
+    if (v > lim) v = lim;
+    if (v < -lim) v = -lim;
+    return (int64_t)llrint(v * ORC_TREE_FIX);
+}
+
+/* Gradient boosting with the loss of Eq. (1) (Sec. 5.4: the weighted squared
+ * error is the training loss of the boosted trees; Alg. 1 ModelUpdate).
+ * Appends n_rounds trees to an ensemble of n_trees_in trees.
+ *
+ *   labels        y_i = fl32(E_i / max E), the normalised energy (Sec. 5.4)
+ *   prediction    p_i in fp32: base, then + leaf of tree 0, 1, ... in order
+ *   per round     g_i = 2 (p_i - y_i) / y_i,  h_i = 2 / y_i   (first and second
+ *                 derivative of Eq. (1) in the prediction), in fp64, then
+ *                 rounded to integers of resolution 2^-20 (clamped to 2^20):
+ *                 all sums below are exact integer sums, so they do not
+ *                 depend on the order of summation
+ *   growth        level by level to depth d.  For a node with statistics
+ *                 (G, H) and every split "feature f, bins <= b left":
+ *                   gain = GL^2/(HL+lam) + GR^2/(HR+lam) - G^2/(H+lam)
+ *                 (the second-order gain of tree boosting, Chen & Guestrin
+ *                 2016, Eq. 7 without the constant factor and the complexity
+ *                 term), evaluated in fp64 on the integer sums with lam =
+ *                 lambda * 2^20; both sides must hold at least one sample.
+ *                 The split of largest gain > 0 wins, ties to the lower
+ *                 feature, then the lower bin; no such split: thr = +inf.
+ *   leaves        w = -eta * G / (H + lam) in fp64, stored as fp32; empty: 0
+ *   then          p_i <- p_i + w(leaf of i)  in fp32
+ *
+ * snr_out: sum y^2 / sum (p - y)^2 of the ensemble as it is on entry;
+ * loss_out: mean of Eq. (1) over the pairs after the last round (fp64).
+ * Any E <= 0 or non-finite: snr = loss = NaN, nothing appended. */
+int32_t orc_trees_boost(int32_t n_feat, int32_t depth, int32_t n_trees_in, int32_t n_rounds, uint8_t *node_feat,
+                        float *node_thr, float *leaf, double base, const float *feat, uint64_t ld,
+                        const float *e_meas, uint64_t n_pairs, double eta, double lambda, double *snr_out,
+                        double *loss_out)
+{
+    if (n_feat < 1 || n_feat > 256 || depth < 1 || depth > 8 || n_trees_in < 0 || n_rounds < 0 || n_pairs == 0 ||
+        n_pairs > (1u << 20) || ld < n_pairs || !(eta > 0.0) || !(lambda >= 0.0))
+        return ORC_EINVAL;
+    const uint32_t nodes = (1u << depth) - 1u, leaves = 1u << depth;
+    float emax = 0.0f;
+    int bad = 0;
+    for (uint64_t i = 0; i < n_pairs; ++i) {
+        if (!(e_meas[i] > 0.0f) || isinf(e_meas[i])) bad = 1;
+        if (e_meas[i] > emax) emax = e_meas[i];
+    }
+    if (bad) { *snr_out = NAN; *loss_out = NAN; return ORC_OK; }
+
+    float *y = (float *)malloc(n_pairs * sizeof(float));
+    float *p = (float *)malloc(n_pairs * sizeof(float));
+    int64_t *gq = (int64_t *)malloc(n_pairs * sizeof(int64_t));
+    int64_t *hq = (int64_t *)malloc(n_pairs * sizeof(int64_t));
+    uint32_t *at = (uint32_t *)malloc(n_pairs * sizeof(uint32_t));
+    for (uint64_t i = 0; i < n_pairs; ++i) y[i] = e_meas[i] / emax;
+    {
+        double *tmp = (double *)malloc(n_pairs * sizeof(double));
+        orc_trees_predict(n_feat, depth, n_trees_in, node_feat, node_thr, leaf, base, feat, ld, n_pairs, 1, tmp);
+        double sig = 0.0, noise = 0.0;
+        for (uint64_t i = 0; i < n_pairs; ++i) {
+            p[i] = (float)tmp[i];
+            sig += (double)y[i] * (double)y[i];
+            noise += ((double)p[i] - (double)y[i]) * ((double)p[i] - (double)y[i]);
+        }
+        *snr_out = sig / noise;
+        free(tmp);
+    }
+
+    const double lam = lambda * ORC_TREE_FIX;
+    int64_t *hg = (int64_t *)malloc((size_t)n_feat * 256 * sizeof(int64_t));
+    int64_t *hh = (int64_t *)malloc((size_t)n_feat * 256 * sizeof(int64_t));
+    int64_t *hc = (int64_t *)malloc((size_t)n_feat * 256 * sizeof(int64_t));
+    for (int32_t r = 0; r < n_rounds; ++r) {
+        uint8_t *nf = node_feat + (uint64_t)(n_trees_in + r) * nodes;
+        float *nt = node_thr + (uint64_t)(n_trees_in + r) * nodes;
+        float *lw = leaf + (uint64_t)(n_trees_in + r) * leaves;
+        for (uint64_t i = 0; i < n_pairs; ++i) {
+            const double d = (double)p[i] - (double)y[i];
+            gq[i] = tree_quantise(2.0 * d / (double)y[i]);
+            hq[i] = tree_quantise(2.0 / (double)y[i]);
+            at[i] = 0;
+        }
+        for (uint32_t j = 0; j < nodes; ++j) { /* level order: all samples of node j are known when j comes up */
+            memset(hg, 0, (size_t)n_feat * 256 * sizeof(int64_t));
+            memset(hh, 0, (size_t)n_feat * 256 * sizeof(int64_t));
+            memset(hc, 0, (size_t)n_feat * 256 * sizeof(int64_t));
+            int64_t G = 0, H = 0, N = 0;
+            for (uint64_t i = 0; i < n_pairs; ++i) {
+                if (at[i] != j) continue;
+                G += gq[i]; H += hq[i]; N += 1;
+                for (int32_t f = 0; f < n_feat; ++f) {
+                    const int b = tree_bin(feat[(uint64_t)f * ld + i]);
+                    hg[f * 256 + b] += gq[i];
+                    hh[f * 256 + b] += hq[i];
+                    hc[f * 256 + b] += 1;
+                }
+            }
+            double best = 0.0;
+            int best_f = -1, best_b = -1;
+            const double parent = (double)G * (double)G / ((double)H + lam);
+            for (int32_t f = 0; f < n_feat && N > 1; ++f) {
+                int64_t GL = 0, HL = 0, NL = 0;
+                for (int b = 0; b < 255; ++b) {
+                    GL += hg[f * 256 + b]; HL += hh[f * 256 + b]; NL += hc[f * 256 + b];
+                    if (NL == 0 || NL == N) continue;
+                    const int64_t GR = G - GL, HR = H - HL;
+                    const double gain = (double)GL * (double)GL / ((double)HL + lam) +
+                                        (double)GR * (double)GR / ((double)HR + lam) - parent;
+                    if (gain > best) { best = gain; best_f = f; best_b = b; }
+                }
+            }
+            if (best_f < 0) { nf[j] = 0; nt[j] = INFINITY; }
+            else { nf[j] = (uint8_t)best_f; nt[j] = (float)(best_b + 1) * 0.25f; }
+            for (uint64_t i = 0; i < n_pairs; ++i)
+                if (at[i] == j) at[i] = 2 * j + ((feat[(uint64_t)nf[j] * ld + i] < nt[j]) ? 1u : 2u);
+        }
+        for (uint32_t l = 0; l < leaves; ++l) {
+            int64_t G = 0, H = 0, N = 0;
+            for (uint64_t i = 0; i < n_pairs; ++i)
+                if (at[i] == nodes + l) { G += gq[i]; H += hq[i]; N += 1; }
+            lw[l] = N ? (float)(-eta * (double)G / ((double)H + lam)) : 0.0f;
+        }
+        for (uint64_t i = 0; i < n_pairs; ++i) p[i] = p[i] + lw[at[i] - nodes];
+    }
+    double total = 0.0;
+    for (uint64_t i = 0; i < n_pairs; ++i) total += orc_loss((double)p[i], (double)y[i]);
+    *loss_out = total / (double)n_pairs;
+    free(y); free(p); free(gq); free(hq); free(at); free(hg); free(hh); free(hc);
+    return ORC_OK;
 }
