@@ -274,6 +274,69 @@ int32_t costmodel_update(eck_model *model, const void *feat, int32_t feat_dtype,
 /* Library version as major*10000 + minor*100 + patch. */
 int32_t eck_version(void);
 
+/* ------------------------------------------------- boosted-tree cost model */
+
+/* The cost model in the paper's own form (Sec. 5.4 "Approach"): an ensemble of
+ * regression trees built one after another by gradient boosting; the
+ * prediction is the base score plus the sum of the trees' outputs.  Trees are
+ * complete binary trees of one fixed depth d, stored level by level: node j
+ * tests x[feature_j] < threshold_j; true -> node 2j+1, false (also NaN) ->
+ * node 2j+2; after d tests the walk stands on node (2^d - 1) + leaf.  A node
+ * that does not split has threshold +inf.  Arrays (device, per tree):
+ *   node_feat uint8 [2^d - 1], node_thr float [2^d - 1], leaf float [2^d].
+ * n_feat in 1..256, depth in 1..ECK_MAX_TREE_DEPTH, capacity = most trees the
+ * model can hold (<= 65536).  Allocates device memory for `capacity` trees.
+ * Errors: EINVAL, EUNSUPPORTED (limits), EDEVICE. */
+typedef struct eck_trees eck_trees;
+#define ECK_MAX_TREE_DEPTH 8
+int32_t eck_trees_create(int32_t n_feat, int32_t depth, int32_t capacity, float base_score, eck_trees **out);
+void eck_trees_destroy(eck_trees *trees);
+
+/* Number of trees the model holds now.  Host only. */
+int32_t eck_trees_count(const eck_trees *trees, int32_t *n_trees);
+
+/* Replace / read the ensemble (checkpointing).  The arrays are device memory,
+ * [n_trees][...] as above; the copies are enqueued on stream.  A feature index
+ * >= n_feat is read as n_feat - 1 when scoring.  ESHAPE: n_trees > capacity. */
+int32_t eck_trees_set(eck_trees *trees, int32_t n_trees, const uint8_t *node_feat, const float *node_thr,
+                      const float *leaf, void *stream);
+int32_t eck_trees_get(const eck_trees *trees, uint8_t *node_feat, float *node_thr, float *leaf, void *stream);
+
+/* score_out[i] = base + sum over trees of the leaf candidate i reaches, added in
+ * fp32 in tree order.  feat: device, [n_feat][ld] of feat_dtype (ECK_F32 or
+ * ECK_BF16; values are compared exactly, never rounded); score_out: device,
+ * float [n].  Errors: EINVAL, ESHAPE (ld < n), EUNSUPPORTED (feature tile does
+ * not fit the LDS: n_feat * 1 KB fp32 / 512 B bf16 above ~140 KB). */
+int32_t treemodel_score(const eck_trees *trees, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n,
+                        float *score_out, void *stream);
+
+/* Gradient boosting on the loss of Eq. (1) (Sec. 5.4; Alg. 1 ModelUpdate):
+ * appends n_rounds trees fitted to the measured pairs.
+ *   labels      y = energy_measured / max(energy_measured) in fp32
+ *   prediction  p in fp32: base, then the trees in order
+ *   per round   g = 2 (p - y) / y, h = 2 / y (derivatives of Eq. (1) in p),
+ *               computed in fp64 and rounded to integers of resolution 2^-20
+ *               (|g|, h clamped to 2^20); all sums are exact integer sums
+ *   growth      level by level; features are binned into 256 bins of width 1/4
+ *               on [0, 64) (the range of the transformed features); a split
+ *               "feature f, bins <= b go left" has threshold (b + 1) / 4 and
+ *               gain GL^2/(HL+lam) + GR^2/(HR+lam) - G^2/(H+lam), fp64, lam =
+ *               lambda * 2^20; both sides non-empty; largest gain > 0 wins, ties
+ *               to the lower feature then the lower bin; else no split
+ *   leaves      w = -eta * G / (H + lam), fp64 -> fp32; empty leaf 0
+ * The result is identical to a sequential evaluation of these steps: nothing
+ * depends on the order of execution.
+ * snr_out (device float): sum y^2 / sum (p - y)^2 of the ensemble on entry;
+ * loss_out (device float): mean Eq. (1) loss after the last round.
+ * Any energy <= 0 or not finite: snr = loss = NaN and the appended trees are
+ * empty (no split, all leaves 0), so predictions do not change.
+ * n_pairs <= 2^20 (EUNSUPPORTED above); ESHAPE: ld < n_pairs or capacity
+ * exceeded; EWORKSPACE / EALIGN (256 B) for ws. */
+uint64_t treemodel_update_workspace_bytes(const eck_trees *trees, uint64_t n_pairs);
+int32_t treemodel_update(eck_trees *trees, const void *feat, int32_t feat_dtype, uint64_t ld,
+                         const float *energy_measured, uint64_t n_pairs, int32_t n_rounds, float eta, float lambda,
+                         float *snr_out, float *loss_out, void *ws, uint64_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

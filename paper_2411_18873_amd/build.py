@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libeck.so")
-SOURCES = ["space.hip", "model.hip", "topk.hip", "update.hip"]
+SOURCES = ["space.hip", "model.hip", "topk.hip", "update.hip", "trees.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     # compiler-generated packed fp32 math is switched off for device code

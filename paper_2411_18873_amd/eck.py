@@ -29,7 +29,9 @@ EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_in
            "candidate_enumerate", "candidate_enumerate_batch", "eck_candidates_gather", "features_compute",
            "features_compute_batch", "eck_model_create", "eck_model_destroy",
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
-           "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update"]
+           "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update",
+           "eck_trees_create", "eck_trees_destroy", "eck_trees_count", "eck_trees_set", "eck_trees_get",
+           "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update"]
 
 
 class EckError(RuntimeError):
@@ -80,6 +82,16 @@ def lib():
         L.eck_model_set_state.argtypes = [vp, vp, u64, vp]
         L.eck_model_get_state.argtypes = [vp, vp, u64, vp]
         L.costmodel_score.argtypes = [vp, vp, i32, u64, u64, vp, vp, u64, vp]
+        L.eck_trees_create.argtypes = [i32, i32, i32, f32, C.POINTER(vp)]
+        L.eck_trees_destroy.argtypes = [vp]
+        L.eck_trees_destroy.restype = None
+        L.eck_trees_count.argtypes = [vp, C.POINTER(i32)]
+        L.eck_trees_set.argtypes = [vp, i32, vp, vp, vp, vp]
+        L.eck_trees_get.argtypes = [vp, vp, vp, vp, vp]
+        L.treemodel_score.argtypes = [vp, vp, i32, u64, u64, vp, vp]
+        L.treemodel_update_workspace_bytes.argtypes = [vp, u64]
+        L.treemodel_update_workspace_bytes.restype = u64
+        L.treemodel_update.argtypes = [vp, vp, i32, u64, vp, u64, i32, f32, f32, vp, vp, vp, u64, vp]
         L.topk_select_workspace_bytes.argtypes = [u64, u32, u32]
         L.topk_select_workspace_bytes.restype = u64
         L.topk_select.argtypes = [vp, vp, vp, u64, u32, u32, i32, f32, u32, vp, vp, vp, vp, u64, vp]
@@ -176,6 +188,51 @@ class Model:
     def close(self):
         if getattr(self, "h", None) and _lib is not None:
             _lib.eck_model_destroy(self.h)
+        self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class Trees:
+    """Boosted regression-tree cost model (eck_trees): complete trees of one depth, level-order arrays."""
+
+    def __init__(self, n_feat, depth, capacity, base_score=0.5):
+        self.n_feat, self.depth, self.capacity, self.base_score = int(n_feat), int(depth), int(capacity), float(base_score)
+        h = C.c_void_p()
+        _check("eck_trees_create", lib().eck_trees_create(self.n_feat, self.depth, self.capacity, self.base_score,
+                                                          C.byref(h)))
+        self.h = h
+
+    @property
+    def n_trees(self):
+        n = C.c_int32()
+        _check("eck_trees_count", lib().eck_trees_count(self.h, C.byref(n)))
+        return n.value
+
+    def set(self, node_feat, node_thr, leaf):
+        """uint8 [T][2^d-1], float32 [T][2^d-1], float32 [T][2^d] CUDA tensors"""
+        n = int(leaf.shape[0])
+        _dev(node_feat, torch.uint8, "node_feat")
+        _dev(node_thr, torch.float32, "node_thr")
+        _dev(leaf, torch.float32, "leaf")
+        assert node_feat.shape == (n, (1 << self.depth) - 1) == node_thr.shape and leaf.shape[1] == 1 << self.depth
+        _check("eck_trees_set", lib().eck_trees_set(self.h, n, _ptr(node_feat), _ptr(node_thr), _ptr(leaf), _stream()))
+
+    def get(self):
+        n = self.n_trees
+        node_feat = torch.zeros((n, (1 << self.depth) - 1), dtype=torch.uint8, device="cuda")
+        node_thr = torch.zeros((n, (1 << self.depth) - 1), dtype=torch.float32, device="cuda")
+        leaf = torch.zeros((n, 1 << self.depth), dtype=torch.float32, device="cuda")
+        _check("eck_trees_get", lib().eck_trees_get(self.h, _ptr(node_feat), _ptr(node_thr), _ptr(leaf), _stream()))
+        return node_feat, node_thr, leaf
+
+    def close(self):
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.eck_trees_destroy(self.h)
         self.h = None
 
     def __del__(self):
@@ -321,3 +378,28 @@ def costmodel_update(model, feat, energy_measured, n_steps, minibatch, snr_out, 
         model.h, _ptr(feat), feat_dtype, feat.shape[1], _ptr(energy_measured), energy_measured.numel(), n_steps,
         minibatch, lr, beta1, beta2, eps, _ptr(snr_out), _ptr(loss_out), _ptr(ws), ws.numel() * ws.element_size(),
         _stream()))
+
+
+def treemodel_score(trees, feat, n, score_out):
+    feat_dtype = {torch.float32: F32, torch.bfloat16: BF16}[feat.dtype]
+    assert feat.is_cuda and feat.is_contiguous() and feat.shape[0] == trees.n_feat
+    _dev(score_out, torch.float32, "score_out")
+    assert score_out.numel() >= n
+    _check("treemodel_score", lib().treemodel_score(trees.h, _ptr(feat), feat_dtype, feat.shape[1], n, _ptr(score_out),
+                                                    _stream()))
+
+
+def treemodel_update_workspace_bytes(trees, n_pairs):
+    return int(lib().treemodel_update_workspace_bytes(trees.h, n_pairs))
+
+
+def treemodel_update(trees, feat, energy_measured, n_rounds, snr_out, loss_out, ws, eta=0.3, lam=1.0):
+    feat_dtype = {torch.float32: F32, torch.bfloat16: BF16}[feat.dtype]
+    assert feat.is_cuda and feat.is_contiguous() and feat.shape[0] == trees.n_feat
+    _dev(energy_measured, torch.float32, "energy_measured")
+    _dev(snr_out, torch.float32, "snr_out")
+    _dev(loss_out, torch.float32, "loss_out")
+    assert ws.is_cuda and ws.is_contiguous()
+    _check("treemodel_update", lib().treemodel_update(
+        trees.h, _ptr(feat), feat_dtype, feat.shape[1], _ptr(energy_measured), energy_measured.numel(), n_rounds, eta,
+        lam, _ptr(snr_out), _ptr(loss_out), _ptr(ws), ws.numel() * ws.element_size(), _stream()))

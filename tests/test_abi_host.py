@@ -186,3 +186,26 @@ def test_product_package_never_touches_the_oracle():
                 assert "import oracle" not in text and "from oracle" not in text and "liboracle" not in text, name
     text = open(os.path.join(ROOT, "oracle", "__init__.py")).read() + open(os.path.join(ROOT, "oracle", "eck_oracle.c")).read()
     assert "paper_2411_18873_amd" not in text and "libeck" not in text and "eck.h" not in text
+
+
+def test_tree_model_validation():
+    L = eck.lib()
+    h = C.c_void_p()
+    T = L.eck_trees_create
+    assert T(64, 6, 100, 0.5, None) == eck.EINVAL
+    assert T(0, 6, 100, 0.5, C.byref(h)) == eck.EINVAL
+    assert T(64, 0, 100, 0.5, C.byref(h)) == eck.EINVAL
+    assert T(64, 6, 0, 0.5, C.byref(h)) == eck.EINVAL
+    assert T(64, 6, 100, float("nan"), C.byref(h)) == eck.EINVAL
+    assert T(257, 6, 100, 0.5, C.byref(h)) == eck.EUNSUPPORTED
+    assert T(64, 9, 100, 0.5, C.byref(h)) == eck.EUNSUPPORTED
+    assert T(64, 6, 70000, 0.5, C.byref(h)) == eck.EUNSUPPORTED
+    assert h.value is None
+    n = C.c_int32()
+    assert L.eck_trees_count(None, C.byref(n)) == eck.EINVAL
+    assert L.eck_trees_set(None, 0, None, None, None, None) == eck.EINVAL
+    assert L.eck_trees_get(None, None, None, None, None) == eck.EINVAL
+    assert L.treemodel_score(None, FAKE, 0, 16, 16, FAKE, None) == eck.EINVAL
+    assert L.treemodel_update_workspace_bytes(None, 100) == 0
+    assert L.treemodel_update(None, FAKE, 0, 16, FAKE, 16, 1, 0.3, 1.0, FAKE, FAKE, FAKE, 1 << 20, None) == eck.EINVAL
+    L.eck_trees_destroy(None)
