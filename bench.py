@@ -71,7 +71,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=18)
-    ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update", "copy"], default=None,
+    ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update", "copy", "treescore", "treeupdate"],
+                    default=None,
                     help="profiling aid: after set-up run only this call of the step (prints a short JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -148,6 +149,12 @@ def main():
 
     if args.only:
         feat_copy = torch.empty_like(feat) if args.only == "copy" else None
+        trees = None
+        if args.only in ("treescore", "treeupdate"):
+            # the paper's own model form on the same workload: 100 trees of depth 6, each refit call adds 4
+            trees = eck.Trees(F, 6, 100 + 4 * (args.steps + args.warmup + 1), 0.5)
+            ws_trees = torch.empty(eck.treemodel_update_workspace_bytes(trees, upd_rows), dtype=torch.uint8, device=dev)
+            eck.treemodel_update(trees, upd_feat, upd_energy, 100, snr, loss, ws_trees)
         step(0, False)  # fills every buffer once
         torch.cuda.synchronize()
 
@@ -162,6 +169,10 @@ def main():
                 # plain device copy of known size (2^24 x 64 bf16 = 2 GiB read + 2 GiB written): calibrates
                 # the FETCH_SIZE / WRITE_SIZE counters
                 feat_copy.copy_(feat)
+            elif args.only == "treescore":
+                eck.treemodel_score(trees, feat, N, energy)
+            elif args.only == "treeupdate":
+                eck.treemodel_update(trees, upd_feat, upd_energy, 4, snr, loss, ws_trees)
             elif args.only == "topk":
                 eck.topk_select(energy, latency, legal, S, K, idx, e_out, count, ws_topk, alpha=cfg["alpha"])
             else:

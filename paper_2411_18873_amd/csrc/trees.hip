@@ -7,7 +7,7 @@
 // on node (2^d - 1) + leaf.  A node that does not split has threshold +inf.
 //
 // Scoring: one candidate per lane.  A block stages the features of 256 candidates and a chunk of trees in LDS
-// and walks four trees at a time per lane (four independent chains of dependent LDS reads); leaf values are
+// and walks eight trees at a time per lane (eight independent chains of dependent LDS reads); leaf values are
 // added in fp32 in tree order, so the result does not depend on how trees are chunked or interleaved.
 //
 // Boosting: gradient statistics are rounded to integers of resolution 2^-20 and summed with integer atomics,
@@ -33,6 +33,7 @@ namespace {
 
 constexpr int BLOCK = 256;
 constexpr int BINS = 256;
+constexpr int WALKS = 8; // trees walked at the same time by one lane
 constexpr double FIX = 1048576.0; // 2^20
 
 __device__ __forceinline__ float feature_value(const void *feat, int is_bf16, uint64_t at)
@@ -83,21 +84,27 @@ __global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__rest
                 else return (float)v;
             };
             int t = 0;
-            for (; t + 4 <= in_chunk; t += 4) {
-                uint32_t j0 = 0, j1 = 0, j2 = 0, j3 = 0;
-                const uint2 *n0 = node_lds + (size_t)t * nodes, *n1 = n0 + nodes, *n2 = n1 + nodes, *n3 = n2 + nodes;
+            for (; t + WALKS <= in_chunk; t += WALKS) {
+                uint32_t j[WALKS];
+#pragma unroll
+                for (int w = 0; w < WALKS; ++w) j[w] = 0;
+                const uint2 *first = node_lds + (size_t)t * nodes;
                 for (int l = 0; l < depth; ++l) {
-                    const uint2 a = n0[j0], b = n1[j1], c = n2[j2], d = n3[j3];
-                    j0 = 2 * j0 + (x_of(a.y) < __uint_as_float(a.x) ? 1u : 2u);
-                    j1 = 2 * j1 + (x_of(b.y) < __uint_as_float(b.x) ? 1u : 2u);
-                    j2 = 2 * j2 + (x_of(c.y) < __uint_as_float(c.x) ? 1u : 2u);
-                    j3 = 2 * j3 + (x_of(d.y) < __uint_as_float(d.x) ? 1u : 2u);
+                    uint2 nd[WALKS];
+#pragma unroll
+                    for (int w = 0; w < WALKS; ++w) nd[w] = first[(size_t)w * nodes + j[w]];
+                    float x[WALKS];
+#pragma unroll
+                    for (int w = 0; w < WALKS; ++w) x[w] = x_of(nd[w].y);
+#pragma unroll
+                    for (int w = 0; w < WALKS; ++w) j[w] = 2 * j[w] + (x[w] < __uint_as_float(nd[w].x) ? 1u : 2u);
                 }
                 const float *lf = leaf_lds + (size_t)t * leaves;
-                acc = acc + lf[j0 - nodes];
-                acc = acc + lf[leaves + j1 - nodes];
-                acc = acc + lf[2 * leaves + j2 - nodes];
-                acc = acc + lf[3 * leaves + j3 - nodes];
+                float v[WALKS];
+#pragma unroll
+                for (int w = 0; w < WALKS; ++w) v[w] = lf[(size_t)w * leaves + j[w] - nodes];
+#pragma unroll
+                for (int w = 0; w < WALKS; ++w) acc = acc + v[w]; // tree order
             }
             for (; t < in_chunk; ++t) {
                 uint32_t j = 0;
@@ -120,15 +127,17 @@ int32_t launch_score(const eck_trees *m, int n_trees, const void *feat, int32_t 
     if (tiles64 > 0xFFFFFFFFull) return ECK_EUNSUPPORTED;
     const size_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
     const size_t x_bytes = (size_t)m->n_feat * BLOCK * elem;
-    // trees per chunk: what fits beside the feature tile in 72 KB (two blocks per compute unit), at least 4
+    // trees per chunk: what fits beside the feature tile in 72 KB (two blocks per compute unit), else in
+    // 150 KB; a multiple of the number of simultaneous walks
     const size_t per_tree = tree_lds_bytes(m->depth);
     size_t budget = 72 * 1024;
-    if (x_bytes + 4 * per_tree > budget) budget = 150 * 1024;
-    if (x_bytes + 4 * per_tree > budget) return ECK_EUNSUPPORTED;
+    if (x_bytes + WALKS * per_tree > budget) budget = 150 * 1024;
+    if (x_bytes + WALKS * per_tree > budget) return ECK_EUNSUPPORTED;
     int chunk = (int)((budget - x_bytes) / per_tree);
-    chunk &= ~3;
-    if (n_trees > 0 && chunk > ((n_trees + 3) & ~3)) chunk = (n_trees + 3) & ~3;
-    if (chunk < 4) chunk = 4;
+    chunk -= chunk % WALKS;
+    const int rounded = (n_trees + WALKS - 1) / WALKS * WALKS;
+    if (n_trees > 0 && chunk > rounded) chunk = rounded;
+    if (chunk < WALKS) chunk = WALKS;
     const size_t lds = x_bytes + (size_t)chunk * per_tree;
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device);
@@ -264,27 +273,48 @@ __global__ void tree_zero_kernel(unsigned long long *ptr, uint64_t words)
 }
 
 // Histograms of one level: hist[node in level][feature][bin] = (sum g, sum h, count) over the pairs that
-// stand on that node.  Integer atomics only.
-__global__ void tree_hist_kernel(const uint8_t *__restrict__ bins, const long long *__restrict__ gq,
-                                 const long long *__restrict__ hq, const uint32_t *__restrict__ at, uint64_t n_pairs,
-                                 int n_feat, uint32_t first_node, unsigned long long *__restrict__ hist)
+// stand on that node.  Every pair of a level hits the few cells of one feature, and device-wide atomics on
+// them serialise, so a block takes one feature, a group of 8 nodes and a slice of the pairs, accumulates in
+// LDS (integer atomics) and merges its non-empty cells once.
+constexpr uint32_t LDS_HIST_NODES = 8;
+__global__ __launch_bounds__(BLOCK) void tree_hist_lds_kernel(const uint8_t *__restrict__ bins,
+                                                             const long long *__restrict__ gq,
+                                                             const long long *__restrict__ hq,
+                                                             const uint32_t *__restrict__ at, uint64_t n_pairs,
+                                                             int n_feat, uint32_t first_node, uint32_t level_nodes,
+                                                             unsigned long long *__restrict__ hist)
 {
-    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    __shared__ unsigned long long cells[LDS_HIST_NODES * BINS * 3];
+    const uint32_t group0 = blockIdx.z * LDS_HIST_NODES; // first node (within the level) of this block's group
+    const uint32_t in_group = min(LDS_HIST_NODES, level_nodes - group0);
+    const uint32_t n_cells = in_group * BINS * 3;
+    for (uint32_t c = threadIdx.x; c < n_cells; c += BLOCK) cells[c] = 0;
+    __syncthreads();
     const int f = blockIdx.y;
-    if (i >= n_pairs) return;
-    const uint32_t r = at[i] - first_node;
-    const uint32_t b = bins[(uint64_t)f * n_pairs + i];
-    unsigned long long *cell = hist + (((uint64_t)r * n_feat + f) * BINS + b) * 3;
-    atomicAdd(cell, (unsigned long long)gq[i]);
-    atomicAdd(cell + 1, (unsigned long long)hq[i]);
-    atomicAdd(cell + 2, 1ull);
+    for (uint64_t i = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; i < n_pairs; i += (uint64_t)gridDim.x * BLOCK) {
+        const uint32_t r = at[i] - first_node - group0; // wraps for nodes below the group
+        if (r >= in_group) continue;
+        const uint32_t b = bins[(uint64_t)f * n_pairs + i];
+        unsigned long long *cell = cells + ((uint64_t)r * BINS + b) * 3;
+        atomicAdd(cell, (unsigned long long)gq[i]);
+        atomicAdd(cell + 1, (unsigned long long)hq[i]);
+        atomicAdd(cell + 2, 1ull);
+    }
+    __syncthreads();
+    for (uint32_t c = threadIdx.x; c < n_cells; c += BLOCK) {
+        const unsigned long long v = cells[c];
+        if (!v) continue;
+        const uint32_t r = group0 + c / (BINS * 3), rest = c % (BINS * 3);
+        atomicAdd(hist + ((uint64_t)r * n_feat + f) * BINS * 3 + rest, v);
+    }
 }
 
-// One block per node of the level: the split of largest gain.  Wavefront w takes features w, w+4, ...; a lane
+// One block per node of the level: the split of largest gain.  Wavefront w takes features w, w+16, ...; a lane
 // takes four consecutive bins; prefix sums over the bins by shuffles.  gain(f, b) = GL^2/(HL+lam) +
 // GR^2/(HR+lam) - G^2/(H+lam) in fp64; the largest gain > 0 wins, ties to the lower feature, then the lower
 // bin (the candidate's rank f * 256 + b breaks ties in every comparison).
-__global__ __launch_bounds__(BLOCK) void tree_split_kernel(const unsigned long long *__restrict__ hist, int n_feat,
+constexpr int SPLIT_BLOCK = 1024;
+__global__ __launch_bounds__(SPLIT_BLOCK) void tree_split_kernel(const unsigned long long *__restrict__ hist, int n_feat,
                                                           uint32_t first_node, double lam, uint8_t *__restrict__ nf,
                                                           float *__restrict__ nt, const BoostScalars *sc)
 {
@@ -321,7 +351,7 @@ __global__ __launch_bounds__(BLOCK) void tree_split_kernel(const unsigned long l
     const double parent = (double)G * (double)G / ((double)H + lam);
     double best = 0.0;
     uint32_t best_rank = 0xFFFFFFFFu;
-    for (int f = wave; f < n_feat && N > 1; f += 4) {
+    for (int f = wave; f < n_feat && N > 1; f += SPLIT_BLOCK / 64) {
         long long g[4], hh[4], c[4];
         long long sg = 0, sh = 0, scnt = 0;
 #pragma unroll
@@ -364,12 +394,12 @@ __global__ __launch_bounds__(BLOCK) void tree_split_kernel(const unsigned long l
         }
     }
     // block argmax, lower rank on equal gain
-    __shared__ double s_gain[BLOCK];
-    __shared__ uint32_t s_rank[BLOCK];
+    __shared__ double s_gain[SPLIT_BLOCK];
+    __shared__ uint32_t s_rank[SPLIT_BLOCK];
     s_gain[threadIdx.x] = best;
     s_rank[threadIdx.x] = best_rank;
     __syncthreads();
-    for (int off = BLOCK / 2; off > 0; off >>= 1) {
+    for (int off = SPLIT_BLOCK / 2; off > 0; off >>= 1) {
         if ((int)threadIdx.x < off) {
             const double og = s_gain[threadIdx.x + off];
             const uint32_t orank = s_rank[threadIdx.x + off];
@@ -600,9 +630,14 @@ extern "C" int32_t treemodel_update(eck_trees *m, const void *feat, int32_t feat
             const uint32_t level_nodes = 1u << l, first = level_nodes - 1u;
             const uint64_t words = (uint64_t)level_nodes * m->n_feat * BINS * 3;
             hipLaunchKernelGGL(tree_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, hist, words);
-            hipLaunchKernelGGL(tree_hist_kernel, dim3(pair_blocks, m->n_feat), dim3(256), 0, st, bins, gq, hq, at,
-                               n_pairs, m->n_feat, first, hist);
-            hipLaunchKernelGGL(tree_split_kernel, dim3(level_nodes), dim3(BLOCK), 0, st, hist, m->n_feat, first, lam, nf,
+            {
+                unsigned slices = (unsigned)(n_pairs / 2048);
+                slices = slices < 1 ? 1 : (slices > 64 ? 64 : slices);
+                const unsigned groups = (level_nodes + LDS_HIST_NODES - 1) / LDS_HIST_NODES;
+                hipLaunchKernelGGL(tree_hist_lds_kernel, dim3(slices, m->n_feat, groups), dim3(BLOCK), 0, st, bins, gq, hq,
+                                   at, n_pairs, m->n_feat, first, level_nodes, hist);
+            }
+            hipLaunchKernelGGL(tree_split_kernel, dim3(level_nodes), dim3(SPLIT_BLOCK), 0, st, hist, m->n_feat, first, lam, nf,
                                nt, sc);
             hipLaunchKernelGGL(tree_partition_kernel, dim3(pair_blocks), dim3(256), 0, st, feat, is_bf16, ld, n_pairs, nf,
                                nt, at);

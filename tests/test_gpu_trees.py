@@ -176,3 +176,39 @@ def test_boosting_rejects_bad_energies_without_changing_predictions(G):
     assert np.array_equal(_score(trees, feat_dev, 512), before)
     a, b, c = (t.cpu().numpy() for t in trees.get())
     assert np.all(np.isinf(b[4:])) and np.all(c[4:] == 0)
+
+
+def test_tree_scores_at_the_benchmark_size(G):
+    """The c5 population (2^24 candidates of 64 GEMM shapes, bf16 features) scored by an ensemble boosted on
+    2048 measured pairs, in the launch configuration bench.py --only treescore times; every 4099th candidate
+    and the ends of the range are checked against the oracle, bit for bit."""
+    cfg = synth.CONFIGS["c5"]
+    shapes, per = cfg["shapes"], cfg["n_per_shape"]
+    S, N = len(shapes), len(shapes) * cfg["n_per_shape"]
+    spaces = [eck.Space(synth.gemm(*s), eck.SPACE_SPLIT) for s in shapes]
+    seeds = [cfg["seed_base"] + s for s in range(S)]
+    genes = torch.zeros((5, N), dtype=torch.int16, device="cuda")
+    feat = torch.zeros((64, N), dtype=torch.bfloat16, device="cuda")
+    eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, per, genes, seeds)
+    eck.features_compute_batch(spaces, genes, per, 64, eck.BF16, feat_out=feat)
+    # measured pairs: 32 candidates of every shape, as in the benchmark
+    pg = torch.zeros((5, 2048), dtype=torch.int16, device="cuda")
+    pf = torch.zeros((64, 2048), dtype=torch.bfloat16, device="cuda")
+    eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, 32, pg, [5000 + s for s in range(S)])
+    eck.features_compute_batch(spaces, pg, 32, 64, eck.BF16, feat_out=pf)
+    torch.cuda.synchronize()
+    e = synth.measured_energy(pf.float().cpu().numpy(), 13)
+    base = float(np.float32(0.5))
+    trees = eck.Trees(64, 6, 100, base)
+    snr, loss = _boost_gpu(trees, pf, e, 100, float(np.float32(0.3)), float(np.float32(1.0)))
+    assert np.isfinite(snr) and loss < 1e-3
+    out = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+    eck.treemodel_score(trees, feat, N, out)
+    torch.cuda.synchronize()
+    cols = np.unique(np.concatenate([np.arange(0, N, 4099), np.arange(N - 300, N), np.arange(0, 300)]))
+    sub = feat[:, torch.from_numpy(cols).cuda()].view(torch.int16).cpu().numpy().view(np.uint16)
+    a, b, c = (t.cpu().numpy() for t in trees.get())
+    want = oracle.trees_predict(64, 6, a, b, c, base, oracle.bf16_bits_to_f32(sub), fp32_sequential=True)
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    assert np.array_equal(got[cols], want.astype(np.float32))
