@@ -274,6 +274,14 @@ int32_t costmodel_update(eck_model *model, const void *feat, int32_t feat_dtype,
 /* Library version as major*10000 + minor*100 + patch. */
 int32_t eck_version(void);
 
+/* The k controller of Alg. 1 (Sec. 6.4): after a round in which round(k*M)
+ * kernels were measured and the model updated, a signal-to-noise ratio of the
+ * pre-update predictions below mu raises k by 0.2 (more measurements next
+ * round), otherwise k falls by 0.2; k stays in [0, 1].  A round that measured
+ * nothing (round(k*M) == 0) has no SNR and leaves k unchanged.  Host only;
+ * *k_out receives the next k.  EINVAL: nulls, M < 0, k outside [0, 1], NaN. */
+int32_t eck_k_step(double k, double snr, double mu, int64_t M, double *k_out);
+
 /* ------------------------------------------------- boosted-tree cost model */
 
 /* The cost model in the paper's own form (Sec. 5.4 "Approach"): an ensemble of

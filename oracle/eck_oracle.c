@@ -863,7 +863,9 @@ double orc_k_step(double k, double snr, double mu, int64_t M)
 {
     int64_t measured = (int64_t)floor(k * (double)M + 0.5);
     if (measured == 0) return k;
-    if (snr < mu) return fmin(1.0, k + 0.2);
+    /* Alg. 1 says nothing about a ratio that does not exist (rejected energies
+     * give NaN): read as "no evidence of a good model", i.e. as below mu */
+    if (!(snr >= mu)) return fmin(1.0, k + 0.2);
     return fmax(0.0, k - 0.2);
 }
 

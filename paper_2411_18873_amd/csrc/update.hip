@@ -493,3 +493,18 @@ extern "C" int32_t costmodel_update(eck_model *m, const void *feat, int32_t feat
     ECK_HIP_TRY(hipGetLastError());
     return model_repack(m, st);
 }
+
+extern "C" int32_t eck_k_step(double k, double snr, double mu, int64_t M, double *k_out)
+{
+    if (!k_out || M < 0 || !(k >= 0.0 && k <= 1.0) || mu != mu) return ECK_EINVAL;
+    const int64_t measured = (int64_t)__builtin_floor(k * (double)M + 0.5);
+    if (measured == 0) {
+        *k_out = k;
+        return ECK_OK;
+    }
+    // a NaN ratio (rejected energies) counts as a poor model: measure more
+    const bool poor = !(snr >= mu);
+    const double next = poor ? k + 0.2 : k - 0.2;
+    *k_out = next > 1.0 ? 1.0 : (next < 0.0 ? 0.0 : next);
+    return ECK_OK;
+}

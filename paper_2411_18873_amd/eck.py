@@ -31,7 +31,7 @@ EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_in
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
            "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update",
            "eck_trees_create", "eck_trees_destroy", "eck_trees_count", "eck_trees_set", "eck_trees_get",
-           "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update"]
+           "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step"]
 
 
 class EckError(RuntimeError):
@@ -82,6 +82,7 @@ def lib():
         L.eck_model_set_state.argtypes = [vp, vp, u64, vp]
         L.eck_model_get_state.argtypes = [vp, vp, u64, vp]
         L.costmodel_score.argtypes = [vp, vp, i32, u64, u64, vp, vp, u64, vp]
+        L.eck_k_step.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int64, C.POINTER(C.c_double)]
         L.eck_trees_create.argtypes = [i32, i32, i32, f32, C.POINTER(vp)]
         L.eck_trees_destroy.argtypes = [vp]
         L.eck_trees_destroy.restype = None
@@ -403,3 +404,10 @@ def treemodel_update(trees, feat, energy_measured, n_rounds, snr_out, loss_out, 
     _check("treemodel_update", lib().treemodel_update(
         trees.h, _ptr(feat), feat_dtype, feat.shape[1], _ptr(energy_measured), energy_measured.numel(), n_rounds, eta,
         lam, _ptr(snr_out), _ptr(loss_out), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def k_step(k, snr, mu, M):
+    """next k of the measurement-budget controller (host only)"""
+    out = C.c_double()
+    _check("eck_k_step", lib().eck_k_step(k, snr, mu, M, C.byref(out)))
+    return out.value

@@ -209,3 +209,16 @@ def test_tree_model_validation():
     assert L.treemodel_update_workspace_bytes(None, 100) == 0
     assert L.treemodel_update(None, FAKE, 0, 16, FAKE, 16, 1, 0.3, 1.0, FAKE, FAKE, FAKE, 1 << 20, None) == eck.EINVAL
     L.eck_trees_destroy(None)
+
+
+def test_k_controller_matches_the_oracle_and_validates():
+    for k in (0.0, 0.1, 0.2, 0.5, 0.8, 1.0):
+        for snr in (0.0, 1.0, 9.999, 10.0, 50.0, float("inf"), float("nan")):
+            for M in (0, 1, 4, 100):
+                assert eck.k_step(k, snr, 10.0, M) == oracle.k_step(k, snr, 10.0, M)
+    L = eck.lib()
+    out = C.c_double()
+    assert L.eck_k_step(0.5, 1.0, 10.0, 64, None) == eck.EINVAL
+    assert L.eck_k_step(1.5, 1.0, 10.0, 64, C.byref(out)) == eck.EINVAL
+    assert L.eck_k_step(0.5, 1.0, 10.0, -1, C.byref(out)) == eck.EINVAL
+    assert L.eck_k_step(0.5, 1.0, float("nan"), 64, C.byref(out)) == eck.EINVAL

@@ -171,3 +171,5 @@ def test_k_controller_traces():
         assert abs(k - want) < 1e-12
     # k = 0.5 halves the measurements of a round
     assert round(0.5 * M) == M // 2
+    # a ratio that does not exist (rejected energies) is no evidence of a good model
+    assert abs(oracle.k_step(0.4, float("nan"), mu, M) - 0.6) < 1e-12
