@@ -71,7 +71,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=18)
-    ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update", "copy", "treescore", "treeupdate"],
+    ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update", "copy", "treescore", "treeupdate", "search"],
                     default=None,
                     help="profiling aid: after set-up run only this call of the step (prints a short JSON)")
     args = ap.parse_args()
@@ -91,6 +91,28 @@ def main():
     eck.lib()  # fails loudly if the HIP library is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.only == "search":
+        # Alg. 1 closed into a loop (config 3's operator, 2^20 children per round, M = 128, boosted-tree models,
+        # simulated meter): rounds per second and candidates per second through the whole round
+        from paper_2411_18873_amd.search import EnergySearch
+        pop, rounds = 1 << 20, args.steps
+        s = EnergySearch(synth.CONFIGS["c3"]["problem"], eck.SPACE_SPLIT,
+                         lambda f, b: synth.simulated_kernel_metrics(f, 77, b), population=pop, M=128, n_parents=128,
+                         depth=6, init_rounds=40, update_rounds=8, mu=1000.0, max_rounds=rounds + args.warmup)
+        s.initialise()
+        for _ in range(args.warmup):
+            s.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(rounds):
+            s.step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        print(json.dumps({"only": "search", "ms_per_round": 1e3 * dt / rounds, "candidates_per_s": pop * rounds / dt,
+                          "population": pop, "rounds": rounds, "measured": sum(h["measured"] for h in s.history),
+                          "k": [round(h["k"], 2) for h in s.history]}))
+        return
 
     cfg = synth.CONFIGS["c5"]
     shapes, per = cfg["shapes"], cfg["n_per_shape"]

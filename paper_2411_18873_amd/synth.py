@@ -124,3 +124,19 @@ def gaussian_scores(n, seed, ties=0.0, quantum=None):
 def legal_mask(n, seed, frac=0.3):
     rng = np.random.default_rng(seed)
     return (rng.random(n) < frac).astype(np.uint8)
+
+
+def simulated_kernel_metrics(feat, seed, batch):
+    """Stand-in for running kernels under a power meter and a timer: (energy, latency) of the feature
+    columns feat[F][m].  Two fixed log-linear forms of the features (the "hardware", drawn from `seed`;
+    exp(0.5 (w . x - 8)) with positive weights summing to one, so schedules differ by factors, not percent)
+    times lognormal(0, 0.03) measurement noise drawn from (seed, batch) in column order."""
+    F, m = feat.shape
+    hw = np.random.default_rng(seed)
+    we, wl = hw.random(F), hw.random(F)
+    we, wl = we / we.sum(), wl / wl.sum()
+    noise = np.random.default_rng([seed, batch])
+    x = np.asarray(feat, dtype=np.float64)
+    energy = np.exp(0.5 * ((we[:, None] * x).sum(axis=0) - 8.0) + 0.03 * noise.standard_normal(m))
+    latency = np.exp(0.5 * ((wl[:, None] * x).sum(axis=0) - 8.0) + 0.03 * noise.standard_normal(m))
+    return energy.astype(np.float32), latency.astype(np.float32)

@@ -1,0 +1,81 @@
+"""Alg. 1 as a closed loop (Sec. 6.4): properties of the oracle's loop on the CPU, and the library's loop on the
+GPU reproducing the oracle's trajectory -- the kernels picked for measurement in every round, the k sequence,
+the boosted trees -- exactly.  Exactness is possible because every link is exact: genes and features are
+integers, tree scores are fp32 sums in tree order, selection is on integer keys, boosting uses integer sums."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import closed_loop
+from paper_2411_18873_amd import synth
+
+ETA, LAM = float(np.float32(0.3)), float(np.float32(1.0))
+KW = dict(population=1 << 13, M=64, n_parents=32, depth=4, init_rounds=30, update_rounds=6, eta=ETA, lam=LAM, seed=1)
+
+
+def _measure(feat, batch):
+    return synth.simulated_kernel_metrics(feat, 77, batch)
+
+
+def _problem():
+    return synth.CONFIGS["c3"]["problem"]
+
+
+def test_oracle_loop_follows_the_k_rule_and_saves_measurements():
+    rounds = 8
+    # a threshold no model reaches: k stays at 1 and every round measures all M kernels
+    always, _, _ = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, rounds, mu=1e9, **KW)
+    assert all(h["k"] == 1.0 and h["measured"] == 64 for h in always)
+    # a threshold every model passes: k falls by 0.2 per round down to the floor
+    never, _, _ = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, rounds, mu=1e-9, **KW)
+    assert [round(h["k"], 9) for h in never] == [1.0, 0.8, 0.6, 0.4, 0.2, 0.2, 0.2, 0.2, 0.2]
+    assert [h["measured"] for h in never[1:]] == [64, 51, 38, 26, 13, 13, 13, 13]   # round(k M) of the k before
+    saved = sum(h["measured"] for h in always) / sum(h["measured"] for h in never)
+    assert saved > 1.9                      # the paper's "nearly 2x" at these settings (Sec. 6.4, last paragraph)
+    # in between, k moves both ways and each move is the rule applied to that round's ratio
+    mid, _, _ = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, rounds, mu=1000.0, **KW)
+    ups = downs = 0
+    for prev, cur in zip(mid, mid[1:]):
+        want = max(0.2, oracle.k_step(prev["k"], float(np.float32(cur["snr"])), 1000.0, 64))
+        assert abs(cur["k"] - want) < 1e-12
+        ups += cur["k"] > prev["k"]
+        downs += cur["k"] < prev["k"]
+    assert ups >= 1 and downs >= 1
+    # measured kernels get better: the median measured energy of the last round is below the initial sample's
+    _, _, energies = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, 4, mu=1e9, **KW)
+    assert np.median(energies[-64:]) < 0.95 * np.median(energies[:64])
+
+
+def test_simulated_meter_is_deterministic_and_positive():
+    rng = np.random.default_rng(0)
+    x = rng.uniform(0, 40, size=(64, 50)).astype(np.float32)
+    e1, l1 = synth.simulated_kernel_metrics(x, 5, 3)
+    e2, l2 = synth.simulated_kernel_metrics(x, 5, 3)
+    e3, _ = synth.simulated_kernel_metrics(x, 5, 4)
+    assert np.array_equal(e1, e2) and np.array_equal(l1, l2) and not np.array_equal(e1, e3)
+    assert np.all(e1 > 0) and np.all(l1 > 0)
+    assert np.max(np.abs(np.log(e1 / e3))) < 0.3            # the same hardware, different noise
+
+
+@pytest.mark.gpu
+def test_gpu_loop_reproduces_the_oracles_trajectory():
+    import torch
+    from paper_2411_18873_amd import eck
+    from paper_2411_18873_amd.search import EnergySearch
+    rounds, mu = 6, 1000.0
+    want, (w_nf, w_nt, w_lf), w_energy = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, rounds, mu=mu, **KW)
+    s = EnergySearch(_problem(), eck.SPACE_SPLIT, _measure, mu=mu, max_rounds=rounds, **KW)
+    s.initialise()
+    for _ in range(rounds):
+        s.step()
+    torch.cuda.synchronize()
+    assert len(s.history) == len(want)
+    for got, ref in zip(s.history, want):
+        assert got["round"] == ref["round"] and got["measured"] == ref["measured"]
+        assert got["k"] == ref["k"] and got["best"] == ref["best"]
+        if ref["round"] > 0:
+            assert np.array_equal(got["picked"], ref["picked"])
+            assert abs(got["snr"] - ref["snr"]) <= 1e-6 * ref["snr"]
+    assert np.array_equal(s.h_energy, w_energy)
+    a, b, c = (t.cpu().numpy() for t in s.energy_model.get())
+    assert np.array_equal(a, w_nf) and np.array_equal(b, w_nt) and np.array_equal(c.view(np.uint32), w_lf.view(np.uint32))
