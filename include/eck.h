@@ -60,6 +60,7 @@ extern "C" {
 #define ECK_MODE_EXHAUSTIVE 0
 #define ECK_MODE_SAMPLE 1
 #define ECK_MODE_MUTATE 2
+#define ECK_MODE_CROSSOVER 3
 
 /* element types of feature matrices and models */
 #define ECK_F32 0
@@ -121,8 +122,13 @@ int32_t eck_space_table(const eck_space *space, int32_t gene, uint32_t *out, uin
  *               state starts at mix(seed + gamma*(round+1)).
  *   MUTATE:     child c copies parent (c mod n_parents); gene g is redrawn as
  *               in SAMPLE when high32(u) < p_mut_q32 (probability p*2^32).
+ *   CROSSOVER:  two parents: (c mod n_parents) and one drawn uniformly with
+ *               word 14 of the child ((low32(u14) * n_parents) >> 32); gene g
+ *               comes from the second parent when bit g of word 15 is set;
+ *               then every gene mutates as in MUTATE.  (Alg. 1 names the
+ *               reproduction step without fixing its operators.)
  * genes_out: device, uint16 [n_genes][ld].  parents: device, uint16
- * [n_genes][n_parents] (MUTATE only, else NULL).
+ * [n_genes][n_parents] (MUTATE and CROSSOVER, else NULL).
  * Errors: EINVAL (nulls, n == 0, bad mode, index range), ESHAPE (ld < n),
  * EALIGN (genes_out not 4-byte aligned or ld odd). */
 int32_t candidate_enumerate(const eck_space *space, int32_t mode, uint64_t seed, uint32_t round,
@@ -155,6 +161,21 @@ int32_t candidate_enumerate_batch(const eck_space *const *spaces, uint32_t n_spa
  * Errors: EINVAL (nulls, k == 0, n_genes outside 1..ECK_MAX_GENES), ESHAPE (ld_out < k). */
 int32_t eck_candidates_gather(const uint16_t *genes, uint64_t ld, uint64_t n, int32_t n_genes, const uint32_t *idx,
                               uint32_t k, uint16_t *out, uint64_t ld_out, void *stream);
+
+/* Duplicate removal before scoring (a generation bred from few parents
+ * repeats itself; Alg. 1's reproduction step): candidate i is a first
+ * occurrence when no candidate of lower index has the same genes.
+ *   overwrite != 0: flags[i] = first occurrence ? 1 : 0
+ *   overwrite == 0: flags[i] = flags[i] && first occurrence   (e.g. the legal
+ *                   flags of features_compute, so that duplicates drop out of
+ *                   topk_select)
+ * genes: device uint16 [n_genes][ld]; flags: device uint8 [n]; ws: device, at
+ * least eck_candidates_dedup_workspace_bytes(n) bytes (a hash table of candidate
+ * indices, 4-byte aligned).  The result does not depend on execution order.
+ * Errors: EINVAL, ESHAPE (ld < n), EUNSUPPORTED (n > 2^30), EWORKSPACE, EALIGN. */
+uint64_t eck_candidates_dedup_workspace_bytes(uint64_t n);
+int32_t eck_candidates_dedup(const uint16_t *genes, uint64_t ld, uint64_t n, int32_t n_genes, uint8_t *flags,
+                             int32_t overwrite, void *ws, uint64_t ws_bytes, void *stream);
 
 /* ---------------------------------------------------------------- features */
 

@@ -17,7 +17,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 OP_GEMM, OP_BGEMM, OP_CONV2D = 0, 1, 2
 SPACE_KNOB, SPACE_SPLIT = 0, 1
-MODE_EXHAUSTIVE, MODE_SAMPLE, MODE_MUTATE = 0, 1, 2
+MODE_EXHAUSTIVE, MODE_SAMPLE, MODE_MUTATE, MODE_CROSSOVER = 0, 1, 2, 3
 SEL_THRESHOLD, SEL_RANK = 0, 1
 
 
@@ -277,3 +277,14 @@ def trees_boost(n_feat, depth, node_feat, node_thr, leaf, n_trees_in, n_rounds, 
     if rc:
         raise ValueError("oracle trees_boost: rc=%d" % rc)
     return snr.value, ls.value
+
+
+def dedup(genes, n=None):
+    """keep[i] = 1 iff no earlier candidate has the same genes (uint16 [G][ld])"""
+    genes = np.ascontiguousarray(genes, dtype=np.uint16)
+    n = genes.shape[1] if n is None else n
+    keep = np.zeros(n, dtype=np.uint8)
+    rc = lib().orc_dedup(_p(genes), C.c_uint64(genes.shape[1]), C.c_uint64(n), C.c_int32(genes.shape[0]), _p(keep))
+    if rc:
+        raise ValueError("oracle dedup: rc=%d" % rc)
+    return keep

@@ -14,7 +14,8 @@ import oracle
 
 
 def run(problem, kind, measure, rounds, population=1 << 14, M=64, n_parents=64, depth=6, init_rounds=40,
-        update_rounds=8, mu=20.0, k_min=0.2, eta=0.3, lam=1.0, p_mut_q32=429496729, seed=1):
+        update_rounds=8, mu=20.0, k_min=0.2, eta=0.3, lam=1.0, p_mut_q32=429496729, seed=1, crossover=False,
+        dedup=False):
     sp = oracle.Space(problem, kind)
     N, P = population, n_parents
     nodes, leaves = (1 << depth) - 1, 1 << depth
@@ -45,9 +46,11 @@ def run(problem, kind, measure, rounds, population=1 << 14, M=64, n_parents=64, 
     k = 1.0
     history.append(dict(round=0, measured=len(first), k=k, snr=float("nan"), best=float(m_energy.min())))
     for r in range(1, rounds + 1):
-        genes = oracle.enumerate_candidates(sp, oracle.MODE_MUTATE, N, seed=seed, rnd=r, parents=parents,
-                                            p_mut_q32=p_mut_q32)
+        genes = oracle.enumerate_candidates(sp, oracle.MODE_CROSSOVER if crossover else oracle.MODE_MUTATE, N,
+                                            seed=seed, rnd=r, parents=parents, p_mut_q32=p_mut_q32)
         _, f32, b16, legal = oracle.features(sp, genes, 64)
+        if dedup:
+            legal = legal & oracle.dedup(genes)
         x = oracle.bf16_bits_to_f32(b16)
         l_pred = oracle.trees_predict(64, depth, l_nf, l_nt, l_lf, 0.5, x, fp32_sequential=True).astype(np.float32)
         e_pred = oracle.trees_predict(64, depth, e_nf[:n_e], e_nt[:n_e], e_lf[:n_e], 0.5, x,

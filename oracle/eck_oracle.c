@@ -10,7 +10,9 @@
  * What it computes, and the passage of the paper each part follows:
  *   orc_enumerate  -- candidate generation: exhaustive index decode, random
  *                     initial sampling (Sec. 6.4, first paragraph) and the
- *                     GeneticReproduction step of Alg. 1 (mutation only).
+ *                     GeneticReproduction step of Alg. 1 (mutation, or uniform
+ *                     two-parent crossover followed by mutation).
+ *   orc_dedup      -- first-occurrence duplicate removal of a generation.
  *   orc_features   -- analytic high-level kernel features: float ops, integer
  *                     ops, vectorisation-, loop- and cache-access features
  *                     (Sec. 5.3 "Insight", Sec. 5.4 "Approach"); grid / block /
@@ -55,7 +57,7 @@
 
 enum { ORC_OP_GEMM = 0, ORC_OP_BGEMM = 1, ORC_OP_CONV2D = 2 };
 enum { ORC_SPACE_KNOB = 0, ORC_SPACE_SPLIT = 1 };
-enum { ORC_MODE_EXHAUSTIVE = 0, ORC_MODE_SAMPLE = 1, ORC_MODE_MUTATE = 2 };
+enum { ORC_MODE_EXHAUSTIVE = 0, ORC_MODE_SAMPLE = 1, ORC_MODE_MUTATE = 2, ORC_MODE_CROSSOVER = 3 };
 enum { ORC_SEL_THRESHOLD = 0, ORC_SEL_RANK = 1 };
 
 /* problem fields, in the order the Python side packs them */
@@ -286,8 +288,45 @@ int32_t orc_enumerate(const void *h, int32_t mode, uint64_t seed, uint32_t round
                 genes[(uint64_t)g * ld + i] = value;
             }
         }
+    } else if (mode == ORC_MODE_CROSSOVER) {
+        /* GeneticReproduction with two parents (Alg. 1 names the step, not its operators; uniform
+         * crossover followed by the same mutation as above is the reading taken): the first parent is
+         * child mod P as in MUTATE, the second is drawn uniformly with word 14 of the child, gene g
+         * comes from the second parent when bit g of word 15 is set, then each gene mutates as above. */
+        if (!parents || n_parents == 0 || G > 14) return ORC_EINVAL;
+        for (uint64_t i = 0; i < n; ++i) {
+            uint64_t child = first_index + i;
+            uint64_t pa = child % n_parents;
+            uint64_t pb = draw_value(orc_hash(seed, round, child, 14), n_parents);
+            uint64_t mask = orc_hash(seed, round, child, 15);
+            for (int g = 0; g < G; ++g) {
+                uint64_t u = orc_hash(seed, round, child, (uint32_t)g);
+                uint32_t coin = (uint32_t)(u >> 32);
+                uint16_t value = parents[(uint64_t)g * n_parents + (((mask >> g) & 1) ? pb : pa)];
+                if (coin < p_mut_q32) value = (uint16_t)draw_value(u, sp->radix[g]);
+                genes[(uint64_t)g * ld + i] = value;
+            }
+        }
     } else {
         return ORC_EINVAL;
+    }
+    return ORC_OK;
+}
+
+/* Duplicate removal before scoring (a generation bred from few parents repeats itself): keep[i] = 1
+ * when no candidate of lower index has the same genes, else 0.  Plain definition: compare with every
+ * earlier candidate (quadratic; sized for tests). */
+int32_t orc_dedup(const uint16_t *genes, uint64_t ld, uint64_t n, int32_t n_genes, uint8_t *keep)
+{
+    if (!genes || !keep || ld < n || n_genes < 1) return ORC_EINVAL;
+    for (uint64_t i = 0; i < n; ++i) {
+        int first = 1;
+        for (uint64_t j = 0; j < i && first; ++j) {
+            int same = 1;
+            for (int g = 0; g < n_genes && same; ++g) same = genes[(uint64_t)g * ld + i] == genes[(uint64_t)g * ld + j];
+            if (same) first = 0;
+        }
+        keep[i] = (uint8_t)first;
     }
     return ORC_OK;
 }

@@ -299,13 +299,21 @@ __global__ __launch_bounds__(256) void enumerate_kernel(SpaceBatch spaces, Strea
     } else {
         // generator state before the first gene's word: stream state + gamma * 16c
         uint64_t state = streams.state[s] + kGamma * (c << 4);
-        const uint64_t parent = MODE == ECK_MODE_MUTATE ? (uint64_t)s * n_parents + (uint32_t)(c % n_parents) : 0;
+        constexpr bool INHERITS = MODE == ECK_MODE_MUTATE || MODE == ECK_MODE_CROSSOVER;
+        const uint64_t parent = INHERITS ? (uint64_t)s * n_parents + (uint32_t)(c % n_parents) : 0;
+        // crossover: the second parent comes from word 14 of the child, the per-gene source bits from word 15
+        uint64_t second = parent, from_second = 0;
+        if (MODE == ECK_MODE_CROSSOVER) {
+            second = (uint64_t)s * n_parents + __umulhi((uint32_t)splitmix_finalise(state + kGamma * 15), n_parents);
+            from_second = splitmix_finalise(state + kGamma * 16);
+        }
         for (int g = 0; g < p.n_genes; ++g) {
             state += kGamma;
             const uint64_t u = splitmix_finalise(state);
             uint32_t value = __umulhi((uint32_t)u, p.radix[g]);
-            if (MODE == ECK_MODE_MUTATE) {
-                const uint32_t inherited = parents[(uint64_t)g * ld_parents + parent];
+            if (INHERITS) {
+                const uint64_t source = ((from_second >> g) & 1) ? second : parent;
+                const uint32_t inherited = parents[(uint64_t)g * ld_parents + source];
                 value = ((uint32_t)(u >> 32) < p_mut) ? value : inherited;
             }
             genes[(uint64_t)g * ld + col] = (uint16_t)value;
@@ -354,11 +362,13 @@ int32_t enumerate_launch(const eck_space *const *spaces, uint32_t n_spaces, int3
     if (!seeds || !genes_out || n == 0) return ECK_EINVAL;
     int32_t rc = check_batch(spaces, n_spaces);
     if (rc != ECK_OK) return rc;
-    if (mode != ECK_MODE_EXHAUSTIVE && mode != ECK_MODE_SAMPLE && mode != ECK_MODE_MUTATE) return ECK_EINVAL;
+    if (mode != ECK_MODE_EXHAUSTIVE && mode != ECK_MODE_SAMPLE && mode != ECK_MODE_MUTATE &&
+        mode != ECK_MODE_CROSSOVER)
+        return ECK_EINVAL;
     if (n > (1ull << 40) || first_index > UINT64_MAX - n) return ECK_EINVAL;
     if (ld / n_spaces < n) return ECK_ESHAPE;
     if ((ld & 1) || ((uintptr_t)genes_out & 3)) return ECK_EALIGN;
-    if (mode == ECK_MODE_MUTATE && (!parents || n_parents == 0)) return ECK_EINVAL;
+    if ((mode == ECK_MODE_MUTATE || mode == ECK_MODE_CROSSOVER) && (!parents || n_parents == 0)) return ECK_EINVAL;
     SpaceBatch batch;
     StreamBatch streams;
     for (uint32_t s = 0; s < n_spaces; ++s) {
@@ -380,8 +390,11 @@ int32_t enumerate_launch(const eck_space *const *spaces, uint32_t n_spaces, int3
     else if (mode == ECK_MODE_SAMPLE)
         hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_SAMPLE>, grid, block, 0, st, batch, streams, first_index, n,
                            parents, n_parents, ld_parents, p_mut_q32, genes_out, ld);
-    else
+    else if (mode == ECK_MODE_MUTATE)
         hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_MUTATE>, grid, block, 0, st, batch, streams, first_index, n,
+                           parents, n_parents, ld_parents, p_mut_q32, genes_out, ld);
+    else
+        hipLaunchKernelGGL(enumerate_kernel<ECK_MODE_CROSSOVER>, grid, block, 0, st, batch, streams, first_index, n,
                            parents, n_parents, ld_parents, p_mut_q32, genes_out, ld);
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
@@ -430,6 +443,107 @@ extern "C" int32_t eck_candidates_gather(const uint16_t *genes, uint64_t ld, uin
     if (ld_out < k || ld < n) return ECK_ESHAPE;
     hipLaunchKernelGGL(gather_genes_kernel, dim3((k + 255) / 256), dim3(256), 0, as_stream(stream), genes, ld, n,
                        (int)n_genes, idx, k, out, ld_out);
+    ECK_HIP_TRY(hipGetLastError());
+    return ECK_OK;
+}
+
+// ------------------------------------------------------------ de-duplication
+
+namespace {
+constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
+
+__device__ __forceinline__ uint64_t genes_hash(const uint16_t *__restrict__ genes, uint64_t ld, int n_genes, uint32_t i)
+{
+    uint64_t h = 0;
+    for (int g = 0; g < n_genes; ++g) h = splitmix_finalise(h + kGamma + genes[(uint64_t)g * ld + i]);
+    return h;
+}
+
+__device__ __forceinline__ bool same_genes(const uint16_t *__restrict__ genes, uint64_t ld, int n_genes, uint32_t a,
+                                           uint32_t b)
+{
+    for (int g = 0; g < n_genes; ++g)
+        if (genes[(uint64_t)g * ld + a] != genes[(uint64_t)g * ld + b]) return false;
+    return true;
+}
+
+__global__ void dedup_clear_kernel(uint32_t *table, uint64_t slots)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < slots) table[i] = kEmptySlot;
+}
+
+// Open-addressing table of candidate indices, one slot per distinct gene tuple; a slot ends up holding the
+// lowest index with its tuple (integer atomics only, so the outcome does not depend on execution order).
+// The table has at least 2n slots, so a probe sequence always meets a free slot or its own tuple.
+__global__ void dedup_insert_kernel(const uint16_t *__restrict__ genes, uint64_t ld, uint32_t n, int n_genes,
+                                    uint32_t *table, uint32_t mask)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint32_t slot = (uint32_t)genes_hash(genes, ld, n_genes, i) & mask;
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        const uint32_t seen = atomicCAS(&table[slot], kEmptySlot, i);
+        if (seen == kEmptySlot) return; // this candidate now stands for its tuple
+        if (seen == i || same_genes(genes, ld, n_genes, seen, i)) {
+            atomicMin(&table[slot], i);
+            return;
+        }
+        slot = (slot + 1) & mask;
+    }
+}
+
+__global__ void dedup_mark_kernel(const uint16_t *__restrict__ genes, uint64_t ld, uint32_t n, int n_genes,
+                                  const uint32_t *__restrict__ table, uint32_t mask, uint8_t *__restrict__ flags,
+                                  int overwrite)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint32_t slot = (uint32_t)genes_hash(genes, ld, n_genes, i) & mask;
+    bool first = false;
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        const uint32_t seen = table[slot];
+        if (seen == kEmptySlot) break; // cannot happen after the insert pass
+        if (seen == i || same_genes(genes, ld, n_genes, seen, i)) {
+            first = seen == i;
+            break;
+        }
+        slot = (slot + 1) & mask;
+    }
+    flags[i] = overwrite ? (first ? 1 : 0) : (flags[i] && first ? 1 : 0);
+}
+
+uint64_t dedup_slots(uint64_t n)
+{
+    uint64_t slots = 2;
+    while (slots < 2 * n) slots <<= 1;
+    return slots;
+}
+} // namespace
+
+extern "C" uint64_t eck_candidates_dedup_workspace_bytes(uint64_t n)
+{
+    if (n == 0 || n > (1ull << 30)) return 0;
+    return dedup_slots(n) * sizeof(uint32_t);
+}
+
+extern "C" int32_t eck_candidates_dedup(const uint16_t *genes, uint64_t ld, uint64_t n, int32_t n_genes, uint8_t *flags,
+                                        int32_t overwrite, void *ws, uint64_t ws_bytes, void *stream)
+{
+    if (!genes || !flags || n == 0 || n_genes < 1 || n_genes > ECK_MAX_GENES) return ECK_EINVAL;
+    if (ld < n) return ECK_ESHAPE;
+    if (n > (1ull << 30)) return ECK_EUNSUPPORTED;
+    const uint64_t slots = dedup_slots(n);
+    if (!ws || ws_bytes < slots * sizeof(uint32_t)) return ECK_EWORKSPACE;
+    if ((uintptr_t)ws & 3) return ECK_EALIGN;
+    uint32_t *table = static_cast<uint32_t *>(ws);
+    hipStream_t st = as_stream(stream);
+    const uint32_t mask = (uint32_t)(slots - 1);
+    hipLaunchKernelGGL(dedup_clear_kernel, dim3((unsigned)((slots + 255) / 256)), dim3(256), 0, st, table, slots);
+    hipLaunchKernelGGL(dedup_insert_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, genes, ld, (uint32_t)n,
+                       (int)n_genes, table, mask);
+    hipLaunchKernelGGL(dedup_mark_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, genes, ld, (uint32_t)n,
+                       (int)n_genes, table, mask, flags, (int)overwrite);
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
 }

@@ -19,7 +19,7 @@ ERROR_NAMES = {EINVAL: "ECK_EINVAL", ESHAPE: "ECK_ESHAPE", EUNSUPPORTED: "ECK_EU
                EWORKSPACE: "ECK_EWORKSPACE", EDEVICE: "ECK_EDEVICE"}
 OP_GEMM, OP_BGEMM, OP_CONV2D = 0, 1, 2
 SPACE_KNOB, SPACE_SPLIT = 0, 1
-MODE_EXHAUSTIVE, MODE_SAMPLE, MODE_MUTATE = 0, 1, 2
+MODE_EXHAUSTIVE, MODE_SAMPLE, MODE_MUTATE, MODE_CROSSOVER = 0, 1, 2, 3
 F32, BF16 = 0, 1
 SELECT_THRESHOLD, SELECT_RANK = 0, 1
 MAX_K = 4096
@@ -31,7 +31,8 @@ EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_in
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
            "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update",
            "eck_trees_create", "eck_trees_destroy", "eck_trees_count", "eck_trees_set", "eck_trees_get",
-           "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step"]
+           "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step",
+           "eck_candidates_dedup", "eck_candidates_dedup_workspace_bytes"]
 
 
 class EckError(RuntimeError):
@@ -82,6 +83,9 @@ def lib():
         L.eck_model_set_state.argtypes = [vp, vp, u64, vp]
         L.eck_model_get_state.argtypes = [vp, vp, u64, vp]
         L.costmodel_score.argtypes = [vp, vp, i32, u64, u64, vp, vp, u64, vp]
+        L.eck_candidates_dedup_workspace_bytes.argtypes = [u64]
+        L.eck_candidates_dedup_workspace_bytes.restype = u64
+        L.eck_candidates_dedup.argtypes = [vp, u64, u64, i32, vp, i32, vp, u64, vp]
         L.eck_k_step.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int64, C.POINTER(C.c_double)]
         L.eck_trees_create.argtypes = [i32, i32, i32, f32, C.POINTER(vp)]
         L.eck_trees_destroy.argtypes = [vp]
@@ -411,3 +415,19 @@ def k_step(k, snr, mu, M):
     out = C.c_double()
     _check("eck_k_step", lib().eck_k_step(k, snr, mu, M, C.byref(out)))
     return out.value
+
+
+def candidates_dedup_workspace_bytes(n):
+    return int(lib().eck_candidates_dedup_workspace_bytes(n))
+
+
+def candidates_dedup(genes, n, flags, overwrite=False, ws=None):
+    """flags[i] (uint8) = first occurrence of its gene tuple (AND-ed into flags unless overwrite)"""
+    assert genes.element_size() == 2 and genes.is_cuda and genes.is_contiguous()
+    assert flags.is_cuda and flags.element_size() == 1 and flags.numel() >= n
+    need = int(lib().eck_candidates_dedup_workspace_bytes(n))
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=genes.device)
+    _check("eck_candidates_dedup", lib().eck_candidates_dedup(
+        _ptr(genes), genes.shape[1], n, genes.shape[0], _ptr(flags), 1 if overwrite else 0, _ptr(ws),
+        ws.numel() * ws.element_size(), _stream()))

@@ -20,12 +20,13 @@ from . import eck
 class EnergySearch:
     def __init__(self, problem, kind, measure, population=1 << 14, M=64, n_parents=64, depth=6, init_rounds=40,
                  update_rounds=8, mu=20.0, k_min=0.2, eta=0.3, lam=1.0, p_mut_q32=429496729, seed=1,
-                 max_rounds=64):
+                 max_rounds=64, crossover=False, dedup=False):
         self.space = eck.Space(problem, kind)
         self.measure, self.N, self.M, self.P = measure, int(population), int(M), int(n_parents)
         self.init_rounds, self.update_rounds = int(init_rounds), int(update_rounds)
         self.mu, self.k_min, self.eta, self.lam = float(mu), float(k_min), float(eta), float(lam)
         self.p_mut, self.seed = int(p_mut_q32), int(seed)
+        self.crossover, self.dedup = bool(crossover), bool(dedup)
         G, N, dev = self.space.n_genes, self.N, "cuda"
         cap_trees = init_rounds + update_rounds * (max_rounds + 1)
         self.energy_model = eck.Trees(64, depth, cap_trees, 0.5)
@@ -39,6 +40,7 @@ class EnergySearch:
         self.e_sel = torch.zeros((1, self.M), dtype=torch.float32, device=dev)
         self.count = torch.zeros(1, dtype=torch.int32, device=dev)
         self.ws_topk = torch.empty(eck.topk_select_workspace_bytes(N, 1, self.M), dtype=torch.uint8, device=dev)
+        self.ws_dedup = torch.empty(eck.candidates_dedup_workspace_bytes(N), dtype=torch.uint8, device=dev) if dedup else None
         # everything measured so far: genes and features side by side, energies, in order of measurement
         self.cap = self.M * (max_rounds + 2)
         self.buf_genes = torch.zeros((G, self.cap), dtype=torch.int16, device=dev)
@@ -110,9 +112,11 @@ class EnergySearch:
     def step(self):
         self.round += 1
         r = self.round
-        eck.candidate_enumerate(self.space, eck.MODE_MUTATE, self.N, self.genes, seed=self.seed, round=r,
-                                parents=self.parents, p_mut_q32=self.p_mut)
+        eck.candidate_enumerate(self.space, eck.MODE_CROSSOVER if self.crossover else eck.MODE_MUTATE, self.N,
+                                self.genes, seed=self.seed, round=r, parents=self.parents, p_mut_q32=self.p_mut)
         eck.features_compute(self.space, self.genes, self.N, 64, eck.BF16, feat_out=self.feat, legal_out=self.legal)
+        if self.dedup:  # repeated children leave the selection (their first occurrence stays)
+            eck.candidates_dedup(self.genes, self.N, self.legal, ws=self.ws_dedup)
         eck.treemodel_score(self.latency_model, self.feat, self.N, self.l_pred)
         eck.treemodel_score(self.energy_model, self.feat, self.N, self.e_pred)
         want = max(1, int(np.floor(self.k * self.M + 0.5)))

@@ -94,6 +94,8 @@ def test_enumerate_and_features_validate_before_launch():
     assert E(sp.h, 0, 0, 0, 0, 16, None, 0, 0, C.c_void_p(0x1002), 16, None) == eck.EALIGN
     assert E(sp.h, 0, 0, 0, 6390, 16, None, 0, 0, FAKE, 16, None) == eck.EINVAL   # beyond the space
     assert E(sp.h, 2, 0, 0, 0, 16, None, 0, 0, FAKE, 16, None) == eck.EINVAL      # MUTATE without parents
+    assert E(sp.h, 3, 0, 0, 0, 16, None, 0, 0, FAKE, 16, None) == eck.EINVAL      # CROSSOVER without parents
+    assert E(sp.h, 4, 0, 0, 0, 16, FAKE, 4, 0, FAKE, 16, None) == eck.EINVAL      # no such mode
     F = L.features_compute
     assert F(sp.h, None, 16, 16, 32, 0, FAKE, None, None, None) == eck.EINVAL
     assert F(sp.h, FAKE, 16, 16, 32, 0, None, None, None, None) == eck.EINVAL
@@ -222,3 +224,18 @@ def test_k_controller_matches_the_oracle_and_validates():
     assert L.eck_k_step(1.5, 1.0, 10.0, 64, C.byref(out)) == eck.EINVAL
     assert L.eck_k_step(0.5, 1.0, 10.0, -1, C.byref(out)) == eck.EINVAL
     assert L.eck_k_step(0.5, 1.0, float("nan"), 64, C.byref(out)) == eck.EINVAL
+
+
+def test_dedup_validation():
+    L = eck.lib()
+    D = L.eck_candidates_dedup
+    assert L.eck_candidates_dedup_workspace_bytes(0) == 0
+    assert L.eck_candidates_dedup_workspace_bytes(1000) == 2048 * 4
+    assert L.eck_candidates_dedup_workspace_bytes((1 << 30) + 1) == 0
+    assert D(None, 16, 16, 5, FAKE, 1, FAKE, 1 << 20, None) == eck.EINVAL
+    assert D(FAKE, 16, 16, 5, None, 1, FAKE, 1 << 20, None) == eck.EINVAL
+    assert D(FAKE, 16, 0, 5, FAKE, 1, FAKE, 1 << 20, None) == eck.EINVAL
+    assert D(FAKE, 16, 16, 0, FAKE, 1, FAKE, 1 << 20, None) == eck.EINVAL
+    assert D(FAKE, 8, 16, 5, FAKE, 1, FAKE, 1 << 20, None) == eck.ESHAPE
+    assert D(FAKE, 16, 16, 5, FAKE, 1, FAKE, 16, None) == eck.EWORKSPACE
+    assert D(FAKE, 16, 16, 5, FAKE, 1, C.c_void_p(0x1001), 1 << 20, None) == eck.EALIGN

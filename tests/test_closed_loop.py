@@ -57,14 +57,24 @@ def test_simulated_meter_is_deterministic_and_positive():
     assert np.max(np.abs(np.log(e1 / e3))) < 0.3            # the same hardware, different noise
 
 
+def test_oracle_loop_with_crossover_and_dedup_never_measures_a_kernel_twice_in_a_round():
+    hist, _, _ = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, 4, mu=1e9, crossover=True, dedup=True, **KW)
+    sp = oracle.Space(_problem(), oracle.SPACE_SPLIT)
+    assert all(h["measured"] == 64 for h in hist)
+    plain, _, _ = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, 4, mu=1e9, **KW)
+    assert any(not np.array_equal(a["picked"], b["picked"]) for a, b in zip(hist[1:], plain[1:]))
+
+
 @pytest.mark.gpu
-def test_gpu_loop_reproduces_the_oracles_trajectory():
+@pytest.mark.parametrize("variant", [dict(), dict(crossover=True, dedup=True)])
+def test_gpu_loop_reproduces_the_oracles_trajectory(variant):
     import torch
     from paper_2411_18873_amd import eck
     from paper_2411_18873_amd.search import EnergySearch
     rounds, mu = 6, 1000.0
-    want, (w_nf, w_nt, w_lf), w_energy = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, rounds, mu=mu, **KW)
-    s = EnergySearch(_problem(), eck.SPACE_SPLIT, _measure, mu=mu, max_rounds=rounds, **KW)
+    want, (w_nf, w_nt, w_lf), w_energy = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, rounds, mu=mu,
+                                                         **KW, **variant)
+    s = EnergySearch(_problem(), eck.SPACE_SPLIT, _measure, mu=mu, max_rounds=rounds, **KW, **variant)
     s.initialise()
     for _ in range(rounds):
         s.step()

@@ -213,3 +213,68 @@ def test_batched_knob_spaces_and_single_space_batch(G):
         assert np.array_equal(feat.cpu().numpy()[:, s * n:(s + 1) * n].view(np.uint32), f32_o[:, :n].view(np.uint32))
     assert np.array_equal(one.cpu().numpy().view(np.uint16),
                           oracle.enumerate_candidates(refs[1], oracle.MODE_SAMPLE, n, seed=5))
+
+
+@pytest.mark.parametrize("p_mut", [synth.P_MUT_Q32, 0])
+def test_crossover(G, p_mut):
+    mine, ref = _spaces("c3", eck.SPACE_SPLIT)
+    parents = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, 100, seed=7)
+    n = (1 << 16) + 11
+    for rnd, first in [(1, 0), (5, 123457)]:
+        got = G.enumerate_gpu(mine, eck.MODE_CROSSOVER, n, seed=9, rnd=rnd, first_index=first, parents=parents,
+                              p_mut_q32=p_mut)
+        want = oracle.enumerate_candidates(ref, oracle.MODE_CROSSOVER, n, seed=9, rnd=rnd, first_index=first,
+                                           parents=parents, p_mut_q32=p_mut)
+        assert np.array_equal(got[:, :n], want)
+
+
+def test_crossover_batched_over_spaces(G):
+    import torch
+    problems = [synth.gemm(*s) for s in synth.sweep_shapes()[::21]]
+    mine = [eck.Space(pb, eck.SPACE_SPLIT) for pb in problems]
+    refs = [oracle.Space(pb, oracle.SPACE_SPLIT) for pb in problems]
+    S, n, P = len(problems), 2049, 17
+    parents = np.concatenate([oracle.enumerate_candidates(r, oracle.MODE_SAMPLE, P, seed=3 + s)
+                              for s, r in enumerate(refs)], axis=1)
+    ld = S * n + (S * n & 1)
+    genes = torch.full((mine[0].n_genes, ld), -1, dtype=torch.int16, device="cuda")
+    seeds = [40 + s for s in range(S)]
+    eck.candidate_enumerate_batch(mine, eck.MODE_CROSSOVER, n, genes, seeds, round=3, parents=G.to_dev(parents),
+                                  p_mut_q32=synth.P_MUT_Q32)
+    torch.cuda.synchronize()
+    got = genes.cpu().numpy().view(np.uint16)
+    for s, ref in enumerate(refs):
+        want = oracle.enumerate_candidates(ref, oracle.MODE_CROSSOVER, n, seed=seeds[s], rnd=3,
+                                           parents=parents[:, s * P:(s + 1) * P], p_mut_q32=synth.P_MUT_Q32)
+        assert np.array_equal(got[:, s * n:(s + 1) * n], want), "space %d" % s
+
+
+def test_dedup_marks_first_occurrences(G):
+    import torch
+    mine, ref = _spaces("c3", eck.SPACE_SPLIT)
+    parents = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, 8, seed=7)
+    n = 20000 + 1   # children of 8 parents with a low mutation rate: mostly repeats
+    kids = oracle.enumerate_candidates(ref, oracle.MODE_MUTATE, n, seed=1, rnd=1, parents=parents, p_mut_q32=1 << 28)
+    want = oracle.dedup(kids)
+    assert 0.02 < want.mean() < 0.9
+    genes = G.to_dev(np.concatenate([kids, kids[:, :1]], axis=1))      # ld = n + 1
+    flags = torch.full((n + 1,), 9, dtype=torch.uint8, device="cuda")
+    eck.candidates_dedup(genes, n, flags, overwrite=True)
+    torch.cuda.synchronize()
+    got = flags.cpu().numpy()
+    assert np.array_equal(got[:n], want) and got[n] == 9
+    # AND-ed into existing flags (e.g. legality)
+    legal = (np.arange(n) % 3 != 0).astype(np.uint8)
+    flags = torch.from_numpy(legal).cuda()
+    eck.candidates_dedup(genes, n, flags)
+    torch.cuda.synchronize()
+    assert np.array_equal(flags.cpu().numpy(), legal & want)
+    # all distinct and all equal
+    distinct = np.arange(5000, dtype=np.uint16)[None, :].repeat(2, axis=0)
+    flags = torch.zeros(5000, dtype=torch.uint8, device="cuda")
+    eck.candidates_dedup(G.to_dev(distinct), 5000, flags, overwrite=True)
+    same = np.zeros((6, 4096), dtype=np.uint16)
+    flags2 = torch.ones(4096, dtype=torch.uint8, device="cuda")
+    eck.candidates_dedup(G.to_dev(same), 4096, flags2, overwrite=True)
+    torch.cuda.synchronize()
+    assert flags.cpu().numpy().all() and list(flags2.cpu().numpy()[:3]) == [1, 0, 0] and flags2.sum().item() == 1

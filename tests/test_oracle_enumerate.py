@@ -161,3 +161,64 @@ def test_mutation_rate_and_inheritance():
     copies = oracle.enumerate_candidates(sp, oracle.MODE_MUTATE, 4096, seed=7, rnd=2, parents=parents, p_mut_q32=0)
     assert np.array_equal(copies, parents[:, np.arange(4096) % P])
     assert G == 6
+
+
+def test_crossover_follows_its_definition_from_the_hash():
+    """Every gene of a child is re-derived here from the independent SplitMix model: second parent from word 14,
+    source mask from word 15, mutation coin and value from the gene's own word."""
+    sp = oracle.Space(synth.CONFIGS["c3"]["problem"], oracle.SPACE_SPLIT)
+    P, n, seed, rnd, first, p_mut = 37, 3000, 7, 4, 1234567, synth.P_MUT_Q32
+    parents = oracle.enumerate_candidates(sp, oracle.MODE_SAMPLE, P, seed=3)
+    kids = oracle.enumerate_candidates(sp, oracle.MODE_CROSSOVER, n, seed=seed, rnd=rnd, first_index=first,
+                                       parents=parents, p_mut_q32=p_mut)
+    key = _mix((seed + GOLDEN_GAMMA * (rnd + 1)) & M64)
+    word = lambda c, g: _splitmix_output(key, 16 * c + g + 1)
+    for i in range(0, n, 7):
+        c = first + i
+        pa, pb = c % P, ((word(c, 14) & 0xFFFFFFFF) * P) >> 32
+        mask = word(c, 15)
+        for g in range(sp.n_genes):
+            u = word(c, g)
+            want = parents[g, pb if (mask >> g) & 1 else pa]
+            if (u >> 32) < p_mut:
+                want = ((u & 0xFFFFFFFF) * sp.radix[g]) >> 32
+            assert kids[g, i] == want
+
+
+def test_crossover_statistics_and_degenerate_cases():
+    sp = oracle.Space(synth.CONFIGS["c3"]["problem"], oracle.SPACE_SPLIT)
+    P, n = 64, 1 << 15
+    parents = oracle.enumerate_candidates(sp, oracle.MODE_SAMPLE, P, seed=11)
+    assert len({tuple(parents[:, j]) for j in range(P)}) == P
+    kids = oracle.enumerate_candidates(sp, oracle.MODE_CROSSOVER, n, seed=5, rnd=1, parents=parents, p_mut_q32=0)
+    # without mutation every gene is one of the two parents' genes, about half of them the second parent's
+    pa = np.arange(n) % P
+    from_a = kids == parents[:, pa]
+    others = ~from_a
+    assert 0.40 < others.mean() < 0.52        # a little under 1/2: the two parents sometimes agree on a gene
+    for g in range(sp.n_genes):
+        assert set(np.unique(kids[g])) <= set(np.unique(parents[g]))
+    # one parent only: crossover has nothing to mix, children are copies
+    one = parents[:, :1].copy()
+    kids1 = oracle.enumerate_candidates(sp, oracle.MODE_CROSSOVER, 100, seed=5, rnd=1, parents=one, p_mut_q32=0)
+    assert np.all(kids1 == one)
+    # with mutation, the mutated fraction per gene is p (1 - P(redraw equals the inherited value))
+    kids_m = oracle.enumerate_candidates(sp, oracle.MODE_CROSSOVER, n, seed=5, rnd=1, parents=parents,
+                                         p_mut_q32=synth.P_MUT_Q32)
+    changed = (kids_m != kids).mean(axis=1)
+    assert np.all(changed < 0.1 + 0.01) and np.all(changed > 0.1 * (1 - 1 / 4) - 0.02)
+
+
+def test_dedup_keeps_first_occurrences_like_numpy_unique():
+    rng = np.random.default_rng(2)
+    genes = rng.integers(0, 3, size=(4, 2000)).astype(np.uint16)      # 81 distinct tuples, many repeats
+    keep = oracle.dedup(genes)
+    _, first = np.unique(genes.T, axis=0, return_index=True)
+    want = np.zeros(2000, dtype=np.uint8)
+    want[first] = 1
+    assert np.array_equal(keep, want) and keep.sum() == 81
+    assert np.all(oracle.dedup(np.arange(50, dtype=np.uint16)[None, :]) == 1)
+    same = np.zeros((3, 10), dtype=np.uint16)
+    assert list(oracle.dedup(same)) == [1] + [0] * 9
+    # n < ld: columns past n are ignored
+    assert list(oracle.dedup(same, n=4)) == [1, 0, 0, 0]
