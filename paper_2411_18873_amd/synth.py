@@ -68,6 +68,22 @@ CONFIGS = {
 }
 
 
+def paper_operators(hw=HW_MI355X):
+    """The operator shapes of the paper's evaluation (Sec. 7.2), as problems of this library.  MM / MV are
+    (batch, M, N, K): batch 1 is a GEMM, batch 8 a batched GEMM, MV has M = 1.  CONV is (batch, height, width,
+    in channels, out channels, kernel, stride, padding).  MV1's N is taken as printed (49512)."""
+    ops = {
+        "MM1": gemm(512, 512, 512, hw=hw), "MM2": gemm(1024, 1024, 1024, hw=hw),
+        "MM3": bgemm(8, 512, 512, 512, hw=hw), "MM4": bgemm(8, 1024, 1024, 1024, hw=hw),
+        "MV1": gemm(1, 49512, 12288, hw=hw), "MV2": gemm(1, 32768, 16384, hw=hw),
+        "MV3": bgemm(8, 1, 4096, 1024, hw=hw), "MV4": bgemm(8, 1, 8192, 2048, hw=hw),
+        "CONV1": conv2d(8, 512, 512, 7, 7, 3, 3, 1, 1, hw=hw),
+        "CONV2": conv2d(16, 64, 64, 56, 56, 1, 1, 1, 0, hw=hw),
+        "CONV3": conv2d(64, 64, 64, 56, 56, 1, 1, 1, 0, hw=hw),
+    }
+    return ops
+
+
 def round_to_bf16(x):
     """fp32 array -> nearest-even bf16 value, returned as fp32 (finite inputs)."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)

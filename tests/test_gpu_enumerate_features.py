@@ -278,3 +278,15 @@ def test_dedup_marks_first_occurrences(G):
     eck.candidates_dedup(G.to_dev(same), 4096, flags2, overwrite=True)
     torch.cuda.synchronize()
     assert flags.cpu().numpy().all() and list(flags2.cpu().numpy()[:3]) == [1, 0, 0] and flags2.sum().item() == 1
+
+
+def test_paper_operator_shapes(G):
+    """The eleven operators of the paper's evaluation (Sec. 7.2: MM1-4, MV1-4, CONV1-3): sampled schedules,
+    all 64 features, both output types, bit for bit."""
+    for i, (name, pb) in enumerate(synth.paper_operators().items()):
+        mine, ref = _spaces(pb, eck.SPACE_SPLIT)
+        n = 3001
+        got = G.enumerate_gpu(mine, eck.MODE_SAMPLE, n, seed=300 + i)
+        want = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, n, seed=300 + i)
+        assert np.array_equal(got[:, :n], want), name
+        _check_features(G, mine, ref, want, 64)

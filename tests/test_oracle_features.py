@@ -190,3 +190,19 @@ def test_feature_matrix_outputs_are_consistent():
         bad = genes.copy()
         bad[1, 0] = 165
         oracle.features(sp, bad, 64)
+
+
+def test_paper_operator_shapes_have_the_closed_form_work():
+    """The eleven operators of the paper's evaluation (Sec. 7.2): useful flop 2BMNK (MM, MV) and
+    2 N K Ho Wo C R S (CONV), whatever the schedule."""
+    want = {"MM1": 2 * 512 ** 3, "MM2": 2 * 1024 ** 3, "MM3": 2 * 8 * 512 ** 3, "MM4": 2 * 8 * 1024 ** 3,
+            "MV1": 2 * 49512 * 12288, "MV2": 2 * 32768 * 16384, "MV3": 2 * 8 * 4096 * 1024, "MV4": 2 * 8 * 8192 * 2048,
+            "CONV1": 2 * 8 * 512 * 7 * 7 * 512 * 9, "CONV2": 2 * 16 * 64 * 56 * 56 * 64, "CONV3": 2 * 64 * 64 * 56 * 56 * 64}
+    ops = synth.paper_operators()
+    assert set(ops) == set(want)
+    for name, pb in ops.items():
+        sp = oracle.Space(pb, oracle.SPACE_SPLIT)
+        genes = oracle.enumerate_candidates(sp, oracle.MODE_SAMPLE, 64, seed=3)
+        raw, _, _, _ = oracle.features(sp, genes, 64)
+        assert np.all(raw[0] == want[name]), name
+        assert np.all(raw[1] == raw[0]), name          # exact factorisations: executed = useful
