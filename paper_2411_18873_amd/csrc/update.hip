@@ -131,11 +131,19 @@ __device__ __forceinline__ uint16_t to_bf16_bits(float x)
     return (uint16_t)(u >> 16);
 }
 
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g)
+// The reduction dimension is also split inside the block: KG groups of four wavefronts take every KG-th
+// stage each (these products are latency-bound -- 64 blocks, 8 dependent stages), and their partial tiles
+// are added through LDS in group order, so the result does not depend on scheduling.
+constexpr int KG = 2;
+constexpr size_t GEMM_MFMA_LDS = (size_t)KG * (TM + TN) * MLD * sizeof(uint16_t);
+static_assert((KG - 1) * TM * TN * sizeof(float) <= GEMM_MFMA_LDS, "partial tiles reuse the operand buffers");
+
+__global__ __launch_bounds__(256 * KG) void gemm_mfma_kernel(GemmArgs g)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t As[TM * MLD]; // [m][k]
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[TN * MLD]; // [n][k]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
+    const int group = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+    uint16_t *As = reinterpret_cast<uint16_t *>(gemm_lds) + (size_t)group * (TM + TN) * MLD; // [m][k]
+    uint16_t *Bs = As + TM * MLD;                                                            // [n][k]
     const int h = lane >> 5, c = lane & 31;
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
     const int wm = (wave >> 1) * 32, wn = (wave & 1) * 32; // quadrant of this wavefront
@@ -184,11 +192,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g)
     f32x16 acc;
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
-    fetch(0);
-    for (int k0 = 0; k0 < g.K; k0 += MK) {
+    // every group runs the same number of rounds (stages past K read as zero), so the barriers match
+    const int n_stages = (g.K + MK - 1) / MK, rounds = (n_stages + KG - 1) / KG;
+    fetch(group * MK);
+    for (int r = 0; r < rounds; ++r) {
         stage();
         __syncthreads();
-        if (k0 + MK < g.K) fetch(k0 + MK);
+        if (r + 1 < rounds) fetch(((r + 1) * KG + group) * MK);
 #pragma unroll
         for (int ks = 0; ks < MK / 16; ++ks) {
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(&As[(wm + c) * MLD + 16 * ks + 8 * h]);
@@ -197,6 +207,18 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g)
         }
         __syncthreads();
     }
+    // partial tiles of groups 1 .. KG-1 through LDS, added by group 0 in group order
+    float *partial = reinterpret_cast<float *>(gemm_lds); // [KG-1][4 wavefronts][16][64 lanes]
+    if (group > 0) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) partial[(((group - 1) * 4 + wave) * 16 + q) * 64 + lane] = acc[q];
+    }
+    __syncthreads();
+    if (group > 0) return;
+#pragma unroll
+    for (int other = 0; other < KG - 1; ++other)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[q] += partial[((other * 4 + wave) * 16 + q) * 64 + lane];
     // accumulator register q of lane (h, c): row 8*(q/4) + 4h + q%4, column c of the quadrant
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
@@ -410,7 +432,15 @@ UpdWs upd_layout(const eck_model *m, uint64_t n_pairs, int mb)
 void launch_gemm(const GemmArgs &g, hipStream_t st, bool matrix_cores = false)
 {
     const dim3 grid((g.N + TN - 1) / TN, (g.M + TM - 1) / TM);
-    if (matrix_cores) hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256), 0, st, g);
+    if (matrix_cores) {
+        static bool lds_set = false; // the kernel needs more LDS than the default dynamic limit
+        if (!lds_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_mfma_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_MFMA_LDS);
+            lds_set = true;
+        }
+        hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256 * KG), GEMM_MFMA_LDS, st, g);
+    }
     else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, st, g);
 }
 
