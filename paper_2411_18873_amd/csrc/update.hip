@@ -433,12 +433,9 @@ void launch_gemm(const GemmArgs &g, hipStream_t st, bool matrix_cores = false)
 {
     const dim3 grid((g.N + TN - 1) / TN, (g.M + TM - 1) / TM);
     if (matrix_cores) {
-        static bool lds_set = false; // the kernel needs more LDS than the default dynamic limit
-        if (!lds_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_mfma_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_MFMA_LDS);
-            lds_set = true;
-        }
+        // set per call: the attribute belongs to the current device
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_mfma_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_MFMA_LDS);
         hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256 * KG), GEMM_MFMA_LDS, st, g);
     }
     else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, st, g);
