@@ -127,13 +127,16 @@ int32_t launch_score(const eck_trees *m, int n_trees, const void *feat, int32_t 
     if (tiles64 > 0xFFFFFFFFull) return ECK_EUNSUPPORTED;
     const size_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
     const size_t x_bytes = (size_t)m->n_feat * BLOCK * elem;
-    // trees per chunk: what fits beside the feature tile in 72 KB (two blocks per compute unit), else in
-    // 150 KB; a multiple of the number of simultaneous walks
+    // Trees per chunk.  The walks are chains of dependent LDS reads, so what counts is how many wavefronts a
+    // compute unit holds: the smallest chunk (one group of simultaneous walks) beside the feature tile lets
+    // the most blocks share the 160 KB; blocks per unit = what fits, chunk = what is left of a block's share.
     const size_t per_tree = tree_lds_bytes(m->depth);
-    size_t budget = 72 * 1024;
-    if (x_bytes + WALKS * per_tree > budget) budget = 150 * 1024;
-    if (x_bytes + WALKS * per_tree > budget) return ECK_EUNSUPPORTED;
-    int chunk = (int)((budget - x_bytes) / per_tree);
+    const size_t lds_cu = 156 * 1024, floor_bytes = x_bytes + WALKS * per_tree;
+    if (floor_bytes > lds_cu) return ECK_EUNSUPPORTED;
+    size_t blocks_cu = lds_cu / floor_bytes;
+    if (blocks_cu > 8) blocks_cu = 8; // 2048 threads per unit
+    const size_t share = lds_cu / blocks_cu;
+    int chunk = (int)((share - x_bytes) / per_tree);
     chunk -= chunk % WALKS;
     const int rounded = (n_trees + WALKS - 1) / WALKS * WALKS;
     if (n_trees > 0 && chunk > rounded) chunk = rounded;
@@ -142,7 +145,7 @@ int32_t launch_score(const eck_trees *m, int n_trees, const void *feat, int32_t 
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device);
     const uint32_t n_tiles = (uint32_t)tiles64;
-    const uint32_t want = (uint32_t)cus * (lds <= 72 * 1024 ? 2u : 1u);
+    const uint32_t want = (uint32_t)cus * (uint32_t)blocks_cu;
     const uint32_t grid = n_tiles < want ? n_tiles : want;
     auto kern = feat_dtype == ECK_BF16 ? tree_score_kernel<true> : tree_score_kernel<false>;
     ECK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
