@@ -76,8 +76,8 @@ def main():
                     help="profiling aid: after set-up run only this call of the step (prints a short JSON)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (candidates are independent and would shard by shape; "
-              "see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (candidates are independent and would shard by shape, with only "
+              "the per-segment selection exchanging a few KB). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

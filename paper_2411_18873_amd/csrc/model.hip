@@ -776,7 +776,13 @@ extern "C" int32_t costmodel_score(const eck_model *m, const void *feat, int32_t
     }
     if (feat_dtype == ECK_BF16 && (ld & 1)) return ECK_EALIGN;
     if (F == 64 && H1 == 512 && H2 == 512) return launch_bf16<64, 512, 512, 2>(m, feat, feat_dtype, ld, n, score_out, st);
+    // 256 hidden units leave room for four candidate tiles per wavefront (half the weight traffic per candidate)
+    // when the features arrive as bf16; fp32 features need the registers for themselves
+    if (F == 64 && H1 == 256 && H2 == 256 && feat_dtype == ECK_BF16)
+        return launch_bf16<64, 256, 256, 4>(m, feat, feat_dtype, ld, n, score_out, st);
     if (F == 64 && H1 == 256 && H2 == 256) return launch_bf16<64, 256, 256, 2>(m, feat, feat_dtype, ld, n, score_out, st);
+    if (F == 64 && H1 == 128 && H2 == 128 && feat_dtype == ECK_BF16)
+        return launch_bf16<64, 128, 128, 4>(m, feat, feat_dtype, ld, n, score_out, st);
     if (F == 64 && H1 == 128 && H2 == 128) return launch_bf16<64, 128, 128, 2>(m, feat, feat_dtype, ld, n, score_out, st);
     if (F == 32 && H1 == 64 && H2 == 64) return launch_bf16<32, 64, 64, 2>(m, feat, feat_dtype, ld, n, score_out, st);
     return ECK_EUNSUPPORTED;
