@@ -104,3 +104,27 @@ def test_repeatable(G):
     a = G.topk_gpu(e, lat, None, 4, 512)
     b = G.topk_gpu(e, lat, None, 4, 512)
     _same(a, b)
+
+
+def test_scalar_and_vector_streaming_paths_agree_with_the_oracle(G):
+    """The streaming kernels read four candidates per load when segment length and pointers allow it and one
+    per load otherwise: odd segment lengths, and score / flag arrays that start one element into an allocation,
+    take the scalar path at a size that spans many blocks; the result is the oracle's either way."""
+    import torch
+    S, seg = 3, 123457                                   # odd segment length
+    n = S * seg
+    e = synth.gaussian_scores(n, 11, ties=0.2, quantum=0.01)
+    lat = synth.gaussian_scores(n, 12) * 0.3 + 2.0
+    legal = synth.legal_mask(n, 13, 0.5)
+    want = oracle.topk(e, lat, legal, S, 200, alpha=1.1)
+    _same(G.topk_gpu(e, lat, legal, S, 200, alpha=1.1), want)
+    # aligned length, misaligned pointers: views that start at element 1
+    n2 = 1 << 18
+    e2, l2, g2 = e[:n2], lat[:n2], legal[:n2]
+    want2 = oracle.topk(e2, l2, g2, 4, 77, alpha=1.1)
+    pad_f = lambda a: torch.cat([torch.zeros(1, dtype=torch.float32), torch.from_numpy(a.copy())]).cuda()[1:]
+    pad_b = torch.cat([torch.zeros(1, dtype=torch.uint8), torch.from_numpy(g2.copy())]).cuda()[1:]
+    assert pad_f(e2).data_ptr() % 16 != 0
+    _same(G.topk_dev(pad_f(e2), pad_f(l2), pad_b, 4, 77, alpha=1.1), want2)
+    # and the aligned (vector) path on the same data
+    _same(G.topk_gpu(e2, l2, g2, 4, 77, alpha=1.1), want2)
