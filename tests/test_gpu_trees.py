@@ -212,3 +212,27 @@ def test_tree_scores_at_the_benchmark_size(G):
     got = out.cpu().numpy()
     assert np.isfinite(got).all()
     assert np.array_equal(got[cols], want.astype(np.float32))
+
+
+def test_held_out_accuracy_on_the_simulated_meter(G):
+    """The paper's accuracy check (Sec. 7.3: thousands of measured kernels, 80 % to train, 20 % to test,
+    normalised prediction against normalised measurement close to a straight line), on the simulated meter:
+    trees boosted on 3277 kernels of config 2's space predict the other 819."""
+    n, n_train = 4096, 3277
+    f32, b16, _ = _pairs(n)
+    energy, _ = synth.simulated_kernel_metrics(f32[:, :n], 21, 0)
+    feat = G.bf16_dev(b16)
+    trees = eck.Trees(64, 6, 100, 0.5)
+    train = torch.from_numpy(energy[:n_train].copy()).cuda()
+    snr = torch.zeros(1, dtype=torch.float32, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(eck.treemodel_update_workspace_bytes(trees, n_train), dtype=torch.uint8, device="cuda")
+    eck.treemodel_update(trees, feat, train, 100, snr, loss, ws, eta=0.3, lam=1.0)
+    pred = _score(trees, feat, n)
+    y = energy / energy[:n_train].max()
+    held = slice(n_train, n)
+    r = np.corrcoef(pred[held], y[held])[0, 1]
+    slope = np.polyfit(y[held], pred[held], 1)[0]
+    print("held-out: r = %.4f, slope = %.3f, train loss = %.2e" % (r, slope, float(loss.item())))
+    assert r > 0.95 and 0.8 < slope < 1.1
+    assert np.corrcoef(pred[:n_train], y[:n_train])[0, 1] > r      # fits the training set better, as it must
