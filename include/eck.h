@@ -26,6 +26,11 @@
  *     array is at base + r*ld elements, candidate i at column i, ld >= n.
  *   - There is no CPU fallback: without a usable GPU the compute calls return
  *     ECK_EDEVICE.
+ *   - Handles (eck_space, eck_model, eck_trees) belong to the device that was
+ *     current when they were created and are not synchronised internally: a
+ *     space uploads its tables on first use, models change under update calls.
+ *     Calls on one handle from several host threads must be serialised by the
+ *     caller; different handles are independent.
  */
 #ifndef ECK_H
 #define ECK_H
