@@ -32,9 +32,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 //
 // Packed buffer of a BF16 model (byte offsets 16-aligned):
 //   W1 fragments   [H1/32][F/16][64 lanes][8 bf16]
-//   b1 fragments   [H1/32][64 lanes][8 bf16]: one extra k-step of layer 1 whose only non-zero k slot
-//                  (lane half 0, slot 0) holds b1 -- multiplied by a constant-one activation it adds the
-//                  bias inside the matrix unit instead of with 32 vector moves per tile
+//   b1             [H1/32][2][16] fp32 in D-register order: a chunk's first matrix instruction takes its 16
+//                  values as the C operand, so the bias costs neither a vector instruction nor a k-step
 //   W2 fragments   [H2/32][H1/16][64 lanes][8 bf16]   (k permuted as above)
 //   b2 [H2/32][2][16] fp32, w3 [H2/32][2][16] fp32   (D-register order), b3 (1 float, padded to 4)
 
@@ -52,7 +51,7 @@ PackedLayout packed_layout(int F, int H1, int H2)
     PackedLayout L;
     L.w1 = 0;
     L.w1b = L.w1 + (uint64_t)F * H1 * 2;
-    L.w2 = L.w1b + (uint64_t)(H1 / 32) * 1024;
+    L.w2 = L.w1b + (uint64_t)H1 * 4;
     L.b2 = L.w2 + (uint64_t)H1 * H2 * 2;
     L.w3 = L.b2 + (uint64_t)H2 * 4;
     L.b3 = L.w3 + (uint64_t)H2 * 4;
@@ -79,7 +78,7 @@ __global__ void pack_kernel(const float *__restrict__ theta, int F, int H1, int 
                             uint64_t off_w2, uint64_t off_b2, uint64_t off_w3, uint64_t off_b3,
                             unsigned char *__restrict__ packed, PackedLayout L)
 {
-    const uint32_t n_w1 = F * H1, n_w1b = (H1 / 32) * 512, n_w2 = H1 * H2;
+    const uint32_t n_w1 = F * H1, n_w1b = H1, n_w2 = H1 * H2;
     const uint32_t total = n_w1 + n_w1b + n_w2 + 2 * H2 + 1;
     for (uint32_t e = blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gridDim.x * blockDim.x) {
         if (e < n_w1) {
@@ -91,9 +90,8 @@ __global__ void pack_kernel(const float *__restrict__ theta, int F, int H1, int 
             reinterpret_cast<uint16_t *>(packed + L.w1)[e] = bf16_bits(theta[off_w1 + (uint64_t)k * H1 + unit]);
         } else if (e < n_w1 + n_w1b) {
             const uint32_t x = e - n_w1;
-            const uint32_t t = x & 7, lane = (x >> 3) & 63, oc = x >> 9;
-            const bool holds_bias = t == 0 && lane < 32;
-            reinterpret_cast<uint16_t *>(packed + L.w1b)[x] = holds_bias ? bf16_bits(theta[off_b1 + 32 * oc + lane]) : (uint16_t)0;
+            const uint32_t q = x & 15, h = (x >> 4) & 1, chunk = x >> 5;
+            reinterpret_cast<float *>(packed + L.w1b)[x] = round_through_bf16(theta[off_b1 + unit_of_dreg(chunk, h, q)]);
         } else if (e < n_w1 + n_w1b + n_w2) {
             const uint32_t x = e - n_w1 - n_w1b;
             const uint32_t t = x & 7, lane = (x >> 3) & 63, frag = x >> 9;
@@ -318,7 +316,7 @@ __device__ __forceinline__ bf16x8 park_in_acc(bf16x8 v)
 // One block = 4 wavefronts; a wavefront carries NC tiles of 32 candidates
 // through all three layers in registers: lane (h, col) owns candidates
 // base + NC*col + c, c < NC (consecutive in memory, so one 4- or 8-byte load per
-// feature row serves all of a lane's columns).  W1 (with its bias fragments) and
+// feature row serves all of a lane's columns).  W1 (with b1) and
 // the b2 / w3 vectors stay in LDS for the block's lifetime.  W2 streams through
 // a ring of four LDS slots in pieces of half an output chunk (32 units x H1/2
 // inputs), shared by the four wavefronts and written into LDS directly by the
@@ -452,14 +450,14 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     constexpr int RING = KSP < 4 ? KSP : 4;          // weight fragments held in registers
     constexpr int PF = RING - 1;                     // LDS read-ahead in k-steps
     constexpr int N_DMA = KSP / 4 > 0 ? KSP / 4 : 1; // 1 KB fetches per wavefront per piece
-    constexpr uint32_t W1_BYTES = F * H1 * 2, W1B_BYTES = OC1 * 1024, PIECE_BYTES = KSP * 1024;
+    constexpr uint32_t W1_BYTES = F * H1 * 2, W1B_BYTES = H1 * 4, PIECE_BYTES = KSP * 1024;
     static_assert(KS2 % 2 == 0 && KSP % RING == 0 && OC2 % 2 == 0 && PIECES % 4 == 0, "unsupported shape");
     static_assert(NC == 2 || NC == 4, "unsupported tile width");
     static_assert(N_DMA + NXLOADS < 63, "outstanding loads must fit the load counter");
     using Raw = RawFeat<NC, FEAT_BF16>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const bf16x8 *lds_w1 = reinterpret_cast<const bf16x8 *>(lds);
-    const bf16x8 *lds_w1b = reinterpret_cast<const bf16x8 *>(lds + W1_BYTES);
+    const float *lds_b1 = reinterpret_cast<const float *>(lds + W1_BYTES); // [OC1][2][16], D-register order
     unsigned char *lds_ring = lds + W1_BYTES + W1B_BYTES; // four slots of PIECE_BYTES; piece p uses slot p & 3
     float *lds_b2 = reinterpret_cast<float *>(lds_ring + 4 * PIECE_BYTES);
     float *lds_w3 = lds_b2 + H2;
@@ -523,23 +521,15 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         fetch_piece(2);
         load_tile(blockIdx.x, raw);
     }
-    // resident part: W1 fragments, bias fragments and the two vectors
+    // resident part: W1 fragments, b1 and the two vectors of the output side
     {
-        const uint4 *src = reinterpret_cast<const uint4 *>(packed + L.w1); // w1 and its bias fragments are contiguous
+        const uint4 *src = reinterpret_cast<const uint4 *>(packed + L.w1); // w1 and b1 are contiguous
         uint4 *dst = reinterpret_cast<uint4 *>(lds);
         for (uint32_t i = tid; i < (W1_BYTES + W1B_BYTES) / 16; i += 256) dst[i] = src[i];
         const float *vb = reinterpret_cast<const float *>(packed + L.b2);
         for (uint32_t i = tid; i < (uint32_t)(2 * H2); i += 256) lds_b2[i] = vb[i]; // b2 and w3 are contiguous
     }
     const float b3 = *reinterpret_cast<const float *>(packed + L.b3);
-    // the constant-one activation that multiplies the bias fragments: k slot 0 of lane half 0
-    bf16x8 x_one;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) x_one[t] = (__bf16)0.0f;
-    if (h == 0) x_one[0] = (__bf16)1.0f;
-    f32x16 zero16;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) zero16[j] = 0.0f;
     __syncthreads();
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -576,24 +566,25 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                     h1[c][2 * oc + half] = park_in_acc(__builtin_bit_cast(bf16x8, words));
                 }
         };
-        bf16x8 a1[2][KS1 + 1]; // weight + bias fragments of two chunks: one in use, one on its way from LDS
+        bf16x8 a1[2][KS1]; // weight fragments of two chunks: one in use, one on its way from LDS
+        f32x16 b1c[2];     // and their bias in accumulator order
         auto load_chunk = [&](int oc) {
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks) a1[oc & 1][ks] = lds_w1[(oc * KS1 + ks) * 64 + lane];
-            a1[oc & 1][KS1] = lds_w1b[oc * 64 + lane];
+            b1c[oc & 1] = *reinterpret_cast<const f32x16 *>(lds_b1 + (oc * 2 + h) * 16);
         };
         load_chunk(0);
 #pragma unroll
         for (int oc = 0; oc < OC1; ++oc) {
             f32x16(&acc)[NC] = acc1[oc & 1];
-            const bf16x8(&a)[KS1 + 1] = a1[oc & 1];
+            const bf16x8(&a)[KS1] = a1[oc & 1];
+            const f32x16 bias = b1c[oc & 1];
             if (oc + 1 < OC1) load_chunk(oc + 1);
-#pragma unroll
-            for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[KS1], x_one, zero16, 0, 0, 0);
 #pragma unroll
             for (int ks = 0; ks < KS1; ++ks)
 #pragma unroll
-                for (int c = 0; c < NC; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], x[c][ks], acc[c], 0, 0, 0);
+                for (int c = 0; c < NC; ++c)
+                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], x[c][ks], ks == 0 ? bias : acc[c], 0, 0, 0);
 #pragma unroll
             for (int c = 0; c < NC; ++c) keep_in_vgprs(acc[c]);
             if (oc > 0) convert_chunk(oc - 1, acc1[(oc - 1) & 1]);
@@ -732,8 +723,8 @@ int32_t launch_bf16(const eck_model *m, const void *feat, int32_t feat_dtype, ui
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device);
     const uint32_t grid = n_tiles < (uint32_t)cus ? n_tiles : (uint32_t)cus;
-    // W1 + its bias fragments, four ring slots of half a W2 chunk, b2 and w3
-    const size_t lds = (size_t)F * H1 * 2 + (H1 / 32) * 1024 + 4 * (size_t)(H1 / 32) * 1024 + 2 * H2 * 4;
+    // W1 and b1, four ring slots of half a W2 chunk, b2 and w3
+    const size_t lds = (size_t)F * H1 * 2 + (size_t)H1 * 4 + 4 * (size_t)(H1 / 32) * 1024 + 2 * H2 * 4;
     // the per-lane part of a feature address is a 32-bit offset unless eight rows exceed it
     const uint64_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
     const bool wide = 8 * ld * elem > 0xFFFFFFFFull - TILE * elem;
