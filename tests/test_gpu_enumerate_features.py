@@ -290,3 +290,45 @@ def test_paper_operator_shapes(G):
         want = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, n, seed=300 + i)
         assert np.array_equal(got[:, :n], want), name
         _check_features(G, mine, ref, want, 64)
+
+
+def test_features_random_problems(G):
+    """Seeded random operators across the library's accepted range (both space kinds, all three operator
+    classes, both element sizes, odd extents, strides and paddings): whatever the oracle accepts the library
+    must accept, and every raw feature, transformed feature and legality flag must agree."""
+    rng = np.random.default_rng(2024)
+    dims = [1, 2, 3, 7, 12, 30, 64, 100, 255, 256, 500, 1024, 2047, 4096]
+    checked = 0
+    for trial in range(60):
+        kind_op = rng.integers(0, 4)
+        eb = int(rng.choice([2, 4]))
+        hw = synth.HW_MI355X if trial % 3 else synth.HW_CASE_STUDY
+        if kind_op == 0:
+            pb, kind = synth.gemm(*(int(rng.choice(dims)) for _ in range(3)), elem_bytes=eb, hw=hw), eck.SPACE_KNOB
+        elif kind_op == 1:
+            pb, kind = synth.gemm(*(int(rng.choice(dims)) for _ in range(3)), elem_bytes=eb, hw=hw), eck.SPACE_SPLIT
+        elif kind_op == 2:
+            pb = synth.bgemm(int(rng.choice([2, 3, 8, 32])), *(int(rng.choice(dims[:12])) for _ in range(3)),
+                             elem_bytes=eb, hw=hw)
+            kind = eck.SPACE_SPLIT if trial % 2 else eck.SPACE_KNOB
+        else:
+            r, s_ = int(rng.choice([1, 3, 5])), int(rng.choice([1, 3]))
+            pb = synth.conv2d(int(rng.choice([1, 2, 8])), int(rng.choice([3, 16, 64, 96])), int(rng.choice([8, 32, 100])),
+                              int(rng.choice([7, 14, 28, 57])), int(rng.choice([7, 14, 30])), r, s_,
+                              int(rng.choice([1, 2])), int(rng.choice([0, 1, 2])), elem_bytes=eb, hw=hw)
+            kind = eck.SPACE_SPLIT
+        try:
+            ref = oracle.Space(pb, kind)
+        except Exception:
+            continue                                   # outside the accepted range on the oracle's side too
+        try:
+            mine = eck.Space(pb, kind)
+        except eck.EckError:
+            continue                                   # the library's range limits are tighter in places
+        assert mine.radix == ref.radix
+        n = int(min(ref.size, 1500)) if ref.size else 1500
+        mode = oracle.MODE_EXHAUSTIVE if ref.size and ref.size <= 1500 else oracle.MODE_SAMPLE
+        genes = oracle.enumerate_candidates(ref, mode, n, seed=trial)
+        _check_features(G, mine, ref, genes, 64)
+        checked += 1
+    assert checked >= 40
