@@ -17,6 +17,8 @@ FLAGS = [
     # matrix instructions accumulate in the architectural register file (the form whose results ordinary
     # vector instructions can read without a copy); the score kernel parks activations in the other file
     "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+    # the hand-issued direct-to-LDS loads name M0 as clobbered on purpose
+    "-Wno-inline-asm",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 
