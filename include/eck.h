@@ -59,7 +59,15 @@ extern "C" {
                              unroll in {1,2,4,8}, vec in {1,2,4,8}; GEMM/BGEMM only */
 #define ECK_SPACE_SPLIT 1 /* one gene per split axis (index into the table of ordered 4-way factorisations of
                              the axis extent, lexicographic), then unroll in {1,2,4,8,16}, vec in {1,2,4,8}.
-                             Axis order: GEMM (M,N,K); BGEMM (B,M,N,K); CONV2D (N,K,H_out,W_out,C) */
+                             Axis order: GEMM (M,N,K); BGEMM (B,M,N,K); CONV2D (N,K,H_out,W_out,C).
+                             The reduction axis is staged through shared memory: f0 = stage loop,
+                             f1*f2*f3 = elements per stage */
+#define ECK_SPACE_SPLIT_XRED 2 /* the same genes and tables as SPLIT, read as a schedule that splits the
+                             reduction across threads (the shape reduction-dominated operators need, such as
+                             the matrix-vector products of Sec. 7.2): reduction axis f0 = stage loop,
+                             f1 = threads sharing one output's reduction, f2*f3 = serial per thread; no
+                             staging, every thread loads its own slice; the f1 partial sums of an output are
+                             folded by a halving tree in shared memory (fp32).  Same 64 feature slots */
 
 /* enumeration modes */
 #define ECK_MODE_EXHAUSTIVE 0

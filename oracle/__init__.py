@@ -16,7 +16,7 @@ _SRC = os.path.join(_HERE, "eck_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 OP_GEMM, OP_BGEMM, OP_CONV2D = 0, 1, 2
-SPACE_KNOB, SPACE_SPLIT = 0, 1
+SPACE_KNOB, SPACE_SPLIT, SPACE_SPLIT_XRED = 0, 1, 2
 MODE_EXHAUSTIVE, MODE_SAMPLE, MODE_MUTATE, MODE_CROSSOVER = 0, 1, 2, 3
 SEL_THRESHOLD, SEL_RANK = 0, 1
 

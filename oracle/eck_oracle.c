@@ -56,7 +56,7 @@
 #define ORC_EINVAL (-1)
 
 enum { ORC_OP_GEMM = 0, ORC_OP_BGEMM = 1, ORC_OP_CONV2D = 2 };
-enum { ORC_SPACE_KNOB = 0, ORC_SPACE_SPLIT = 1 };
+enum { ORC_SPACE_KNOB = 0, ORC_SPACE_SPLIT = 1, ORC_SPACE_SPLIT_XRED = 2 };
 enum { ORC_MODE_EXHAUSTIVE = 0, ORC_MODE_SAMPLE = 1, ORC_MODE_MUTATE = 2, ORC_MODE_CROSSOVER = 3 };
 enum { ORC_SEL_THRESHOLD = 0, ORC_SEL_RANK = 1 };
 
@@ -180,7 +180,7 @@ void *orc_space_create(const int32_t *pb_fields, int32_t kind)
         sp->n_genes = 6;
         sp->radix[0] = 5; sp->radix[1] = 5; sp->radix[2] = 4;
         sp->radix[3] = 4; sp->radix[4] = 4; sp->radix[5] = 4;
-    } else if (kind == ORC_SPACE_SPLIT) {
+    } else if (kind == ORC_SPACE_SPLIT || kind == ORC_SPACE_SPLIT_XRED) {
         int g = 0;
         for (int a = 0; a < NAX; ++a) {
             if (!present[a]) continue;
@@ -514,6 +514,151 @@ static void raw_features(const orc_space *sp, const orc_record *rec, uint64_t *x
              (rec->f[sp->vec_axis][3] % V == 0);
 }
 
+static uint64_t ceil_log2(uint64_t v)
+{
+    uint64_t l = 0;
+    while (((uint64_t)1 << l) < v) ++l;
+    return l;
+}
+
+/* The same 64 slots for a schedule that splits the reduction across threads
+ * (space kind SPLIT_XRED), the shape reduction-dominated operators such as the
+ * matrix-vector products of Sec. 7.2 need.  Reading of the reduction axis's
+ * levels: f0 -> serial stage loop, f1 -> threads of the block that share one
+ * output's reduction, f2*f3 -> serial per thread per stage (f3 innermost).
+ * Nothing is staged: every thread loads the operand elements of its own slice
+ * from global memory.  When f1 > 1 the block combines the f1 partial sums of
+ * every output by a pairwise tree in shared memory (fp32 partials): all
+ * partials are stored once, then ceil(log2 f1) halving steps, each addition
+ * loading two partials and storing one; the thread with k1 = 0 writes the
+ * output.  Spatial axes keep their meaning. */
+static void raw_features_xred(const orc_space *sp, const orc_record *rec, uint64_t *x, int *legal)
+{
+    const orc_problem *pb = &sp->pb;
+    const int conv = (pb->op == ORC_OP_CONV2D);
+    const uint64_t b = (uint64_t)pb->elem_bytes;
+    const uint64_t R = sp->R, S = sp->S, st = sp->stride;
+
+    uint64_t G = 1, Ts = 1, Pt = 1, tile[NAX], per_thread[NAX];
+    for (int a = 0; a < NAX; ++a) {
+        tile[a] = rec->f[a][1] * rec->f[a][2] * rec->f[a][3];
+        per_thread[a] = rec->f[a][2] * rec->f[a][3];
+    }
+    for (int a = 0; a < RED_AXIS; ++a) {
+        G *= rec->f[a][0];
+        Ts *= rec->f[a][1];
+        Pt *= per_thread[a];
+    }
+    const uint64_t stages = rec->f[RED_AXIS][0];
+    const uint64_t Kt = rec->f[RED_AXIS][1];         /* threads along the reduction */
+    const uint64_t kser = per_thread[RED_AXIS];      /* serial reduction steps per thread per stage */
+    const uint64_t T = Ts * Kt;
+    const uint64_t red_thread = stages * kser * R * S; /* multiply-adds per output per thread */
+    const uint64_t stage_red = tile[RED_AXIS] * R * S;
+    const uint64_t inner_trip = rec->f[RED_AXIS][3];
+    const uint64_t U = rec->U, V = rec->V;
+    const uint64_t steps = ceil_log2(Kt);
+
+    uint64_t true_out = 1;
+    for (int a = 0; a < RED_AXIS; ++a) true_out *= sp->ext[a];
+    const uint64_t true_red = sp->ext[RED_AXIS] * R * S;
+
+    /* operand elements per stage: of one thread (thrA, thrB), of the whole
+     * block (fpA, fpB); operand elements per reduction step of one thread */
+    uint64_t fpA, fpB, thrA, thrB, pa, pb_, nohalo;
+    if (conv) {
+        uint64_t in_h = (tile[2] - 1) * st + R, in_w = (tile[3] - 1) * st + S;
+        uint64_t th = (per_thread[2] - 1) * st + R, tw = (per_thread[3] - 1) * st + S;
+        fpA = tile[0] * tile[4] * in_h * in_w;
+        fpB = tile[1] * tile[4] * R * S;
+        nohalo = tile[0] * tile[4] * tile[2] * tile[3];
+        thrA = per_thread[0] * kser * th * tw;
+        thrB = per_thread[1] * kser * R * S;
+        pa = per_thread[0] * per_thread[2] * per_thread[3];
+        pb_ = per_thread[1];
+    } else {
+        fpA = tile[0] * tile[1] * tile[4];
+        fpB = tile[0] * tile[2] * tile[4];
+        nohalo = fpA;
+        pa = per_thread[0] * per_thread[1];
+        pb_ = per_thread[0] * per_thread[2];
+        thrA = pa * kser;
+        thrB = pb_ * kser;
+    }
+    const uint64_t ld_per_thread_stage = ceil_div(thrA + thrB, V);
+    const uint64_t glb_ld_bytes = G * T * stages * (thrA + thrB) * b;
+    const uint64_t glb_ld_sectors = ceil_div(glb_ld_bytes, 32);
+    const uint64_t padded_out = G * Ts * Pt;
+    const uint64_t glb_st_sectors = ceil_div(padded_out * b, 32);
+    const uint64_t smem_bytes = Kt > 1 ? T * Pt * 4 : 0; /* fp32 partial sums */
+
+    uint64_t bpc = (uint64_t)pb->hw_max_threads_cu / T;
+    if (smem_bytes > 0) bpc = min_u64(bpc, (uint64_t)pb->hw_lds_bytes / smem_bytes);
+    bpc = min_u64(bpc, (uint64_t)pb->hw_max_blocks_cu);
+    const uint64_t slots = (uint64_t)pb->hw_num_cu * (bpc > 0 ? bpc : 1);
+    const uint64_t active_cu = min_u64(G, (uint64_t)pb->hw_num_cu);
+
+    uint64_t in_elems, w_elems, out_elems = true_out;
+    if (conv) {
+        in_elems = (uint64_t)pb->dim[0] * (uint64_t)pb->dim[1] * (uint64_t)pb->dim[3] * (uint64_t)pb->dim[4];
+        w_elems = sp->ext[1] * sp->ext[4] * R * S;
+    } else {
+        in_elems = sp->ext[0] * sp->ext[1] * sp->ext[4];
+        w_elems = sp->ext[0] * sp->ext[4] * sp->ext[2];
+    }
+
+    uint64_t depth = (R > 1) + (S > 1);
+    for (int a = 0; a < NAX; ++a)
+        for (int l = 0; l < 4; ++l) depth += (rec->f[a][l] > 1);
+
+    memset(x, 0, ORC_NFEAT_MAX * sizeof(uint64_t));
+    x[0] = 2 * true_out * true_red;
+    x[1] = 2 * G * T * Pt * red_thread + padded_out * (Kt - 1); /* multiply-adds, then the tree's additions */
+    x[2] = Pt * red_thread;
+    x[3] = G * T * (stages * (4 * ld_per_thread_stage + 2) + 2 * ceil_div(red_thread, U) + 2 * steps);
+    x[4] = Pt;
+    x[5] = Pt + pa + pb_;
+    x[6] = G;
+    x[7] = T;
+    x[8] = ceil_div(T, (uint64_t)pb->hw_wave);
+    x[9] = bpc;
+    x[10] = active_cu;
+    x[11] = (uint64_t)pb->hw_num_cu - active_cu;
+    x[12] = ceil_div(G, slots);
+    x[13] = G % slots;
+    x[14] = G * T * stages * ld_per_thread_stage;
+    x[15] = glb_ld_sectors;
+    x[16] = glb_st_sectors;
+    x[17] = G * Ts * ceil_div(Pt, V);
+    x[18] = smem_bytes;
+    x[19] = ceil_div(padded_out * (2 * Kt - 1) * 4, 128) * (Kt > 1); /* Kt stores, then one per addition */
+    x[20] = padded_out * 2 * (Kt - 1);                              /* two loads per addition */
+    x[21] = (x[1] << 3) / (glb_ld_sectors + glb_st_sectors);
+    x[22] = (in_elems + w_elems + out_elems) * b;
+    x[23] = (glb_ld_bytes << 8) / ((in_elems + w_elems) * b);
+    x[24] = stages;
+    x[25] = stage_red;
+    x[26] = inner_trip;
+    x[27] = U;
+    x[28] = min_u64(U, inner_trip) * Pt;
+    x[29] = depth;
+    x[30] = V;
+    x[31] = gcd_u64(V, rec->f[sp->vec_axis][3]);
+    for (int a = 0; a < NAX; ++a)
+        for (int l = 0; l < 4; ++l) x[32 + 4 * a + l] = rec->f[a][l];
+    for (int a = 0; a < NAX; ++a) x[52 + a] = tile[a];
+    x[57] = fpA;
+    x[58] = fpB;
+    x[59] = (fpA << 8) / nohalo;
+    x[60] = b;
+    x[61] = (uint64_t)pb->op;
+    x[62] = true_out;
+    x[63] = true_red;
+
+    *legal = (T >= 32 && T <= 1024) && (smem_bytes <= (uint64_t)pb->hw_lds_bytes) && (V * b <= 16) &&
+             (rec->f[sp->vec_axis][3] % V == 0);
+}
+
 /* Fixed-point log2 with a 10-bit linear mantissa: v = raw+1 (saturating),
  * e = floor(log2 v), m = the 10 bits below v's leading one; result e + m/1024.
  * At most 16 significant bits, so the float is exact. */
@@ -564,7 +709,8 @@ int32_t orc_features(const void *h, const uint16_t *genes, uint64_t ld, uint64_t
         uint64_t x[ORC_NFEAT_MAX];
         int legal;
         build_record(sp, g, &rec);
-        raw_features(sp, &rec, x, &legal);
+        if (sp->kind == ORC_SPACE_SPLIT_XRED) raw_features_xred(sp, &rec, x, &legal);
+        else raw_features(sp, &rec, x, &legal);
         for (int f = 0; f < n_feat; ++f) {
             uint64_t at = (uint64_t)f * ld + (uint64_t)i;
             float t = orc_transform(x[f]);

@@ -91,7 +91,7 @@ extern "C" int32_t eck_space_create(const eck_problem *pb, int32_t kind, eck_spa
 {
     if (!pb || !out) return ECK_EINVAL;
     *out = nullptr;
-    if (kind != ECK_SPACE_KNOB && kind != ECK_SPACE_SPLIT) return ECK_EINVAL;
+    if (kind != ECK_SPACE_KNOB && kind != ECK_SPACE_SPLIT && kind != ECK_SPACE_SPLIT_XRED) return ECK_EINVAL;
     if (pb->elem_bytes != 2 && pb->elem_bytes != 4) return ECK_EINVAL;
     if (pb->hw_num_cu < 1 || pb->hw_wave < 1 || pb->hw_lds_bytes < 1 || pb->hw_max_threads_cu < 1 ||
         pb->hw_max_blocks_cu < 1)
@@ -244,7 +244,7 @@ extern "C" int32_t eck_space_info(const eck_space *sp, int32_t *n_genes, uint32_
 
 extern "C" int32_t eck_space_table(const eck_space *sp, int32_t gene, uint32_t *out, uint32_t capacity)
 {
-    if (!sp || sp->prm.kind != ECK_SPACE_SPLIT || gene < 0 || gene >= sp->prm.n_split) return ECK_EINVAL;
+    if (!sp || sp->prm.kind == ECK_SPACE_KNOB || gene < 0 || gene >= sp->prm.n_split) return ECK_EINVAL;
     const uint32_t n = sp->table_n[gene];
     if (out) {
         const uint16_t *src = sp->tables.data() + 4ull * sp->prm.table_off[gene];
@@ -605,7 +605,7 @@ __device__ __forceinline__ uint64_t floor_div_f64(uint64_t a, uint64_t b)
     return q;
 }
 
-template <int OUT_DTYPE, bool TABLES_IN_LDS, int N_FEAT, bool WANT_RAW>
+template <int OUT_DTYPE, bool TABLES_IN_LDS, int N_FEAT, bool WANT_RAW, bool XRED>
 __global__ __launch_bounds__(256) void features_kernel(SpaceBatch spaces, const uint16_t *__restrict__ genes,
                                                        uint64_t ld, uint64_t n, void *__restrict__ feat_out,
                                                        uint64_t *__restrict__ raw_out,
@@ -670,78 +670,6 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceBatch spaces, const 
         lv.log2_vec = gv;
     }
 
-    // ---- derived quantities
-    uint32_t tile[NAX], per_thread[NAX];
-#pragma unroll
-    for (int a = 0; a < NAX; ++a) {
-        per_thread[a] = lv.f[a][2] * lv.f[a][3];
-        tile[a] = lv.f[a][1] * per_thread[a];
-    }
-    const uint32_t grid = lv.f[0][0] * lv.f[1][0] * lv.f[2][0] * lv.f[3][0];
-    const uint32_t threads = lv.f[0][1] * lv.f[1][1] * lv.f[2][1] * lv.f[3][1];
-    const uint32_t outs_thread = per_thread[0] * per_thread[1] * per_thread[2] * per_thread[3];
-    const uint32_t grid_threads = grid * threads; // <= padded outputs < 2^32
-    const uint32_t stages = lv.f[RED_AXIS][0];
-    const uint32_t rs = p.R * p.S;
-    const uint32_t stage_red = tile[RED_AXIS] * rs;
-    const uint32_t red = stages * stage_red;
-    const uint32_t inner_trip = lv.f[RED_AXIS][3];
-    const uint32_t lu = lv.log2_unroll, lvv = lv.log2_vec;
-    const uint32_t unroll = 1u << lu, vec = 1u << lvv;
-    const bool conv = p.op == ECK_OP_CONV2D;
-
-    uint32_t fp_a, fp_b, thr_a, thr_b;
-    uint64_t halo_q8;
-    if (conv) {
-        const uint32_t in_h = (tile[2] - 1) * p.stride + p.R, in_w = (tile[3] - 1) * p.stride + p.S;
-        const uint32_t patch = in_h * in_w;
-        fp_a = tile[0] * tile[4] * patch;
-        fp_b = tile[1] * tile[4] * rs;
-        thr_a = per_thread[0] * per_thread[2] * per_thread[3];
-        thr_b = per_thread[1];
-        halo_q8 = floor_div_f64((uint64_t)patch << 8, tile[2] * tile[3]); // numerator < 2^40
-    } else {
-        fp_a = tile[0] * tile[1] * tile[4];
-        fp_b = tile[0] * tile[2] * tile[4];
-        thr_a = per_thread[0] * per_thread[1];
-        thr_b = per_thread[0] * per_thread[2];
-        halo_q8 = 256;
-    }
-    const uint32_t fp = fp_a + fp_b;
-    const uint64_t smem_bytes = (uint64_t)fp * p.elem_bytes;
-    // vector loads per thread per stage: ceil(fp / (threads * vec)) == ceil(ceil(fp / threads) / vec)
-    const uint32_t loads_thread_stage = (ceil_div_u32(fp, threads) + vec - 1) >> lvv;
-    const uint64_t gs = (uint64_t)grid * stages;
-    const uint64_t ld_bytes = gs * fp * p.elem_bytes;
-    const uint64_t ld_sectors = (ld_bytes + 31) >> 5;
-    const uint64_t padded_out = (uint64_t)grid_threads * outs_thread;
-    const uint64_t st_sectors = (padded_out * p.elem_bytes + 31) >> 5;
-    const uint64_t flop_exec = 2 * padded_out * red;
-
-    uint32_t blocks_cu = p.hw_max_threads_cu / threads;
-    if (smem_bytes > p.hw_lds_bytes) blocks_cu = 0;
-    else if (smem_bytes > 0) blocks_cu = min(blocks_cu, p.hw_lds_bytes / (uint32_t)smem_bytes);
-    blocks_cu = min(blocks_cu, p.hw_max_blocks_cu);
-    const uint32_t slots = p.hw_num_cu * (blocks_cu ? blocks_cu : 1);
-    const uint32_t waves = grid / slots;
-    const uint32_t tail = grid - waves * slots;
-    const uint32_t active = min(grid, p.hw_num_cu);
-
-    uint32_t depth = (p.R > 1) + (p.S > 1);
-#pragma unroll
-    for (int a = 0; a < NAX; ++a)
-#pragma unroll
-        for (int l = 0; l < 4; ++l) depth += lv.f[a][l] > 1;
-
-    const uint32_t contiguous = p.vec_axis == 3 ? lv.f[3][3] : lv.f[2][3];
-    // gcd with a power of two: the power of two dividing both
-    const uint32_t low_bit = contiguous & (0u - contiguous);
-    const uint32_t vec_contig = low_bit < vec ? low_bit : vec;
-
-    const bool legal = threads >= 32 && threads <= 1024 && lv.shape_ok && smem_bytes <= p.hw_lds_bytes &&
-                       vec * p.elem_bytes <= 16 && (contiguous & (vec - 1)) == 0;
-    if (legal_out) legal_out[i] = legal ? 1 : 0;
-
     // ---- transform and store.  Three flavours: per-space constants (transformed on the host), values
     // known to stay below 2^32 (32-bit log2) and the rest (64-bit log2).
     // Row f of an output starts at a wave-uniform address (row base + first column of the block), so the
@@ -772,29 +700,147 @@ __global__ __launch_bounds__(256) void features_kernel(SpaceBatch spaces, const 
         store_q10(f, log2_q10_u64(raw == ~0ull ? raw : raw + 1));
     };
 
+    // ---- derived quantities
+    uint32_t tile[NAX], per_thread[NAX];
+#pragma unroll
+    for (int a = 0; a < NAX; ++a) {
+        per_thread[a] = lv.f[a][2] * lv.f[a][3];
+        tile[a] = lv.f[a][1] * per_thread[a];
+    }
+    const uint32_t grid = lv.f[0][0] * lv.f[1][0] * lv.f[2][0] * lv.f[3][0];
+    const uint32_t threads = lv.f[0][1] * lv.f[1][1] * lv.f[2][1] * lv.f[3][1];
+    const uint32_t outs_thread = per_thread[0] * per_thread[1] * per_thread[2] * per_thread[3];
+    const uint32_t grid_threads = grid * threads; // <= padded outputs < 2^32
+    const uint32_t stages = lv.f[RED_AXIS][0];
+    const uint32_t rs = p.R * p.S;
+    const uint32_t stage_red = tile[RED_AXIS] * rs;
+    const uint32_t inner_trip = lv.f[RED_AXIS][3];
+    const uint32_t lu = lv.log2_unroll, lvv = lv.log2_vec;
+    const uint32_t unroll = 1u << lu, vec = 1u << lvv;
+    const bool conv = p.op == ECK_OP_CONV2D;
+
+    uint32_t fp_a, fp_b, thr_a, thr_b;
+    uint64_t halo_q8;
+    if (conv) {
+        const uint32_t in_h = (tile[2] - 1) * p.stride + p.R, in_w = (tile[3] - 1) * p.stride + p.S;
+        const uint32_t patch = in_h * in_w;
+        fp_a = tile[0] * tile[4] * patch;
+        fp_b = tile[1] * tile[4] * rs;
+        thr_a = per_thread[0] * per_thread[2] * per_thread[3];
+        thr_b = per_thread[1];
+        halo_q8 = floor_div_f64((uint64_t)patch << 8, tile[2] * tile[3]); // numerator < 2^40
+    } else {
+        fp_a = tile[0] * tile[1] * tile[4];
+        fp_b = tile[0] * tile[2] * tile[4];
+        thr_a = per_thread[0] * per_thread[1];
+        thr_b = per_thread[0] * per_thread[2];
+        halo_q8 = 256;
+    }
+    const uint32_t fp = fp_a + fp_b;
+    const uint64_t padded_out = (uint64_t)grid_threads * outs_thread;
+    const uint64_t st_sectors = (padded_out * p.elem_bytes + 31) >> 5;
+
+    // ---- what depends on where the reduction runs
+    uint64_t block_threads, smem_bytes, ld_bytes, flop_exec, fma_thread, int_ops, ld_instr, shared_st_tx, shared_ld;
+    uint64_t waves_block;
+    uint32_t blocks_cu;
+    if (XRED) {
+        // the reduction axis's second level is spread over threads; nothing is staged, every thread loads its
+        // own slice; the partial sums of an output meet in a halving tree in shared memory
+        const uint32_t kt = lv.f[RED_AXIS][1], kser = per_thread[RED_AXIS];
+        const uint32_t red_thread = stages * kser * rs;
+        uint32_t elems_a, elems_b; // operand elements of one thread in one stage (each below 2^31)
+        if (conv) {
+            const uint32_t th = (per_thread[2] - 1) * p.stride + p.R, tw = (per_thread[3] - 1) * p.stride + p.S;
+            elems_a = per_thread[0] * kser * th * tw;
+            elems_b = per_thread[1] * kser * rs;
+        } else {
+            elems_a = thr_a * kser;
+            elems_b = thr_b * kser;
+        }
+        const uint64_t elems = (uint64_t)elems_a + elems_b;
+        const uint64_t loads_thread_stage = (elems + vec - 1) >> lvv;
+        const uint64_t all_threads = (uint64_t)grid_threads * kt; // grid * block
+        const uint32_t tree_steps = kt > 1 ? 32u - (uint32_t)__clz((int)(kt - 1)) : 0u;
+        block_threads = (uint64_t)threads * kt;
+        smem_bytes = kt > 1 ? block_threads * outs_thread * 4 : 0; // fp32 partial sums
+        ld_bytes = all_threads * stages * elems * p.elem_bytes;
+        flop_exec = 2 * all_threads * outs_thread * red_thread + padded_out * (kt - 1);
+        fma_thread = (uint64_t)outs_thread * red_thread;
+        int_ops = all_threads * ((uint64_t)stages * (4 * loads_thread_stage + 2) +
+                                 2ull * ((red_thread + unroll - 1) >> lu) + 2ull * tree_steps);
+        ld_instr = all_threads * stages * loads_thread_stage;
+        shared_st_tx = kt > 1 ? (padded_out * (2ull * kt - 1) * 4 + 127) >> 7 : 0;
+        shared_ld = padded_out * 2 * (kt - 1);
+        waves_block = floor_div_f64(block_threads + p.hw_wave - 1, p.hw_wave); // block_threads < 2^48
+        blocks_cu = block_threads > p.hw_max_threads_cu ? 0u : p.hw_max_threads_cu / (uint32_t)block_threads;
+    } else {
+        // the reduction is staged through shared memory, stage by stage, by the whole block
+        const uint32_t red = stages * stage_red;
+        // vector loads per thread per stage: ceil(fp / (threads * vec)) == ceil(ceil(fp / threads) / vec)
+        const uint32_t loads_thread_stage = (ceil_div_u32(fp, threads) + vec - 1) >> lvv;
+        block_threads = threads;
+        smem_bytes = (uint64_t)fp * p.elem_bytes;
+        ld_bytes = (uint64_t)grid * stages * fp * p.elem_bytes;
+        flop_exec = 2 * padded_out * red;
+        fma_thread = (uint64_t)outs_thread * red;
+        int_ops = (uint64_t)grid_threads *
+                  ((uint64_t)stages * (4ull * loads_thread_stage + 2) + 2ull * ((red + unroll - 1) >> lu));
+        ld_instr = (uint64_t)grid_threads * stages * loads_thread_stage;
+        shared_st_tx = (ld_bytes + 127) >> 7;
+        shared_ld = (uint64_t)grid_threads * ((uint64_t)thr_a + thr_b) * red;
+        waves_block = ceil_div_u32(threads, p.hw_wave);
+        blocks_cu = p.hw_max_threads_cu / threads;
+    }
+    const uint64_t ld_sectors = (ld_bytes + 31) >> 5;
+
+    if (smem_bytes > p.hw_lds_bytes) blocks_cu = 0;
+    else if (smem_bytes > 0) blocks_cu = min(blocks_cu, p.hw_lds_bytes / (uint32_t)smem_bytes);
+    blocks_cu = min(blocks_cu, p.hw_max_blocks_cu);
+    const uint32_t slots = p.hw_num_cu * (blocks_cu ? blocks_cu : 1);
+    const uint32_t waves = grid / slots;
+    const uint32_t tail = grid - waves * slots;
+    const uint32_t active = min(grid, p.hw_num_cu);
+
+    uint32_t depth = (p.R > 1) + (p.S > 1);
+#pragma unroll
+    for (int a = 0; a < NAX; ++a)
+#pragma unroll
+        for (int l = 0; l < 4; ++l) depth += lv.f[a][l] > 1;
+
+    const uint32_t contiguous = p.vec_axis == 3 ? lv.f[3][3] : lv.f[2][3];
+    // gcd with a power of two: the power of two dividing both
+    const uint32_t low_bit = contiguous & (0u - contiguous);
+    const uint32_t vec_contig = low_bit < vec ? low_bit : vec;
+
+    const bool legal = block_threads >= 32 && block_threads <= 1024 && lv.shape_ok && smem_bytes <= p.hw_lds_bytes &&
+                       vec * p.elem_bytes <= 16 && (contiguous & (vec - 1)) == 0;
+    if (legal_out) legal_out[i] = legal ? 1 : 0;
+
     emit_const(0, 0, p.flop_useful);
     emit64(1, flop_exec);
-    emit64(2, (uint64_t)outs_thread * red);
-    emit64(3, (uint64_t)grid_threads *
-                  ((uint64_t)stages * (4ull * loads_thread_stage + 2) + 2ull * ((red + unroll - 1) >> lu)));
+    emit64(2, fma_thread);
+    emit64(3, int_ops);
     emit32(4, outs_thread);
     emit64(5, (uint64_t)outs_thread + thr_a + thr_b);
     emit32(6, grid);
-    emit32(7, threads);
-    emit32(8, ceil_div_u32(threads, p.hw_wave));
+    if (XRED) emit64(7, block_threads);
+    else emit32(7, threads);
+    if (XRED) emit64(8, waves_block);
+    else emit32(8, (uint32_t)waves_block);
     emit32(9, blocks_cu);
     emit32(10, active);
     emit32(11, p.hw_num_cu - active);
     emit32(12, waves + (tail != 0));
     emit32(13, tail);
-    emit64(14, (uint64_t)grid_threads * stages * loads_thread_stage);
+    emit64(14, ld_instr);
     emit64(15, ld_sectors);
     emit64(16, st_sectors);
     emit64(17, (uint64_t)grid_threads * ((outs_thread + vec - 1) >> lvv));
     emit64(18, smem_bytes);
-    emit64(19, (ld_bytes + 127) >> 7);
-    emit64(20, (uint64_t)grid_threads * ((uint64_t)thr_a + thr_b) * red);
-    emit64(21, floor_div_f64(flop_exec << 3, ld_sectors + st_sectors)); // numerator < 2^51
+    emit64(19, shared_st_tx);
+    emit64(20, shared_ld);
+    emit64(21, floor_div_f64(flop_exec << 3, ld_sectors + st_sectors)); // numerator < 2^52
     emit_const(22, 1, p.compulsory_bytes);
     {
         // (ld_bytes * 256) / c with ld_bytes < 2^50 and c < 2^34, as two exact steps
@@ -851,18 +897,21 @@ int32_t features_launch(const eck_space *const *spaces, uint32_t n_spaces, const
     // the tables go to the LDS when those of every space in the batch fit
     uint32_t largest = 0;
     for (uint32_t s = 0; s < n_spaces; ++s) largest = std::max(largest, spaces[s]->prm.table_total);
-    const bool in_lds = spaces[0]->prm.kind == ECK_SPACE_SPLIT && largest <= 6144;
+    const bool xred = spaces[0]->prm.kind == ECK_SPACE_SPLIT_XRED;
+    const bool in_lds = spaces[0]->prm.kind != ECK_SPACE_KNOB && largest <= 6144;
     const size_t lds = in_lds ? (size_t)largest * 8 : 0;
     const dim3 block(256), grid((unsigned)((n + 255) / 256), n_spaces);
     hipStream_t st = as_stream(stream);
     const bool raw = raw_out != nullptr;
-#define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW)                                                                \
-    hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW>), grid, block, lds, st, batch, genes, ld, n, feat_out, \
+#define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW, XR)                                                                \
+    hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW, XR>), grid, block, lds, st, batch, genes, ld, n, feat_out, \
                        raw_out, legal_out)
 #define ECK_PICK_RAW(DT, INLDS, NF)                    \
     do {                                               \
-        if (raw) ECK_LAUNCH_FEATURES(DT, INLDS, NF, true); \
-        else ECK_LAUNCH_FEATURES(DT, INLDS, NF, false);    \
+        if (raw && xred) ECK_LAUNCH_FEATURES(DT, INLDS, NF, true, true);        \
+        else if (raw) ECK_LAUNCH_FEATURES(DT, INLDS, NF, true, false);          \
+        else if (xred) ECK_LAUNCH_FEATURES(DT, INLDS, NF, false, true);         \
+        else ECK_LAUNCH_FEATURES(DT, INLDS, NF, false, false);                  \
     } while (0)
 #define ECK_PICK_NF(DT, INLDS)                          \
     do {                                                \

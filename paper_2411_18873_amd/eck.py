@@ -18,7 +18,7 @@ OK, EINVAL, ESHAPE, EUNSUPPORTED, EALIGN, EWORKSPACE, EDEVICE = 0, -1, -2, -3, -
 ERROR_NAMES = {EINVAL: "ECK_EINVAL", ESHAPE: "ECK_ESHAPE", EUNSUPPORTED: "ECK_EUNSUPPORTED", EALIGN: "ECK_EALIGN",
                EWORKSPACE: "ECK_EWORKSPACE", EDEVICE: "ECK_EDEVICE"}
 OP_GEMM, OP_BGEMM, OP_CONV2D = 0, 1, 2
-SPACE_KNOB, SPACE_SPLIT = 0, 1
+SPACE_KNOB, SPACE_SPLIT, SPACE_SPLIT_XRED = 0, 1, 2
 MODE_EXHAUSTIVE, MODE_SAMPLE, MODE_MUTATE, MODE_CROSSOVER = 0, 1, 2, 3
 F32, BF16 = 0, 1
 SELECT_THRESHOLD, SELECT_RANK = 0, 1

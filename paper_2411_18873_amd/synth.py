@@ -13,7 +13,7 @@ replaced by seeded samples of the spaces described below.
 import numpy as np
 
 OP_GEMM, OP_BGEMM, OP_CONV2D = 0, 1, 2
-SPACE_KNOB, SPACE_SPLIT = 0, 1
+SPACE_KNOB, SPACE_SPLIT, SPACE_SPLIT_XRED = 0, 1, 2
 
 # (num_cu, wave, lds_bytes, max_threads_cu, max_blocks_cu)
 HW_MI355X = (256, 64, 160 * 1024, 2048, 32)

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
     assert L.eck_version() >= 100
 
 
-@pytest.mark.parametrize("cfg,kind", [("c1", 0), ("c2", 1), ("c3", 1)])
+@pytest.mark.parametrize("cfg,kind", [("c1", 0), ("c2", 1), ("c3", 1), ("c2", 2), ("c3", 2)])
 def test_spaces_match_the_oracle(cfg, kind):
     pb = synth.CONFIGS[cfg]["problem"]
     mine, ref = eck.Space(pb, kind), oracle.Space(pb, kind)
@@ -72,6 +72,7 @@ def test_space_create_rejects_bad_problems():
     bad = good.copy(); bad[10] = 0
     assert _rc_space(bad, eck.SPACE_SPLIT) == eck.EINVAL           # hw_num_cu
     assert _rc_space(synth.conv2d(1, 8, 8, 8, 8, 3, 3), eck.SPACE_KNOB) == eck.EUNSUPPORTED
+    assert _rc_space(good, eck.SPACE_SPLIT_XRED) == eck.OK and _rc_space(good, 3) == eck.EINVAL  # space kinds
     assert _rc_space(synth.gemm(65535, 65535, 65535), eck.SPACE_SPLIT) == eck.EUNSUPPORTED  # 2^48 multiply-adds
     assert _rc_space(synth.gemm(70000, 8, 8), eck.SPACE_SPLIT) == eck.EUNSUPPORTED
     assert _rc_space(synth.conv2d(1, 8, 8, 2, 2, 3, 3, 1, 0), eck.SPACE_SPLIT) == eck.EINVAL  # kernel larger than image

@@ -70,7 +70,8 @@ def _check_features(G, mine, ref, genes, n_feat):
     raw_o, f32_o, b16_o, legal_o = oracle.features(ref, genes, n_feat, n=n)
     raw_g, f32_g, legal_g = G.features_gpu(mine, genes, n, n_feat, eck.F32)
     _, b16_g, legal_g2 = G.features_gpu(mine, genes, n, n_feat, eck.BF16, want_raw=False)
-    assert np.array_equal(raw_g[:, :n], raw_o[:, :n])
+    differs = np.nonzero((raw_g[:, :n] != raw_o[:, :n]).any(axis=1))[0]
+    assert differs.size == 0, "raw features that differ: %s" % differs
     assert np.array_equal(f32_g[:, :n].view(np.uint32), f32_o[:, :n].view(np.uint32))
     assert np.array_equal(b16_g[:, :n], b16_o[:, :n])
     assert np.array_equal(legal_g, legal_o) and np.array_equal(legal_g2, legal_o)
@@ -332,3 +333,91 @@ def test_features_random_problems(G):
         _check_features(G, mine, ref, genes, 64)
         checked += 1
     assert checked >= 40
+
+
+def test_reduction_parallel_hand_worked_schedule(G, golden):
+    rows = golden("hand_mv_xred.txt")
+    pb = synth.gemm(1, 8, 32, elem_bytes=2, hw=(4, 64, 1024, 256, 8))
+    mine, ref = _spaces(pb, eck.SPACE_SPLIT_XRED)
+    tabs = [[tuple(int(v) for v in t) for t in oracle.split_table(e)] for e in (1, 8, 32)]
+    g = [tabs[0].index((1, 1, 1, 1)), tabs[1].index((2, 2, 1, 2)), tabs[2].index((2, 4, 2, 2)), 1, 1]
+    genes = np.array([g, g], dtype=np.uint16).T.copy()
+    raw, _, legal = G.features_gpu(mine, genes, 2, 64, eck.F32)
+    assert [int(v) for v in raw[:, 0]] == [int(t) for t in rows[0]] and legal[0] == int(rows[1][0])
+
+
+def test_reduction_parallel_features_of_the_paper_operators(G):
+    """Space kind SPLIT_XRED (the reduction split across threads) on the eleven operators of Sec. 7.2, the
+    matrix-vector products it is meant for among them: every feature and flag bit for bit."""
+    share = {}
+    for i, (name, pb) in enumerate(synth.paper_operators().items()):
+        mine, ref = _spaces(pb, eck.SPACE_SPLIT_XRED)
+        assert mine.radix == ref.radix
+        n = 4097
+        got = G.enumerate_gpu(mine, eck.MODE_SAMPLE, n, seed=500 + i)
+        want = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, n, seed=500 + i)
+        assert np.array_equal(got[:, :n], want), name
+        _, legal = _check_features(G, mine, ref, want, 64)
+        _check_features(G, mine, ref, want[:, :1001], 32)
+        share[name] = legal.mean()
+    assert all(share[k] > 0.02 for k in ("MV1", "MV2", "MV3", "MV4")), share
+
+
+def test_reduction_parallel_features_random_problems(G):
+    rng = np.random.default_rng(77)
+    dims = [1, 2, 3, 7, 12, 30, 64, 100, 255, 256, 500, 1024, 2047, 4096, 12288, 49512]
+    checked = 0
+    for trial in range(50):
+        eb = int(rng.choice([2, 4]))
+        hw = synth.HW_MI355X if trial % 3 else synth.HW_CASE_STUDY
+        which = trial % 3
+        if which == 0:
+            pb = synth.gemm(*(int(rng.choice(dims)) for _ in range(3)), elem_bytes=eb, hw=hw)
+        elif which == 1:
+            pb = synth.bgemm(int(rng.choice([2, 3, 8, 32])), *(int(rng.choice(dims[:13])) for _ in range(3)),
+                             elem_bytes=eb, hw=hw)
+        else:
+            pb = synth.conv2d(int(rng.choice([1, 2, 8])), int(rng.choice([3, 16, 64, 96, 512])),
+                              int(rng.choice([8, 32, 100])), int(rng.choice([7, 14, 28, 57])),
+                              int(rng.choice([7, 14, 30])), int(rng.choice([1, 3, 5])), int(rng.choice([1, 3])),
+                              int(rng.choice([1, 2])), int(rng.choice([0, 1, 2])), elem_bytes=eb, hw=hw)
+        try:
+            ref = oracle.Space(pb, oracle.SPACE_SPLIT_XRED)
+        except Exception:
+            continue
+        try:
+            mine = eck.Space(pb, eck.SPACE_SPLIT_XRED)
+        except eck.EckError:
+            continue
+        n = int(min(ref.size, 1500)) if ref.size else 1500
+        mode = oracle.MODE_EXHAUSTIVE if ref.size and ref.size <= 1500 else oracle.MODE_SAMPLE
+        genes = oracle.enumerate_candidates(ref, mode, n, seed=trial)
+        _check_features(G, mine, ref, genes, 64)
+        checked += 1
+    assert checked >= 30
+
+
+def test_reduction_parallel_spaces_batched(G):
+    """A batch of SPLIT_XRED spaces through the batched calls; kinds cannot be mixed in one batch."""
+    import torch
+    problems = [synth.gemm(1, n_, k) for n_, k in ((4096, 1024), (8192, 2048), (1024, 4096))]
+    mine = [eck.Space(pb, eck.SPACE_SPLIT_XRED) for pb in problems]
+    refs = [oracle.Space(pb, oracle.SPACE_SPLIT_XRED) for pb in problems]
+    n = 2050
+    seeds = [31, 32, 33]
+    genes = torch.zeros((mine[0].n_genes, 3 * n), dtype=torch.int16, device="cuda")
+    eck.candidate_enumerate_batch(mine, eck.MODE_SAMPLE, n, genes, seeds)
+    feat = torch.zeros((64, 3 * n), dtype=torch.float32, device="cuda")
+    legal = torch.zeros(3 * n, dtype=torch.uint8, device="cuda")
+    eck.features_compute_batch(mine, genes, n, 64, eck.F32, feat, None, legal)
+    torch.cuda.synchronize()
+    g_h = genes.cpu().numpy().view(np.uint16)
+    for s in range(3):
+        want = oracle.enumerate_candidates(refs[s], oracle.MODE_SAMPLE, n, seed=seeds[s])
+        assert np.array_equal(g_h[:, s * n:(s + 1) * n], want)
+        _, f32_o, _, legal_o = oracle.features(refs[s], want, 64)
+        assert np.array_equal(feat[:, s * n:(s + 1) * n].cpu().numpy().view(np.uint32), f32_o.view(np.uint32))
+        assert np.array_equal(legal[s * n:(s + 1) * n].cpu().numpy(), legal_o)
+    mixed = [mine[0], eck.Space(problems[1], eck.SPACE_SPLIT)]
+    with pytest.raises(eck.EckError):
+        eck.features_compute_batch(mixed, genes, n, 64, eck.F32, feat, None, legal)
