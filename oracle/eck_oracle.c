@@ -18,6 +18,9 @@
  *                     (Sec. 5.3 "Insight", Sec. 5.4 "Approach"); grid / block /
  *                     global-load / shared-store / global-store counts follow
  *                     the case study (Sec. 8, Table 5).
+ *                     Two readings of the reduction axis: staged per block
+ *                     (SPLIT, KNOB) or split across threads (SPLIT_XRED, for
+ *                     the matrix-vector operators of Sec. 7.2).
  *   orc_score      -- the cost model's forward pass (Sec. 5.4); the model form
  *                     is a 2-hidden-layer ReLU MLP (the workload configs fix
  *                     that; the paper itself uses boosted trees).
@@ -40,6 +43,9 @@
  * a hand-worked ensemble, the closed-form weighted means of a one-split fit,
  * brute-force search of the best split, a library regression tree on the same
  * weighted problem, monotone training loss.
+ * Reduction-parallel schedules (space kind SPLIT_XRED): a matrix-vector
+ * schedule worked by hand and a walker that executes tiny loop nests literally
+ * and counts operations, operand elements and tree steps.
  * parity unpinned: feature 20 (shared-load element count) -- Table 5's
  * shared_ld column is not reproduced by any simple register-tile formula; and
  * the 100-step bf16 update trajectory (checked statistically only).

@@ -65,16 +65,28 @@ def test_oracle_loop_with_crossover_and_dedup_never_measures_a_kernel_twice_in_a
     assert any(not np.array_equal(a["picked"], b["picked"]) for a, b in zip(hist[1:], plain[1:]))
 
 
+def test_oracle_loop_searches_a_matrix_vector_product_in_the_reduction_parallel_space():
+    pb = synth.paper_operators()["MV4"]
+    hist, _, energy = closed_loop.run(pb, oracle.SPACE_SPLIT_XRED, _measure, 6, mu=1000.0, **KW)
+    assert hist[0]["measured"] == 64 and all(h["measured"] >= 1 for h in hist[1:])
+    assert hist[-1]["best"] < hist[0]["best"]          # later rounds find kernels of lower energy
+
+
 @pytest.mark.gpu
-@pytest.mark.parametrize("variant", [dict(), dict(crossover=True, dedup=True)])
+@pytest.mark.parametrize("variant", [dict(), dict(crossover=True, dedup=True), dict(operator="MV4")])
 def test_gpu_loop_reproduces_the_oracles_trajectory(variant):
     import torch
     from paper_2411_18873_amd import eck
     from paper_2411_18873_amd.search import EnergySearch
     rounds, mu = 6, 1000.0
-    want, (w_nf, w_nt, w_lf), w_energy = closed_loop.run(_problem(), oracle.SPACE_SPLIT, _measure, rounds, mu=mu,
-                                                         **KW, **variant)
-    s = EnergySearch(_problem(), eck.SPACE_SPLIT, _measure, mu=mu, max_rounds=rounds, **KW, **variant)
+    variant = dict(variant)
+    operator = variant.pop("operator", None)
+    # a matrix-vector product of Sec. 7.2 is searched in the reduction-parallel space
+    problem = synth.paper_operators()[operator] if operator else _problem()
+    kind = oracle.SPACE_SPLIT_XRED if operator else oracle.SPACE_SPLIT
+    assert eck.SPACE_SPLIT_XRED == oracle.SPACE_SPLIT_XRED and eck.SPACE_SPLIT == oracle.SPACE_SPLIT
+    want, (w_nf, w_nt, w_lf), w_energy = closed_loop.run(problem, kind, _measure, rounds, mu=mu, **KW, **variant)
+    s = EnergySearch(problem, kind, _measure, mu=mu, max_rounds=rounds, **KW, **variant)
     s.initialise()
     for _ in range(rounds):
         s.step()
