@@ -10,6 +10,7 @@
 // activations and back-propagated deltas rounded as they are staged) and fp32
 // accumulation; the width-1 products of the output layer stay in fp32.  All
 // reductions have a fixed order, so a run is reproducible bit for bit.
+#include <algorithm>
 #include <cmath>
 
 #include "eck_internal.h"
@@ -45,8 +46,10 @@ struct GemmArgs {
 
 constexpr int TM = 64, TN = 64, TK = 16;
 
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g)
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs first, GemmArgs second)
 {
+    const GemmArgs g = blockIdx.z ? second : first;
+    if ((int)blockIdx.x * TN >= g.N || (int)blockIdx.y * TM >= g.M) return;
     __shared__ float As[TK][TM + 4];
     __shared__ float Bs[TK][TN + 4];
     const int tid = threadIdx.x;
@@ -138,8 +141,11 @@ constexpr int KG = 2;
 constexpr size_t GEMM_MFMA_LDS = (size_t)KG * (TM + TN) * MLD * sizeof(uint16_t);
 static_assert((KG - 1) * TM * TN * sizeof(float) <= GEMM_MFMA_LDS, "partial tiles reuse the operand buffers");
 
-__global__ __launch_bounds__(256 * KG) void gemm_mfma_kernel(GemmArgs g)
+__global__ __launch_bounds__(256 * KG) void gemm_mfma_kernel(GemmArgs first, GemmArgs second)
 {
+    // blockIdx.z picks the problem; blocks outside that problem's tile grid leave before any barrier
+    const GemmArgs g = blockIdx.z ? second : first;
+    if ((int)blockIdx.x * TN >= g.N || (int)blockIdx.y * TM >= g.M) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_lds[];
     const int group = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
     uint16_t *As = reinterpret_cast<uint16_t *>(gemm_lds) + (size_t)group * (TM + TN) * MLD; // [m][k]
@@ -429,16 +435,18 @@ UpdWs upd_layout(const eck_model *m, uint64_t n_pairs, int mb)
     return w;
 }
 
-void launch_gemm(const GemmArgs &g, hipStream_t st, bool matrix_cores = false)
+// One launch for one product, or for two products that do not depend on each other (grid.z = 2).
+void launch_gemm(const GemmArgs &g, hipStream_t st, bool matrix_cores = false, const GemmArgs *also = nullptr)
 {
-    const dim3 grid((g.N + TN - 1) / TN, (g.M + TM - 1) / TM);
+    const GemmArgs &h = also ? *also : g;
+    const dim3 grid((std::max(g.N, h.N) + TN - 1) / TN, (std::max(g.M, h.M) + TM - 1) / TM, also ? 2 : 1);
     if (matrix_cores) {
         // set per call: the attribute belongs to the current device
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_mfma_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_MFMA_LDS);
-        hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256 * KG), GEMM_MFMA_LDS, st, g);
+        hipLaunchKernelGGL(gemm_mfma_kernel, grid, dim3(256 * KG), GEMM_MFMA_LDS, st, g, h);
     }
-    else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, st, g);
+    else hipLaunchKernelGGL(gemm_kernel, grid, dim3(256), 0, st, g, h);
 }
 
 } // namespace
@@ -505,10 +513,9 @@ extern "C" int32_t costmodel_update(eck_model *m, const void *feat, int32_t feat
                            grad + m->off_w[2], lterm, sc, s == n_steps - 1);
         // [gW2 ; gb2] = [h1 ; 1]^T d2
         g = GemmArgs{h1, 0, 1, H1, H1, d2, H2, 1, grad + m->off_w[1], H2, H1 + 1, H2, B, nullptr, 0, nullptr, 0, 0, 0};
-        launch_gemm(g, st, bf);
-        // d1 = (d2 W2^T) where h1 > 0
-        g = GemmArgs{d2, 0, H2, 1, -1, theta + m->off_w[1], 1, H2, d1, H1, B, H1, H2, nullptr, 0, h1, 0, bf, 0};
-        launch_gemm(g, st, bf);
+        // d1 = (d2 W2^T) where h1 > 0: needs d2 only, like the product above, so both go in one launch
+        const GemmArgs back{d2, 0, H2, 1, -1, theta + m->off_w[1], 1, H2, d1, H1, B, H1, H2, nullptr, 0, h1, 0, bf, 0};
+        launch_gemm(g, st, bf, &back);
         // [gW1 ; gb1] = [X ; 1]^T d1
         g = GemmArgs{x, elem == 2, (int64_t)ld, 1, F, d1, H1, 1, grad + m->off_w[0], H1, F + 1, H1, B, nullptr, 0, nullptr,
                      bf, 0, 0};
