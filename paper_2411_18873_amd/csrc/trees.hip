@@ -67,7 +67,19 @@ __global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__rest
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const uint64_t cand = (uint64_t)tile * BLOCK + tid;
         __syncthreads(); // the previous tile's walks are over
-        for (int f = 0; f < n_feat; ++f) x_lds[f * BLOCK + tid] = cand < n ? feat_e[(uint64_t)f * ld + cand] : (Elem)0;
+        // Sixteen rows at a time, every load and store unconditional (a lane beyond n re-reads the last candidate,
+        // a row beyond n_feat the last row, and stores that same value where it already is): with a condition on
+        // either side the compiler waits for each load right before its store, one round trip per feature.
+        {
+            const uint64_t col = cand < n ? cand : n - 1;
+            for (int f0 = 0; f0 < n_feat; f0 += 16) {
+                Elem v[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) v[k] = feat_e[(uint64_t)min(f0 + k, n_feat - 1) * ld + col];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) x_lds[min(f0 + k, n_feat - 1) * BLOCK + tid] = v[k];
+            }
+        }
         float acc = base;
         for (int t0 = 0; t0 < n_trees; t0 += chunk_trees) {
             const int in_chunk = min(chunk_trees, n_trees - t0);
