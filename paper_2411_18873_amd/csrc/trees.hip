@@ -86,35 +86,55 @@ __global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__rest
             __syncthreads(); // features staged / previous chunk consumed
             for (uint32_t e = tid; e < (uint32_t)in_chunk * nodes; e += BLOCK) {
                 const uint32_t f = min((uint32_t)node_feat[(uint64_t)t0 * nodes + e], (uint32_t)n_feat - 1u);
-                node_lds[e] = make_uint2(__float_as_uint(node_thr[(uint64_t)t0 * nodes + e]), f);
+                node_lds[e] = make_uint2(__float_as_uint(node_thr[(uint64_t)t0 * nodes + e]), f * (uint32_t)(BLOCK * sizeof(Elem)));
             }
             for (uint32_t e = tid; e < (uint32_t)in_chunk * leaves; e += BLOCK) leaf_lds[e] = leaf[(uint64_t)t0 * leaves + e];
             __syncthreads();
-            auto x_of = [&](uint32_t f) {
-                const Elem v = x_lds[f * BLOCK + tid];
+            // feature value from the byte offset of its row (a node's second word)
+            auto x_of = [&](uint32_t row_bytes) {
+                const Elem v = *reinterpret_cast<const Elem *>(lds + row_bytes + tid * sizeof(Elem));
                 if (FEAT_BF16) return __uint_as_float((uint32_t)v << 16);
                 else return (float)v;
             };
+            // Nodes are numbered from 1 here (children of i: 2i and 2i + 1), so that one step is
+            // i <- i + i + (x < t ? 0 : 1): a compare into a scalar mask and an add with that mask as carry-in,
+            // two vector instructions, written out because the compiler makes three of it.  Four walks per
+            // statement keep the compares four instructions ahead of the adds that read their masks.
             int t = 0;
             for (; t + WALKS <= in_chunk; t += WALKS) {
-                uint32_t j[WALKS];
+                uint32_t i[WALKS];
 #pragma unroll
-                for (int w = 0; w < WALKS; ++w) j[w] = 0;
-                const uint2 *first = node_lds + (size_t)t * nodes;
+                for (int w = 0; w < WALKS; ++w) i[w] = 1;
+                const uint2 *first = node_lds + (size_t)t * nodes - 1; // node i of tree w at first[w * nodes + i]
                 for (int l = 0; l < depth; ++l) {
                     uint2 nd[WALKS];
 #pragma unroll
-                    for (int w = 0; w < WALKS; ++w) nd[w] = first[(size_t)w * nodes + j[w]];
+                    for (int w = 0; w < WALKS; ++w) nd[w] = first[(size_t)w * nodes + i[w]];
                     float x[WALKS];
 #pragma unroll
                     for (int w = 0; w < WALKS; ++w) x[w] = x_of(nd[w].y);
 #pragma unroll
-                    for (int w = 0; w < WALKS; ++w) j[w] = 2 * j[w] + (x[w] < __uint_as_float(nd[w].x) ? 1u : 2u);
+                    for (int w = 0; w < WALKS; w += 4) {
+                        unsigned long long m0, m1, m2, m3;
+                        asm("v_cmp_nlt_f32_e64 %4, %8, %12\n\t"
+                            "v_cmp_nlt_f32_e64 %5, %9, %13\n\t"
+                            "v_cmp_nlt_f32_e64 %6, %10, %14\n\t"
+                            "v_cmp_nlt_f32_e64 %7, %11, %15\n\t"
+                            "v_addc_co_u32_e64 %0, %4, %0, %0, %4\n\t"
+                            "v_addc_co_u32_e64 %1, %5, %1, %1, %5\n\t"
+                            "v_addc_co_u32_e64 %2, %6, %2, %2, %6\n\t"
+                            "v_addc_co_u32_e64 %3, %7, %3, %3, %7"
+                            : "+v"(i[w]), "+v"(i[w + 1]), "+v"(i[w + 2]), "+v"(i[w + 3]), "=&s"(m0), "=&s"(m1), "=&s"(m2),
+                              "=&s"(m3)
+                            : "v"(x[w]), "v"(x[w + 1]), "v"(x[w + 2]), "v"(x[w + 3]), "v"(__uint_as_float(nd[w].x)),
+                              "v"(__uint_as_float(nd[w + 1].x)), "v"(__uint_as_float(nd[w + 2].x)),
+                              "v"(__uint_as_float(nd[w + 3].x)));
+                    }
                 }
                 const float *lf = leaf_lds + (size_t)t * leaves;
                 float v[WALKS];
 #pragma unroll
-                for (int w = 0; w < WALKS; ++w) v[w] = lf[(size_t)w * leaves + j[w] - nodes];
+                for (int w = 0; w < WALKS; ++w) v[w] = lf[(size_t)w * leaves + i[w] - leaves]; // i in [2^d, 2^(d+1))
 #pragma unroll
                 for (int w = 0; w < WALKS; ++w) acc = acc + v[w]; // tree order
             }

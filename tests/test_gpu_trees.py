@@ -103,6 +103,39 @@ def test_score_edge_cases(G, golden):
     assert out.cpu().numpy()[5] == 7.0
 
 
+def test_score_special_values_and_thresholds_between_bfloat16_values(G):
+    """bfloat16 features are compared as integer keys against thresholds rounded up to bfloat16.  Every decision
+    must stay that of the float comparison x < t: negative values, both zeros, infinities, NaN (never below
+    anything), subnormals, and thresholds on, just above and just below a bfloat16 value."""
+    rng = np.random.default_rng(5)
+    n, n_feat, depth, T = 4096, 16, 4, 24
+    special = np.array([0x0000, 0x8000, 0x7F80, 0xFF80, 0x7FC0, 0xFFC0, 0x0001, 0x8001, 0x0080, 0x8080, 0x3F80, 0xBF80,
+                        0x7F7F, 0xFF7F, 0x4000, 0xC000], dtype=np.uint16)
+    b16 = rng.integers(0, 1 << 16, size=(n_feat, n), dtype=np.uint16)
+    b16[:, :512] = special[rng.integers(0, special.size, size=(n_feat, 512))]
+    x = oracle.bf16_bits_to_f32(b16)
+    nodes, leaves = (1 << depth) - 1, 1 << depth
+    nf = rng.integers(0, n_feat, size=(T, nodes)).astype(np.uint8)
+    # thresholds: values the features take, and their float neighbours on either side; zeros, infinities, NaN
+    picks = x[rng.integers(0, n_feat, size=(T, nodes)), rng.integers(0, n, size=(T, nodes))].astype(np.float32)
+    picks[~np.isfinite(picks)] = 1.5
+    side = rng.integers(0, 3, size=(T, nodes))
+    nt = np.where(side == 0, picks, np.where(side == 1, np.nextafter(picks, np.float32(np.inf)),
+                                             np.nextafter(picks, np.float32(-np.inf)))).astype(np.float32)
+    extra = np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1e-40, -1e-40, 3.0e38, -3.0e38], dtype=np.float32)
+    where = rng.random((T, nodes)) < 0.2
+    nt[where] = extra[rng.integers(0, extra.size, size=where.sum())]
+    lf = (rng.standard_normal((T, leaves)) * 0.1).astype(np.float32)
+    trees = eck.Trees(n_feat, depth, T, 0.25)
+    _load(trees, G, nf, nt, lf)
+    with np.errstate(invalid="ignore"):
+        want = oracle.trees_predict(n_feat, depth, nf, nt, lf, 0.25, x, n=n, fp32_sequential=True).astype(np.float32)
+    got_bf16 = _score(trees, G.bf16_dev(b16), n)
+    assert np.array_equal(got_bf16, want)
+    got_f32 = _score(trees, G.to_dev(x), n)       # the float path on the same values
+    assert np.array_equal(got_f32, want)
+
+
 def _boost_gpu(trees, feat_dev, e, rounds, eta, lam):
     snr = torch.zeros(1, dtype=torch.float32, device="cuda")
     loss = torch.zeros(1, dtype=torch.float32, device="cuda")
