@@ -47,8 +47,9 @@ __device__ __forceinline__ float feature_value(const void *feat, int is_bf16, ui
 // LDS per tree of a chunk: nodes as (threshold bits, feature) pairs, then the leaves
 __host__ __device__ inline uint32_t tree_lds_bytes(int depth) { return ((1u << depth) - 1u) * 8u + (1u << depth) * 4u; }
 
-template <bool FEAT_BF16>
-__global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__restrict__ node_feat,
+// SCORE_BLOCK: candidates, and threads, per block
+template <bool FEAT_BF16, int SCORE_BLOCK>
+__global__ __launch_bounds__(SCORE_BLOCK) void tree_score_kernel(const uint8_t *__restrict__ node_feat,
                                                           const float *__restrict__ node_thr,
                                                           const float *__restrict__ leaf, int n_feat, int depth,
                                                           int n_trees, int chunk_trees, float base,
@@ -58,14 +59,14 @@ __global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__rest
     using Elem = typename std::conditional<FEAT_BF16, uint16_t, float>::type;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const uint32_t nodes = (1u << depth) - 1u, leaves = 1u << depth;
-    Elem *x_lds = reinterpret_cast<Elem *>(lds); // [n_feat][BLOCK]
-    uint2 *node_lds = reinterpret_cast<uint2 *>(lds + (size_t)n_feat * BLOCK * sizeof(Elem)); // [chunk][nodes]
+    Elem *x_lds = reinterpret_cast<Elem *>(lds); // [n_feat][SCORE_BLOCK]
+    uint2 *node_lds = reinterpret_cast<uint2 *>(lds + (size_t)n_feat * SCORE_BLOCK * sizeof(Elem)); // [chunk][nodes]
     float *leaf_lds = reinterpret_cast<float *>(node_lds + (size_t)chunk_trees * nodes);      // [chunk][leaves]
     const int tid = threadIdx.x;
     const Elem *feat_e = reinterpret_cast<const Elem *>(feat);
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const uint64_t cand = (uint64_t)tile * BLOCK + tid;
+        const uint64_t cand = (uint64_t)tile * SCORE_BLOCK + tid;
         __syncthreads(); // the previous tile's walks are over
         // Sixteen rows at a time, every load and store unconditional (a lane beyond n re-reads the last candidate,
         // a row beyond n_feat the last row, and stores that same value where it already is): with a condition on
@@ -77,18 +78,18 @@ __global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__rest
 #pragma unroll
                 for (int k = 0; k < 16; ++k) v[k] = feat_e[(uint64_t)min(f0 + k, n_feat - 1) * ld + col];
 #pragma unroll
-                for (int k = 0; k < 16; ++k) x_lds[min(f0 + k, n_feat - 1) * BLOCK + tid] = v[k];
+                for (int k = 0; k < 16; ++k) x_lds[min(f0 + k, n_feat - 1) * SCORE_BLOCK + tid] = v[k];
             }
         }
         float acc = base;
         for (int t0 = 0; t0 < n_trees; t0 += chunk_trees) {
             const int in_chunk = min(chunk_trees, n_trees - t0);
             __syncthreads(); // features staged / previous chunk consumed
-            for (uint32_t e = tid; e < (uint32_t)in_chunk * nodes; e += BLOCK) {
+            for (uint32_t e = tid; e < (uint32_t)in_chunk * nodes; e += SCORE_BLOCK) {
                 const uint32_t f = min((uint32_t)node_feat[(uint64_t)t0 * nodes + e], (uint32_t)n_feat - 1u);
-                node_lds[e] = make_uint2(__float_as_uint(node_thr[(uint64_t)t0 * nodes + e]), f * (uint32_t)(BLOCK * sizeof(Elem)));
+                node_lds[e] = make_uint2(__float_as_uint(node_thr[(uint64_t)t0 * nodes + e]), f * (uint32_t)(SCORE_BLOCK * sizeof(Elem)));
             }
-            for (uint32_t e = tid; e < (uint32_t)in_chunk * leaves; e += BLOCK) leaf_lds[e] = leaf[(uint64_t)t0 * leaves + e];
+            for (uint32_t e = tid; e < (uint32_t)in_chunk * leaves; e += SCORE_BLOCK) leaf_lds[e] = leaf[(uint64_t)t0 * leaves + e];
             __syncthreads();
             // feature value from the byte offset of its row (a node's second word)
             auto x_of = [&](uint32_t row_bytes) {
@@ -102,17 +103,48 @@ __global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__rest
             // statement keep the compares four instructions ahead of the adds that read their masks.
             int t = 0;
             for (; t + WALKS <= in_chunk; t += WALKS) {
-                uint32_t i[WALKS];
+                uint32_t i[WALKS], upper[WALKS];
 #pragma unroll
-                for (int w = 0; w < WALKS; ++w) i[w] = 1;
+                for (int w = 0; w < WALKS; ++w) {
+                    i[w] = 1;
+                    upper[w] = 0;
+                }
                 const uint2 *first = node_lds + (size_t)t * nodes - 1; // node i of tree w at first[w * nodes + i]
                 for (int l = 0; l < depth; ++l) {
                     uint2 nd[WALKS];
 #pragma unroll
                     for (int w = 0; w < WALKS; ++w) nd[w] = first[(size_t)w * nodes + i[w]];
                     float x[WALKS];
+                    if constexpr (FEAT_BF16 && WALKS == 8) {
+                        // A bfloat16 is the upper half of the float of the same value.  The load below writes
+                        // only the upper half of its destination, whose lower half is zero from the start and
+                        // stays so: the float arrives ready, without a shift.  The compiler has no such load, so
+                        // it is issued here, followed by its wait; nothing but these two statements touches the
+                        // eight registers in between.
+                        uint32_t at[WALKS];
 #pragma unroll
-                    for (int w = 0; w < WALKS; ++w) x[w] = x_of(nd[w].y);
+                        for (int w = 0; w < WALKS; ++w) at[w] = nd[w].y + tid * 2;
+                        asm volatile("ds_read_u16_d16_hi %0, %8\n\t"
+                                     "ds_read_u16_d16_hi %1, %9\n\t"
+                                     "ds_read_u16_d16_hi %2, %10\n\t"
+                                     "ds_read_u16_d16_hi %3, %11\n\t"
+                                     "ds_read_u16_d16_hi %4, %12\n\t"
+                                     "ds_read_u16_d16_hi %5, %13\n\t"
+                                     "ds_read_u16_d16_hi %6, %14\n\t"
+                                     "ds_read_u16_d16_hi %7, %15"
+                                     : "+v"(upper[0]), "+v"(upper[1]), "+v"(upper[2]), "+v"(upper[3]), "+v"(upper[4]),
+                                       "+v"(upper[5]), "+v"(upper[6]), "+v"(upper[7])
+                                     : "v"(at[0]), "v"(at[1]), "v"(at[2]), "v"(at[3]), "v"(at[4]), "v"(at[5]), "v"(at[6]),
+                                       "v"(at[7]));
+                        asm volatile("s_waitcnt lgkmcnt(0)"
+                                     : "+v"(upper[0]), "+v"(upper[1]), "+v"(upper[2]), "+v"(upper[3]), "+v"(upper[4]),
+                                       "+v"(upper[5]), "+v"(upper[6]), "+v"(upper[7]));
+#pragma unroll
+                        for (int w = 0; w < WALKS; ++w) x[w] = __uint_as_float(upper[w]);
+                    } else {
+#pragma unroll
+                        for (int w = 0; w < WALKS; ++w) x[w] = x_of(nd[w].y);
+                    }
 #pragma unroll
                     for (int w = 0; w < WALKS; w += 4) {
                         unsigned long long m0, m1, m2, m3;
@@ -155,18 +187,23 @@ __global__ __launch_bounds__(BLOCK) void tree_score_kernel(const uint8_t *__rest
 int32_t launch_score(const eck_trees *m, int n_trees, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n,
                      float *out, hipStream_t st)
 {
-    const uint64_t tiles64 = (n + BLOCK - 1) / BLOCK;
-    if (tiles64 > 0xFFFFFFFFull) return ECK_EUNSUPPORTED;
     const size_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
-    const size_t x_bytes = (size_t)m->n_feat * BLOCK * elem;
+    const size_t per_tree = tree_lds_bytes(m->depth);
+    const size_t lds_cu = 156 * 1024;
+    // 512 candidates per block when two such blocks fit a compute unit (a staged chunk of trees then serves
+    // twice as many candidates; measured 2.49 against 2.70 ms for 256, and 2.71 ms for one block of 1024), else 256
+    const size_t floor512 = (size_t)m->n_feat * 512 * elem + WALKS * per_tree;
+    const int block = 2 * floor512 <= lds_cu ? 512 : 256;
+    const uint64_t tiles64 = (n + block - 1) / block;
+    if (tiles64 > 0xFFFFFFFFull) return ECK_EUNSUPPORTED;
+    const size_t x_bytes = (size_t)m->n_feat * block * elem;
     // Trees per chunk.  The walks are chains of dependent LDS reads, so what counts is how many wavefronts a
     // compute unit holds: the smallest chunk (one group of simultaneous walks) beside the feature tile lets
     // the most blocks share the 160 KB; blocks per unit = what fits, chunk = what is left of a block's share.
-    const size_t per_tree = tree_lds_bytes(m->depth);
-    const size_t lds_cu = 156 * 1024, floor_bytes = x_bytes + WALKS * per_tree;
+    const size_t floor_bytes = x_bytes + WALKS * per_tree;
     if (floor_bytes > lds_cu) return ECK_EUNSUPPORTED;
     size_t blocks_cu = lds_cu / floor_bytes;
-    if (blocks_cu > 8) blocks_cu = 8; // 2048 threads per unit
+    if (blocks_cu > (size_t)(2048 / block)) blocks_cu = 2048 / block; // 2048 threads per unit
     const size_t share = lds_cu / blocks_cu;
     int chunk = (int)((share - x_bytes) / per_tree);
     chunk -= chunk % WALKS;
@@ -179,10 +216,11 @@ int32_t launch_score(const eck_trees *m, int n_trees, const void *feat, int32_t 
     const uint32_t n_tiles = (uint32_t)tiles64;
     const uint32_t want = (uint32_t)cus * (uint32_t)blocks_cu;
     const uint32_t grid = n_tiles < want ? n_tiles : want;
-    auto kern = feat_dtype == ECK_BF16 ? tree_score_kernel<true> : tree_score_kernel<false>;
+    auto kern = feat_dtype == ECK_BF16 ? (block == 512 ? tree_score_kernel<true, 512> : tree_score_kernel<true, 256>)
+                                       : (block == 512 ? tree_score_kernel<false, 512> : tree_score_kernel<false, 256>);
     ECK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(BLOCK), lds, st, m->d_feat, m->d_thr, m->d_leaf, m->n_feat, m->depth,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(block), lds, st, m->d_feat, m->d_thr, m->d_leaf, m->n_feat, m->depth,
                        n_trees, chunk, m->base, feat, ld, n, out, n_tiles);
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
