@@ -328,10 +328,17 @@ __global__ __launch_bounds__(1024) void tree_quality_kernel(const float *__restr
 }
 
 // first and second derivative of Eq. (1) in the prediction, as integers of resolution 2^-20
+// (also: every node of the tree about to be built starts as "does not split"; the grid is at least 256 threads,
+// a tree at most 255 nodes)
 __global__ void tree_grad_kernel(const float *__restrict__ p, const float *__restrict__ y, uint64_t n,
-                                 long long *__restrict__ gq, long long *__restrict__ hq, uint32_t *__restrict__ at)
+                                 long long *__restrict__ gq, long long *__restrict__ hq, uint32_t *__restrict__ at,
+                                 uint8_t *__restrict__ nf, float *__restrict__ nt, uint32_t nodes)
 {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nodes) {
+        nf[i] = 0;
+        nt[i] = __builtin_inff();
+    }
     if (i >= n) return;
     const double yi = (double)y[i], d = (double)p[i] - yi;
     gq[i] = quantise(2.0 * d / yi);
@@ -382,63 +389,53 @@ __global__ __launch_bounds__(BLOCK) void tree_hist_lds_kernel(const uint8_t *__r
     }
 }
 
-// One block per node of the level: the split of largest gain.  Wavefront w takes features w, w+16, ...; a lane
-// takes four consecutive bins; prefix sums over the bins by shuffles.  gain(f, b) = GL^2/(HL+lam) +
-// GR^2/(HR+lam) - G^2/(H+lam) in fp64; the largest gain > 0 wins, ties to the lower feature, then the lower
-// bin (the candidate's rank f * 256 + b breaks ties in every comparison).
-constexpr int SPLIT_BLOCK = 1024;
-__global__ __launch_bounds__(SPLIT_BLOCK) void tree_split_kernel(const unsigned long long *__restrict__ hist, int n_feat,
-                                                          uint32_t first_node, double lam, uint8_t *__restrict__ nf,
-                                                          float *__restrict__ nt, const BoostScalars *sc)
+// The split of largest gain, in two parts.  tree_split_kernel: one block per (node of the level, group of four
+// features), a wavefront per feature, a lane per four consecutive bins; prefix sums over the bins by shuffles.
+// gain(f, b) = GL^2/(HL+lam) + GR^2/(HR+lam) - G^2/(H+lam) in fp64; the largest gain > 0 wins, ties to the
+// lower feature, then the lower bin (the candidate's rank f * 256 + b breaks ties in every comparison).  The
+// block leaves its best (gain, rank) in `partial`; the kernel that moves the pairs to their children compares
+// the groups' results.  The fp64 divisions of a node are thus spread over up to 64 compute units instead of
+// one.  Every cell read is set back to zero, so that the histogram buffer is clear again for the next level
+// without a pass of its own.
+struct SplitPartial {
+    double gain;
+    uint32_t rank, pad;
+};
+constexpr int SPLIT_FEATS = 4; // features, and wavefronts, per block
+
+__device__ __forceinline__ bool better_split(double og, uint32_t orank, double g, uint32_t rank)
 {
-    const uint32_t r = blockIdx.x, j = first_node + r;
+    return og > g || (og == g && orank < rank);
+}
+
+__global__ __launch_bounds__(SPLIT_FEATS * 64) void tree_split_kernel(unsigned long long *__restrict__ hist, int n_feat,
+                                                                      double lam, SplitPartial *__restrict__ partial)
+{
+    const uint32_t r = blockIdx.x; // node within the level
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const unsigned long long *h = hist + (uint64_t)r * n_feat * BINS * 3;
-    // node totals from feature 0's histogram
-    __shared__ long long tot[3];
-    {
-        long long g = 0, hh = 0, c = 0;
-        if (wave == 0) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const unsigned long long *cell = h + (uint64_t)(4 * lane + q) * 3;
-                g += (long long)cell[0];
-                hh += (long long)cell[1];
-                c += (long long)cell[2];
-            }
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) {
-                g += __shfl_xor(g, off);
-                hh += __shfl_xor(hh, off);
-                c += __shfl_xor(c, off);
-            }
-            if (lane == 0) {
-                tot[0] = g;
-                tot[1] = hh;
-                tot[2] = c;
-            }
-        }
-    }
-    __syncthreads();
-    const long long G = tot[0], H = tot[1], N = tot[2];
-    const double parent = (double)G * (double)G / ((double)H + lam);
+    const int f = blockIdx.y * SPLIT_FEATS + wave;
     double best = 0.0;
     uint32_t best_rank = 0xFFFFFFFFu;
-    for (int f = wave; f < n_feat && N > 1; f += SPLIT_BLOCK / 64) {
+    if (f < n_feat) { // wave-uniform
+        unsigned long long *cells = hist + (((uint64_t)r * n_feat + f) * BINS + 4 * lane) * 3;
         long long g[4], hh[4], c[4];
-        long long sg = 0, sh = 0, scnt = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const unsigned long long *cell = h + ((uint64_t)f * BINS + 4 * lane + q) * 3;
-            sg += (long long)cell[0];
-            sh += (long long)cell[1];
-            scnt += (long long)cell[2];
-            g[q] = sg;
-            hh[q] = sh;
-            c[q] = scnt;
+            g[q] = (long long)cells[3 * q];
+            hh[q] = (long long)cells[3 * q + 1];
+            c[q] = (long long)cells[3 * q + 2];
         }
-        // exclusive prefix of the lanes' totals
-        long long pg = sg, ph = sh, pc = scnt;
+#pragma unroll
+        for (int q = 0; q < 12; ++q) cells[q] = 0;
+#pragma unroll
+        for (int q = 1; q < 4; ++q) {
+            g[q] += g[q - 1];
+            hh[q] += hh[q - 1];
+            c[q] += c[q - 1];
+        }
+        // inclusive prefix of the lanes' totals; its last lane holds the node's totals (every pair of the node is
+        // in exactly one bin of every feature, so each feature's histogram sums to the same G, H, N)
+        long long pg = g[3], ph = hh[3], pc = c[3];
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
             const long long ug = __shfl_up(pg, off), uh = __shfl_up(ph, off), uc = __shfl_up(pc, off);
@@ -448,63 +445,90 @@ __global__ __launch_bounds__(SPLIT_BLOCK) void tree_split_kernel(const unsigned 
                 pc += uc;
             }
         }
-        pg -= sg;
-        ph -= sh;
-        pc -= scnt;
+        const long long G = __shfl(pg, 63), H = __shfl(ph, 63), N = __shfl(pc, 63);
+        if (N > 1) {
+            const double parent = (double)G * (double)G / ((double)H + lam);
+            pg -= g[3];
+            ph -= hh[3];
+            pc -= c[3];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int b = 4 * lane + q;
-            const long long GL = pg + g[q], HL = ph + hh[q], NL = pc + c[q];
-            if (b >= 255 || NL == 0 || NL == N) continue;
-            const long long GR = G - GL, HR = H - HL;
-            const double gain = (double)GL * (double)GL / ((double)HL + lam) +
-                                (double)GR * (double)GR / ((double)HR + lam) - parent;
-            const uint32_t rank = (uint32_t)f * BINS + (uint32_t)b;
-            if (gain > best || (gain == best && gain > 0.0 && rank < best_rank)) {
-                best = gain;
-                best_rank = rank;
+            for (int q = 0; q < 4; ++q) {
+                const int b = 4 * lane + q;
+                const long long GL = pg + g[q], HL = ph + hh[q], NL = pc + c[q];
+                if (b >= 255 || NL == 0 || NL == N) continue;
+                const long long GR = G - GL, HR = H - HL;
+                const double gain = (double)GL * (double)GL / ((double)HL + lam) +
+                                    (double)GR * (double)GR / ((double)HR + lam) - parent;
+                const uint32_t rank = (uint32_t)f * BINS + (uint32_t)b;
+                if (gain > best || (gain == best && gain > 0.0 && rank < best_rank)) {
+                    best = gain;
+                    best_rank = rank;
+                }
             }
         }
     }
-    // block argmax, lower rank on equal gain
-    __shared__ double s_gain[SPLIT_BLOCK];
-    __shared__ uint32_t s_rank[SPLIT_BLOCK];
-    s_gain[threadIdx.x] = best;
-    s_rank[threadIdx.x] = best_rank;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const double og = __shfl_xor(best, off);
+        const uint32_t orank = __shfl_xor(best_rank, off);
+        if (better_split(og, orank, best, best_rank)) {
+            best = og;
+            best_rank = orank;
+        }
+    }
+    __shared__ double s_gain[SPLIT_FEATS];
+    __shared__ uint32_t s_rank[SPLIT_FEATS];
+    if (lane == 0) {
+        s_gain[wave] = best;
+        s_rank[wave] = best_rank;
+    }
     __syncthreads();
-    for (int off = SPLIT_BLOCK / 2; off > 0; off >>= 1) {
-        if ((int)threadIdx.x < off) {
-            const double og = s_gain[threadIdx.x + off];
-            const uint32_t orank = s_rank[threadIdx.x + off];
-            if (og > s_gain[threadIdx.x] || (og == s_gain[threadIdx.x] && orank < s_rank[threadIdx.x])) {
-                s_gain[threadIdx.x] = og;
-                s_rank[threadIdx.x] = orank;
-            }
-        }
-        __syncthreads();
-    }
     if (threadIdx.x == 0) {
-        const uint32_t rank = s_rank[0];
-        if (sc->bad || rank == 0xFFFFFFFFu || !(s_gain[0] > 0.0)) {
-            nf[j] = 0;
-            nt[j] = __builtin_inff();
-        } else {
-            nf[j] = (uint8_t)(rank / BINS);
-            nt[j] = (float)((rank % BINS) + 1) * 0.25f;
-        }
+#pragma unroll
+        for (int w = 1; w < SPLIT_FEATS; ++w)
+            if (better_split(s_gain[w], s_rank[w], best, best_rank)) {
+                best = s_gain[w];
+                best_rank = s_rank[w];
+            }
+        SplitPartial out;
+        out.gain = best;
+        out.rank = best_rank;
+        out.pad = 0;
+        partial[(uint64_t)r * gridDim.y + blockIdx.y] = out;
     }
 }
 
-// move every pair to the child its node's test sends it to
+// Move every pair to the child its node's test sends it to.  The node's test is settled here, from the feature
+// groups' partial results: every pair standing on a node arrives at the same (feature, threshold) and writes it
+// (equal values, so the order does not matter); nodes no pair stands on keep "does not split".
 __global__ void tree_partition_kernel(const void *__restrict__ feat, int is_bf16, uint64_t ld, uint64_t n_pairs,
-                                      const uint8_t *__restrict__ nf, const float *__restrict__ nt,
+                                      const SplitPartial *__restrict__ partial, uint32_t groups, uint32_t first_node,
+                                      const BoostScalars *sc, uint8_t *__restrict__ nf, float *__restrict__ nt,
                                       uint32_t *__restrict__ at)
 {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_pairs) return;
     const uint32_t j = at[i];
-    const float x = feature_value(feat, is_bf16, (uint64_t)nf[j] * ld + i);
-    at[i] = 2 * j + (x < nt[j] ? 1u : 2u);
+    const SplitPartial *mine = partial + (uint64_t)(j - first_node) * groups;
+    double best = 0.0;
+    uint32_t best_rank = 0xFFFFFFFFu;
+    for (uint32_t g = 0; g < groups; ++g) {
+        const SplitPartial o = mine[g];
+        if (better_split(o.gain, o.rank, best, best_rank)) {
+            best = o.gain;
+            best_rank = o.rank;
+        }
+    }
+    uint32_t f = 0;
+    float thr = __builtin_inff();
+    if (!sc->bad && best_rank != 0xFFFFFFFFu && best > 0.0) {
+        f = best_rank / BINS;
+        thr = (float)((best_rank % BINS) + 1) * 0.25f;
+    }
+    nf[j] = (uint8_t)f;
+    nt[j] = thr;
+    const float x = feature_value(feat, is_bf16, (uint64_t)f * ld + i);
+    at[i] = 2 * j + (x < thr ? 1u : 2u);
 }
 
 // one block: statistics of every leaf by integer atomics in LDS, then w = -eta G / (H + lam) (fp64 -> fp32)
@@ -546,7 +570,7 @@ __global__ void tree_finish_kernel(const BoostScalars *sc, float *snr_out, float
 }
 
 struct BoostWs {
-    uint64_t scalars, y, p, gq, hq, at, bins, hist, total;
+    uint64_t scalars, y, p, gq, hq, at, bins, hist, partial, total;
 };
 
 BoostWs boost_layout(const eck_trees *m, uint64_t n_pairs)
@@ -562,6 +586,7 @@ BoostWs boost_layout(const eck_trees *m, uint64_t n_pairs)
     w.at = o; o = up(o + n_pairs * 4);
     w.bins = o; o = up(o + n_pairs * (uint64_t)m->n_feat);
     w.hist = o; o = up(o + ((uint64_t)1 << (m->depth - 1)) * m->n_feat * BINS * 3 * 8);
+    w.partial = o; o = up(o + ((uint64_t)1 << (m->depth - 1)) * ((m->n_feat + SPLIT_FEATS - 1) / SPLIT_FEATS) * sizeof(SplitPartial));
     w.total = o;
     return w;
 }
@@ -681,6 +706,8 @@ extern "C" int32_t treemodel_update(eck_trees *m, const void *feat, int32_t feat
     uint32_t *at = reinterpret_cast<uint32_t *>(base + w.at);
     uint8_t *bins = reinterpret_cast<uint8_t *>(base + w.bins);
     unsigned long long *hist = reinterpret_cast<unsigned long long *>(base + w.hist);
+    SplitPartial *partial = reinterpret_cast<SplitPartial *>(base + w.partial);
+    const unsigned split_groups = (unsigned)((m->n_feat + SPLIT_FEATS - 1) / SPLIT_FEATS);
     const int is_bf16 = feat_dtype == ECK_BF16;
     const uint32_t nodes = (1u << m->depth) - 1u, leaves = 1u << m->depth;
     const unsigned pair_blocks = (unsigned)((n_pairs + 255) / 256);
@@ -693,16 +720,19 @@ extern "C" int32_t treemodel_update(eck_trees *m, const void *feat, int32_t feat
     hipLaunchKernelGGL(tree_quality_kernel, dim3(1), dim3(1024), 0, st, p, y, n_pairs, 0, sc);
     hipLaunchKernelGGL(tree_bins_kernel, dim3(pair_blocks, m->n_feat), dim3(256), 0, st, feat, is_bf16, ld, n_pairs,
                        m->n_feat, bins);
+    {
+        // the histogram buffer starts clear; from then on the split kernel clears what it reads
+        const uint64_t words = ((uint64_t)1 << (m->depth - 1)) * m->n_feat * BINS * 3;
+        hipLaunchKernelGGL(tree_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, hist, words);
+    }
     for (int32_t r = 0; r < n_rounds; ++r) {
         const size_t t = (size_t)m->n_trees + r;
         uint8_t *nf = m->d_feat + t * nodes;
         float *nt = m->d_thr + t * nodes;
         float *lw = m->d_leaf + t * leaves;
-        hipLaunchKernelGGL(tree_grad_kernel, dim3(pair_blocks), dim3(256), 0, st, p, y, n_pairs, gq, hq, at);
+        hipLaunchKernelGGL(tree_grad_kernel, dim3(pair_blocks), dim3(256), 0, st, p, y, n_pairs, gq, hq, at, nf, nt, nodes);
         for (int l = 0; l < m->depth; ++l) {
             const uint32_t level_nodes = 1u << l, first = level_nodes - 1u;
-            const uint64_t words = (uint64_t)level_nodes * m->n_feat * BINS * 3;
-            hipLaunchKernelGGL(tree_zero_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st, hist, words);
             {
                 unsigned slices = (unsigned)(n_pairs / 2048);
                 slices = slices < 1 ? 1 : (slices > 64 ? 64 : slices);
@@ -710,10 +740,10 @@ extern "C" int32_t treemodel_update(eck_trees *m, const void *feat, int32_t feat
                 hipLaunchKernelGGL(tree_hist_lds_kernel, dim3(slices, m->n_feat, groups), dim3(BLOCK), 0, st, bins, gq, hq,
                                    at, n_pairs, m->n_feat, first, level_nodes, hist);
             }
-            hipLaunchKernelGGL(tree_split_kernel, dim3(level_nodes), dim3(SPLIT_BLOCK), 0, st, hist, m->n_feat, first, lam, nf,
-                               nt, sc);
-            hipLaunchKernelGGL(tree_partition_kernel, dim3(pair_blocks), dim3(256), 0, st, feat, is_bf16, ld, n_pairs, nf,
-                               nt, at);
+            hipLaunchKernelGGL(tree_split_kernel, dim3(level_nodes, split_groups), dim3(SPLIT_FEATS * 64), 0, st, hist,
+                               m->n_feat, lam, partial);
+            hipLaunchKernelGGL(tree_partition_kernel, dim3(pair_blocks), dim3(256), 0, st, feat, is_bf16, ld, n_pairs,
+                               partial, split_groups, first, sc, nf, nt, at);
         }
         hipLaunchKernelGGL(tree_leaf_kernel, dim3(1), dim3(1024), 0, st, gq, hq, at, n_pairs, nodes, leaves, (double)eta,
                            lam, lw, sc);
