@@ -156,42 +156,47 @@ __global__ __launch_bounds__(256 * KG) void gemm_mfma_kernel(GemmArgs first, Gem
     const bool a_k_fast = g.sa_k == 1, b_k_fast = g.sb_k == 1;
     constexpr int PER = TM * MK / 256; // elements per thread per operand per stage
 
-    float ra[PER], rb[PER];
+    // fetch() only loads: every address is clamped into the operand, nothing is decided on what arrives, so the
+    // 2 * PER loads of a stage are in flight together (a value that is tested, or loaded under a condition, is
+    // waited for on the spot).  stage() then zeroes what lies outside M, N, K, sets the row of ones, converts
+    // and stores to the LDS.
+    uint32_t ra[PER], rb[PER]; // raw bits as loaded
+    int fetched_k0 = 0;
+    const int last_a_row = g.a_ones_row == g.M - 1 ? g.M - 2 : g.M - 1; // last row of A that is in memory
     auto fetch = [&](int k0) {
+        fetched_k0 = k0;
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             const int e = tid + 256 * q;
             {
                 const int m = a_k_fast ? e / MK : e % TM, k = a_k_fast ? e % MK : e / TM;
-                const int gm = m0 + m, gk = k0 + k;
-                float v = 0.0f;
-                if (gm < g.M && gk < g.K) {
-                    if (gm == g.a_ones_row) v = 1.0f;
-                    else {
-                        const int64_t at = (int64_t)gm * g.sa_m + (int64_t)gk * g.sa_k;
-                        v = g.a_is_bf16 ? __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(g.A)[at] << 16)
-                                        : reinterpret_cast<const float *>(g.A)[at];
-                    }
-                }
-                ra[q] = v;
+                const int gm = max(min(m0 + m, last_a_row), 0), gk = min(k0 + k, g.K - 1);
+                const int64_t at = (int64_t)gm * g.sa_m + (int64_t)gk * g.sa_k;
+                ra[q] = g.a_is_bf16 ? (uint32_t)reinterpret_cast<const uint16_t *>(g.A)[at]
+                                    : reinterpret_cast<const uint32_t *>(g.A)[at];
             }
             {
                 const int n = b_k_fast ? e / MK : e % TN, k = b_k_fast ? e % MK : e / TN;
-                const int gn = n0 + n, gk = k0 + k;
-                float v = 0.0f;
-                if (gn < g.N && gk < g.K) v = g.B[(int64_t)gk * g.sb_k + (int64_t)gn * g.sb_n];
-                rb[q] = v;
+                const int gn = min(n0 + n, g.N - 1), gk = min(k0 + k, g.K - 1);
+                rb[q] = reinterpret_cast<const uint32_t *>(g.B)[(int64_t)gk * g.sb_k + (int64_t)gn * g.sb_n];
             }
         }
     };
     auto stage = [&]() {
+        const int k0 = fetched_k0;
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             const int e = tid + 256 * q;
             const int m = a_k_fast ? e / MK : e % TM, ka = a_k_fast ? e % MK : e / TM;
-            As[m * MLD + ka] = to_bf16_bits(ra[q]);
+            const int gm = m0 + m;
+            float va = __uint_as_float(g.a_is_bf16 ? ra[q] << 16 : ra[q]);
+            if (gm == g.a_ones_row) va = 1.0f;
+            if (gm >= g.M || k0 + ka >= g.K) va = 0.0f;
+            As[m * MLD + ka] = to_bf16_bits(va);
             const int n = b_k_fast ? e / MK : e % TN, kb = b_k_fast ? e % MK : e / TN;
-            Bs[n * MLD + kb] = to_bf16_bits(rb[q]);
+            float vb = __uint_as_float(rb[q]);
+            if (n0 + n >= g.N || k0 + kb >= g.K) vb = 0.0f;
+            Bs[n * MLD + kb] = to_bf16_bits(vb);
         }
     };
 
