@@ -611,7 +611,7 @@ template <int OUT_DTYPE, bool TABLES_IN_LDS, int N_FEAT, bool WANT_RAW, bool XRE
 __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces, const uint16_t *__restrict__ genes,
                                                        uint64_t ld, uint64_t n, void *__restrict__ feat_out,
                                                        uint64_t *__restrict__ raw_out,
-                                                       uint8_t *__restrict__ legal_out)
+                                                       uint8_t *__restrict__ legal_out, int n_genes)
 {
     extern __shared__ uint2 lds_tables[];
     const unsigned char *blob = spaces.dev[blockIdx.y];
@@ -627,7 +627,9 @@ __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces,
     {
         const uint64_t col = in_space < n ? i : block_col;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) g[j] = genes[(uint64_t)(j < p.n_genes ? j : 0) * ld + col];
+        // (the number of genes comes with the kernel arguments, the same for every space of a batch, so these
+        // loads do not wait for the space's parameters)
+        for (int j = 0; j < 8; ++j) g[j] = genes[(uint64_t)(j < n_genes ? j : 0) * ld + col];
     }
     if (TABLES_IN_LDS) {
         // two entries per 16-byte load (the device copy is padded to a multiple of 16 bytes), four per thread
@@ -705,11 +707,24 @@ __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces,
     // per-lane part of every store address is the same small offset.
     float bias = -1023.0f;
     asm("" : "+v"(bias)); // one register for the whole kernel
+    // bfloat16 output: features come in order, an even one waits for its odd neighbour, one instruction converts
+    // both (round to nearest even) and the two halves go to their rows
+    float held = 0.0f;
     auto store_x = [&](int f, float x) {
         if (!feat_out) return;
         const uint64_t row = (uint64_t)f * ld + block_col;
-        if (OUT_DTYPE == ECK_F32) (reinterpret_cast<float *>(feat_out) + row)[threadIdx.x] = x;
-        else (reinterpret_cast<__bf16 *>(feat_out) + row)[threadIdx.x] = (__bf16)x; // round to nearest even
+        if (OUT_DTYPE == ECK_F32) {
+            (reinterpret_cast<float *>(feat_out) + row)[threadIdx.x] = x;
+        } else if (!(f & 1)) {
+            held = x;
+        } else {
+            typedef float float2_t __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+            const float2_t both = {held, x};
+            const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(both, bf16x2_t));
+            (reinterpret_cast<uint16_t *>(feat_out) + (row - ld))[threadIdx.x] = (uint16_t)packed;
+            (reinterpret_cast<uint16_t *>(feat_out) + row)[threadIdx.x] = (uint16_t)(packed >> 16);
+        }
     };
     auto store_raw = [&](int f, uint64_t raw) {
         if (WANT_RAW) (raw_out + ((uint64_t)f * ld + block_col))[threadIdx.x] = raw;
@@ -832,11 +847,14 @@ __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces,
     const uint32_t tail = grid - waves * slots;
     const uint32_t active = min(grid, p.hw_num_cu);
 
+    // loop levels above one trip: every factor is at least 1, so min(f, 2) - 1 is the indicator (a min and an
+    // add per level; comparisons cost a mask, a select and wait states each)
     uint32_t depth = (p.R > 1) + (p.S > 1);
 #pragma unroll
     for (int a = 0; a < NAX; ++a)
 #pragma unroll
-        for (int l = 0; l < 4; ++l) depth += lv.f[a][l] > 1;
+        for (int l = 0; l < 4; ++l) depth += min(lv.f[a][l], 2u);
+    depth -= NAX * 4;
 
     const uint32_t contiguous = p.vec_axis == 3 ? lv.f[3][3] : lv.f[2][3];
     // gcd with a power of two: the power of two dividing both
@@ -935,7 +953,7 @@ int32_t features_launch(const eck_space *const *spaces, uint32_t n_spaces, const
     const bool raw = raw_out != nullptr;
 #define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW, XR)                                                                \
     hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW, XR>), grid, block, lds, st, batch, genes, ld, n, feat_out, \
-                       raw_out, legal_out)
+                       raw_out, legal_out, spaces[0]->prm.n_genes)
 #define ECK_PICK_RAW(DT, INLDS, NF)                    \
     do {                                               \
         if (raw && xred) ECK_LAUNCH_FEATURES(DT, INLDS, NF, true, true);        \
