@@ -737,7 +737,7 @@ __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces,
     auto emit32 = [&](int f, uint32_t raw) {
         if (f >= N_FEAT) return;
         store_raw(f, raw);
-        store_x(f, log2_fixed((double)raw + 1.0, bias));
+        store_x(f, log2_fixed((double)(raw + 1), bias)); // raw <= 2^32 - 2 by the limits checked at space creation
     };
     auto emit64 = [&](int f, uint64_t raw) {
         if (f >= N_FEAT) return;
