@@ -103,6 +103,27 @@ def test_score_edge_cases(G, golden):
     assert out.cpu().numpy()[5] == 7.0
 
 
+@pytest.mark.parametrize("n_feat,depth,T,bf16", [(5, 3, 9, True), (5, 3, 9, False), (200, 6, 20, True), (100, 5, 17, False),
+                                                  (1, 2, 3, True), (33, 8, 10, True)])
+def test_score_feature_counts_off_the_beaten_path(G, n_feat, depth, T, bf16):
+    """Feature counts that are no multiple of the staging width, and ones large enough that only the smaller
+    block of candidates fits a compute unit."""
+    rng = np.random.default_rng(n_feat * 7 + depth)
+    n = 3000 + 11
+    x = rng.uniform(0, 50, size=(n_feat, n + 1)).astype(np.float32)
+    if bf16:
+        bits = (x.view(np.uint32) >> 16).astype(np.uint16)
+        feat_dev, feat_ref = G.bf16_dev(bits), oracle.bf16_bits_to_f32(bits)
+    else:
+        feat_dev, feat_ref = G.to_dev(x), x
+    nf, nt, lf = _random_ensemble(n_feat, depth, T, seed=n_feat + T)
+    trees = eck.Trees(n_feat, depth, T, 0.1)
+    _load(trees, G, nf, nt, lf)
+    got = _score(trees, feat_dev, n)
+    want = oracle.trees_predict(n_feat, depth, nf, nt, lf, 0.1, feat_ref, n=n, fp32_sequential=True)
+    assert np.array_equal(got, want.astype(np.float32))
+
+
 def test_score_special_values_and_thresholds_between_bfloat16_values(G):
     """bfloat16 features are compared as integer keys against thresholds rounded up to bfloat16.  Every decision
     must stay that of the float comparison x < t: negative values, both zeros, infinities, NaN (never below
