@@ -290,3 +290,43 @@ def test_held_out_accuracy_on_the_simulated_meter(G):
     print("held-out: r = %.4f, slope = %.3f, train loss = %.2e" % (r, slope, float(loss.item())))
     assert r > 0.95 and 0.8 < slope < 1.1
     assert np.corrcoef(pred[:n_train], y[:n_train])[0, 1] > r      # fits the training set better, as it must
+
+
+def test_the_two_model_forms_on_the_same_measurements(G):
+    """The model form the workloads prescribe (MLP, refitted by Adam on Eq. (1)) beside the paper's own (boosted
+    trees, Sec. 5.4) on one set of simulated measurements: 3072 kernels of config 2's space to fit, 1024 held out.
+    Both must rank the held-out kernels nearly as the meter does; the figures are printed for the record."""
+    n, n_train = 4096, 3072
+    f32, b16, _ = _pairs(n)
+    energy, _ = synth.simulated_kernel_metrics(f32[:, :n], 21, 0)
+    feat = G.bf16_dev(b16)
+    train = torch.from_numpy(energy[:n_train].copy()).cuda()
+    snr = torch.zeros(1, dtype=torch.float32, device="cuda")
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    y = energy / energy[:n_train].max()
+    held = slice(n_train, n)
+
+    trees = eck.Trees(64, 6, 100, 0.5)
+    ws = torch.empty(eck.treemodel_update_workspace_bytes(trees, n_train), dtype=torch.uint8, device="cuda")
+    eck.treemodel_update(trees, feat, train, 100, snr, loss, ws, eta=0.3, lam=1.0)
+    p_trees = _score(trees, feat, n)
+
+    widths = [64, 256, 256, 1]
+    model = eck.Model(widths, eck.BF16)
+    model.set_state(torch.from_numpy(synth.mlp_theta(widths, 3, bf16=False)).cuda())
+    ws = torch.empty(eck.costmodel_update_workspace_bytes(model, n_train, 512), dtype=torch.uint8, device="cuda")
+    for _ in range(50):                                           # 3000 Adam steps = 500 passes over the pairs
+        eck.costmodel_update(model, feat, train, 60, 512, snr, loss, ws, lr=1e-3)
+    p_mlp = torch.zeros(n, dtype=torch.float32, device="cuda")
+    eck.costmodel_score(model, feat, n, p_mlp)
+    torch.cuda.synchronize()
+    p_mlp = p_mlp.cpu().numpy()
+
+    def rank_corr(a, b):
+        return np.corrcoef(np.argsort(np.argsort(a)), np.argsort(np.argsort(b)))[0, 1]
+    for name, p in (("trees", p_trees), ("mlp", p_mlp)):
+        eq1 = float(np.mean((p[held] - y[held]) ** 2 / y[held]))
+        print("%s: held-out r = %.4f, rank correlation = %.4f, Eq. (1) loss = %.3e"
+              % (name, np.corrcoef(p[held], y[held])[0, 1], rank_corr(p[held], y[held]), eq1))
+    assert rank_corr(p_trees[held], y[held]) > 0.9
+    assert rank_corr(p_mlp[held], y[held]) > 0.9
