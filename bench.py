@@ -99,7 +99,8 @@ def main():
         pop, rounds = 1 << 20, args.steps
         s = EnergySearch(synth.CONFIGS["c3"]["problem"], eck.SPACE_SPLIT,
                          lambda f, b: synth.simulated_kernel_metrics(f, 77, b), population=pop, M=128, n_parents=128,
-                         depth=6, init_rounds=40, update_rounds=8, mu=1000.0, max_rounds=rounds + args.warmup)
+                         depth=6, init_rounds=40, update_rounds=8, mu=1000.0, max_rounds=rounds + args.warmup,
+                         meter_seconds=1.0)
         s.initialise()
         for _ in range(args.warmup):
             s.step()
@@ -111,7 +112,11 @@ def main():
         dt = time.perf_counter() - t0
         print(json.dumps({"only": "search", "ms_per_round": 1e3 * dt / rounds, "candidates_per_s": pop * rounds / dt,
                           "population": pop, "rounds": rounds, "measured": sum(h["measured"] for h in s.history),
-                          "k": [round(h["k"], 2) for h in s.history]}))
+                          "k": [round(h["k"], 2) for h in s.history],
+                          # at one second per energy measurement: the meter's share with the k controller, and
+                          # what measuring all M kernels of every round would have cost
+                          "meter_s_at_1s_per_kernel": s.account()["meter_seconds"],
+                          "meter_s_if_all_measured": s.account()["full_measurement_seconds"]}))
         return
 
     cfg = synth.CONFIGS["c5"]

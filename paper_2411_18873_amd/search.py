@@ -20,13 +20,16 @@ from . import eck
 class EnergySearch:
     def __init__(self, problem, kind, measure, population=1 << 14, M=64, n_parents=64, depth=6, init_rounds=40,
                  update_rounds=8, mu=20.0, k_min=0.2, eta=0.3, lam=1.0, p_mut_q32=429496729, seed=1,
-                 max_rounds=64, crossover=False, dedup=False):
+                 max_rounds=64, crossover=False, dedup=False, meter_seconds=0.0):
         self.space = eck.Space(problem, kind)
         self.measure, self.N, self.M, self.P = measure, int(population), int(M), int(n_parents)
         self.init_rounds, self.update_rounds = int(init_rounds), int(update_rounds)
         self.mu, self.k_min, self.eta, self.lam = float(mu), float(k_min), float(eta), float(lam)
         self.p_mut, self.seed = int(p_mut_q32), int(seed)
         self.crossover, self.dedup = bool(crossover), bool(dedup)
+        # what one measurement costs on the real meter (Sec. 6.4: energy measurement is what dominates the search
+        # time); only book-kept here, so that a run can say how long its measurements would have taken
+        self.meter_seconds = float(meter_seconds)
         G, N, dev = self.space.n_genes, self.N, "cuda"
         cap_trees = init_rounds + update_rounds * (max_rounds + 1)
         self.energy_model = eck.Trees(64, depth, cap_trees, 0.5)
@@ -143,3 +146,9 @@ class EnergySearch:
         self.history.append(dict(round=r, measured=m, k=self.k, snr=snr, best=float(self.h_energy.min()),
                                  picked=picked))
         return self.history[-1]
+
+    def account(self):
+        """Totals of the run so far: kernels measured, and the time the meter would have needed for them."""
+        measured = sum(h["measured"] for h in self.history)
+        return dict(rounds=self.round, measured=measured, meter_seconds=measured * self.meter_seconds,
+                    full_measurement_seconds=(self.M * (self.round + 1)) * self.meter_seconds)
