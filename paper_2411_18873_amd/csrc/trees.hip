@@ -63,6 +63,9 @@ __global__ __launch_bounds__(SCORE_BLOCK) void tree_score_kernel(const uint8_t *
     uint2 *node_lds = reinterpret_cast<uint2 *>(lds + (size_t)n_feat * SCORE_BLOCK * sizeof(Elem)); // [chunk][nodes]
     float *leaf_lds = reinterpret_cast<float *>(node_lds + (size_t)chunk_trees * nodes);      // [chunk][leaves]
     const int tid = threadIdx.x;
+    // where the dynamic LDS starts within the workgroup's allocation (the hand-written loads below take raw LDS
+    // addresses; a shared-memory pointer's low 32 bits are that address)
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
     const Elem *feat_e = reinterpret_cast<const Elem *>(feat);
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(SCORE_BLOCK) void tree_score_kernel(const uint8_t *
                         // eight registers in between.
                         uint32_t at[WALKS];
 #pragma unroll
-                        for (int w = 0; w < WALKS; ++w) at[w] = nd[w].y + tid * 2;
+                        for (int w = 0; w < WALKS; ++w) at[w] = lds_base + nd[w].y + tid * 2;
                         asm volatile("ds_read_u16_d16_hi %0, %8\n\t"
                                      "ds_read_u16_d16_hi %1, %9\n\t"
                                      "ds_read_u16_d16_hi %2, %10\n\t"
