@@ -64,8 +64,8 @@ __global__ __launch_bounds__(SCORE_BLOCK) void tree_score_kernel(const uint8_t *
     float *leaf_lds = reinterpret_cast<float *>(node_lds + (size_t)chunk_trees * nodes);      // [chunk][leaves]
     const int tid = threadIdx.x;
     // where the dynamic LDS starts within the workgroup's allocation (the hand-written loads below take raw LDS
-    // addresses; a shared-memory pointer's low 32 bits are that address)
-    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    // addresses)
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
     const Elem *feat_e = reinterpret_cast<const Elem *>(feat);
 
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
