@@ -160,19 +160,30 @@ def main():
 
     seeds = [cfg["seed_base"] + s for s in range(S)]
 
+    call_events = {name: [] for name in ("enumerate", "features", "topk", "update")}
+
+    def timed_call(events, timed, fn):
+        """fn() between two events on the stream the library launches on (torch's current stream)"""
+        if not timed:
+            return fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        events.append((a, b))
+
     def step(i, timed):
-        eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, per, genes, seeds, round=i)
-        eck.features_compute_batch(spaces, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal)
+        timed_call(call_events["enumerate"], timed,
+                   lambda: eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, per, genes, seeds, round=i))
+        timed_call(call_events["features"], timed,
+                   lambda: eck.features_compute_batch(spaces, genes, per, F, eck.BF16, feat_out=feat, legal_out=legal))
         for model, out in ((m_energy, energy), (m_latency, latency)):
-            if timed:
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-            eck.costmodel_score(model, feat, N, out)
-            if timed:
-                b.record()
-                score_events.append((a, b))
-        eck.topk_select(energy, latency, legal, S, K, idx, e_out, count, ws_topk, alpha=cfg["alpha"])
-        eck.costmodel_update(m_energy, upd_feat, upd_energy, upd_steps, upd_mb, snr, loss, ws_upd, lr=1e-3)
+            timed_call(score_events, timed, lambda: eck.costmodel_score(model, feat, N, out))
+        timed_call(call_events["topk"], timed,
+                   lambda: eck.topk_select(energy, latency, legal, S, K, idx, e_out, count, ws_topk, alpha=cfg["alpha"]))
+        timed_call(call_events["update"], timed,
+                   lambda: eck.costmodel_update(m_energy, upd_feat, upd_energy, upd_steps, upd_mb, snr, loss, ws_upd,
+                                                lr=1e-3))
 
     if args.only:
         feat_copy = torch.empty_like(feat) if args.only == "copy" else None
@@ -255,6 +266,16 @@ def main():
                      "traffic": 2.155e9 + 0.0692e9 if (F, N) == (64, 1 << 24) else None,
                      "traffic_unit": "bytes/launch"},
     }
+    # the other calls of the step, each between HIP events: milliseconds per call, and for the two calls that only
+    # move data the algorithmic bytes per second against the 8 TB/s of HBM (features: genes in, 64 bf16 features and
+    # a flag out; top-k: energy, latency and flag of every candidate once)
+    calls_ms = {name: sum(a.elapsed_time(b) for a, b in ev) / len(ev) for name, ev in call_events.items()}
+    calls_ms["score"] = score_ms
+    hbm_bytes = {"features": N * (2 * G + 2 * F + 1), "topk": N * 9}
+    result["calls_ms"] = calls_ms
+    result["hbm"] = {name: {"algorithmic_bytes": b, "achieved": b / (calls_ms[name] * 1e-3) / 1e9, "peak": 8000.0,
+                            "unit": "GB/s", "frac": b / (calls_ms[name] * 1e-3) / 8e12}
+                     for name, b in hbm_bytes.items()}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample_log2)
     print(json.dumps(result))
