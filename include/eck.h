@@ -204,8 +204,9 @@ int32_t eck_candidates_dedup(const uint16_t *genes, uint64_t ld, uint64_t n, int
  *   feat_out:  device, [n_feat][ld] of out_dtype (ECK_F32 or ECK_BF16); may be NULL
  *   raw_out:   device, uint64 [n_feat][ld] or NULL
  *   legal_out: device, uint8 [n] or NULL; 1 when the schedule can be launched
- *              (32 <= threads <= 1024, staged bytes fit the LDS, vector width
- *              <= 16 bytes and divides the contiguous per-thread extent)
+ *              (32 <= threads <= 1024, staged bytes -- in a SPLIT_XRED space the
+ *              partial sums -- fit the LDS, vector width <= 16 bytes and
+ *              divides the contiguous per-thread extent)
  * Errors: EINVAL, ESHAPE (ld < n), EUNSUPPORTED (n_feat not 32/64), EALIGN
  * (ld not a multiple of 2). */
 int32_t features_compute(const eck_space *space, const uint16_t *genes, uint64_t ld, uint64_t n,
