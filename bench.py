@@ -67,8 +67,8 @@ def cpu_baseline(cfg, sample_log2=18):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-log2", type=int, default=18)
     ap.add_argument("--only", choices=["enumerate", "features", "score", "topk", "update", "copy", "treescore", "treeupdate", "search"],
