@@ -228,8 +228,10 @@ int32_t features_compute_batch(const eck_space *const *spaces, uint32_t n_spaces
  * form the workloads prescribe (the paper's own model is a tree ensemble).
  * dtype ECK_F32: fp32 weights and arithmetic.  ECK_BF16: bf16 weights and
  * bf16 first-hidden activations on the matrix cores, fp32 accumulation.
- * Supported: n_layers == 3, widths[3] == 1, widths[0] in {32, 64}; BF16 needs
- * hidden widths that are multiples of 32 and at most 512; F32 at most 1024.
+ * Supported: n_layers == 3, widths[3] == 1, widths[0] in {32, 64}, hidden widths
+ * at most 512; a BF16 model must be one of the shapes the matrix-core kernels
+ * are built for: 64-512-512-1, 64-256-256-1, 64-128-128-1, 32-64-64-1
+ * (ECK_EUNSUPPORTED otherwise, here rather than at the first score call).
  * Allocates device memory (parameters, Adam moments, packed weights). */
 int32_t eck_model_create(int32_t n_layers, const int32_t *widths, int32_t dtype, eck_model **out);
 void eck_model_destroy(eck_model *model);
@@ -252,8 +254,11 @@ int32_t eck_model_get_state(const eck_model *model, float *blob, uint64_t n_floa
  *   feat: device [widths[0]][ld] of feat_dtype; score_out: device float [n].
  * A BF16 model takes BF16 or F32 features (F32 is rounded to bf16 on load); an
  * F32 model takes F32 features.  ws/ws_bytes are reserved (pass NULL, 0).
- * Errors: EINVAL, ESHAPE (ld < n), EUNSUPPORTED (dtype combination), EALIGN
- * (ld odd for BF16 features). */
+ * A BF16 model reads two (or four) neighbouring candidates per load: ld must
+ * be even and feat aligned to two elements (4 bytes for BF16, 8 for F32
+ * features), whatever n is; the four-candidate loads are used only when ld is
+ * a multiple of 4 and feat 8-byte aligned.  No load crosses the end of a row.
+ * Errors: EINVAL, ESHAPE (ld < n), EUNSUPPORTED (dtype combination), EALIGN. */
 int32_t costmodel_score(const eck_model *model, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n,
                         float *score_out, void *ws, uint64_t ws_bytes, void *stream);
 
@@ -300,7 +305,7 @@ uint64_t costmodel_update_workspace_bytes(const eck_model *model, uint64_t n_pai
  * A non-positive or non-finite measured energy is a data error found on the
  * device: snr = loss = NaN and the model is left unchanged.
  * Errors: EINVAL, ESHAPE (n_pairs % minibatch, ld < n_pairs), EUNSUPPORTED,
- * EWORKSPACE. */
+ * EWORKSPACE, EALIGN (ws not 256-byte aligned; feat / ld as costmodel_score). */
 int32_t costmodel_update(eck_model *model, const void *feat, int32_t feat_dtype, uint64_t ld,
                          const float *energy_measured, uint64_t n_pairs, int32_t n_steps, int32_t minibatch,
                          float lr, float beta1, float beta2, float eps, float *snr_out, float *loss_out,
@@ -316,6 +321,11 @@ int32_t eck_version(void);
  * nothing (round(k*M) == 0) has no SNR and leaves k unchanged.  Host only;
  * *k_out receives the next k.  EINVAL: nulls, M < 0, k outside [0, 1], NaN. */
 int32_t eck_k_step(double k, double snr, double mu, int64_t M, double *k_out);
+
+/* How many of the M fastest kernels a round measures (Alg. 1: "k*M"): round(k*M),
+ * halves up.  0 means the round measures nothing.  Host only.  EINVAL: null,
+ * M < 0, k outside [0, 1] or NaN. */
+int32_t eck_k_count(double k, int64_t M, int64_t *count_out);
 
 /* ------------------------------------------------- boosted-tree cost model */
 

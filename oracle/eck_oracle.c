@@ -1152,7 +1152,9 @@ static int64_t tree_quantise(double v)
  *
  * snr_out: sum y^2 / sum (p - y)^2 of the ensemble as it is on entry;
  * loss_out: mean of Eq. (1) over the pairs after the last round (fp64).
- * Any E <= 0 or non-finite: snr = loss = NaN, nothing appended. */
+ * Any E <= 0 or non-finite: snr = loss = NaN and the n_rounds appended trees
+ * are empty (no node splits, every leaf 0), so the ensemble grows by n_rounds
+ * as after any other call while its predictions stay what they were. */
 int32_t orc_trees_boost(int32_t n_feat, int32_t depth, int32_t n_trees_in, int32_t n_rounds, uint8_t *node_feat,
                         float *node_thr, float *leaf, double base, const float *feat, uint64_t ld,
                         const float *e_meas, uint64_t n_pairs, double eta, double lambda, double *snr_out,
@@ -1168,7 +1170,19 @@ int32_t orc_trees_boost(int32_t n_feat, int32_t depth, int32_t n_trees_in, int32
         if (!(e_meas[i] > 0.0f) || isinf(e_meas[i])) bad = 1;
         if (e_meas[i] > emax) emax = e_meas[i];
     }
-    if (bad) { *snr_out = NAN; *loss_out = NAN; return ORC_OK; }
+    if (bad) {
+        for (int32_t r = 0; r < n_rounds; ++r) {
+            const uint64_t t = (uint64_t)(n_trees_in + r);
+            for (uint32_t j = 0; j < nodes; ++j) {
+                node_feat[t * nodes + j] = 0;
+                node_thr[t * nodes + j] = INFINITY;
+            }
+            for (uint32_t j = 0; j < leaves; ++j) leaf[t * leaves + j] = 0.0f;
+        }
+        *snr_out = NAN;
+        *loss_out = NAN;
+        return ORC_OK;
+    }
 
     float *y = (float *)malloc(n_pairs * sizeof(float));
     float *p = (float *)malloc(n_pairs * sizeof(float));

@@ -135,6 +135,13 @@ int32_t eck::model_repack(eck_model *m, hipStream_t stream)
     return ECK_OK;
 }
 
+// the shapes the matrix-core forward pass is instantiated for
+static bool bf16_shape_supported(int F, int H1, int H2)
+{
+    return (F == 64 && H1 == 512 && H2 == 512) || (F == 64 && H1 == 256 && H2 == 256) ||
+           (F == 64 && H1 == 128 && H2 == 128) || (F == 32 && H1 == 64 && H2 == 64);
+}
+
 static int32_t check_widths(int32_t n_layers, const int32_t *widths, int32_t dtype)
 {
     if (!widths || n_layers < 1) return ECK_EINVAL;
@@ -145,7 +152,7 @@ static int32_t check_widths(int32_t n_layers, const int32_t *widths, int32_t dty
     if (widths[3] != 1) return ECK_ESHAPE;
     if (widths[0] != 32 && widths[0] != 64) return ECK_EUNSUPPORTED;
     if (widths[1] > 512 || widths[2] > 512) return ECK_EUNSUPPORTED;
-    if (dtype == ECK_BF16 && ((widths[1] % 32) || (widths[2] % 32))) return ECK_EUNSUPPORTED;
+    if (dtype == ECK_BF16 && !bf16_shape_supported(widths[0], widths[1], widths[2])) return ECK_EUNSUPPORTED;
     return ECK_OK;
 }
 
@@ -765,14 +772,20 @@ extern "C" int32_t costmodel_score(const eck_model *m, const void *feat, int32_t
         ECK_HIP_TRY(hipGetLastError());
         return ECK_OK;
     }
-    if (feat_dtype == ECK_BF16 && (ld & 1)) return ECK_EALIGN;
+    // A lane fetches the NC consecutive candidates it owns with one load per feature row.  Groups start at
+    // multiples of NC, so with ld a multiple of NC a group that starts below n ends inside its row; otherwise
+    // the last group of a row would run into the next row and, in the last row, past the matrix.  The pointer
+    // must be aligned to the load as well.
+    const uint64_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
+    if ((ld & 1) || ((uintptr_t)feat & (2 * elem - 1))) return ECK_EALIGN;
+    // four candidate tiles per wavefront (half the weight traffic per candidate) where 256 or fewer hidden units
+    // leave the registers for it, the features arrive as bf16 and groups of four stay inside a row
+    const bool four = feat_dtype == ECK_BF16 && ld % 4 == 0 && ((uintptr_t)feat & 7) == 0;
     if (F == 64 && H1 == 512 && H2 == 512) return launch_bf16<64, 512, 512, 2>(m, feat, feat_dtype, ld, n, score_out, st);
-    // 256 hidden units leave room for four candidate tiles per wavefront (half the weight traffic per candidate)
-    // when the features arrive as bf16; fp32 features need the registers for themselves
-    if (F == 64 && H1 == 256 && H2 == 256 && feat_dtype == ECK_BF16)
+    if (F == 64 && H1 == 256 && H2 == 256 && four)
         return launch_bf16<64, 256, 256, 4>(m, feat, feat_dtype, ld, n, score_out, st);
     if (F == 64 && H1 == 256 && H2 == 256) return launch_bf16<64, 256, 256, 2>(m, feat, feat_dtype, ld, n, score_out, st);
-    if (F == 64 && H1 == 128 && H2 == 128 && feat_dtype == ECK_BF16)
+    if (F == 64 && H1 == 128 && H2 == 128 && four)
         return launch_bf16<64, 128, 128, 4>(m, feat, feat_dtype, ld, n, score_out, st);
     if (F == 64 && H1 == 128 && H2 == 128) return launch_bf16<64, 128, 128, 2>(m, feat, feat_dtype, ld, n, score_out, st);
     if (F == 32 && H1 == 64 && H2 == 64) return launch_bf16<32, 64, 64, 2>(m, feat, feat_dtype, ld, n, score_out, st);

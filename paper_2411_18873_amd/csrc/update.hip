@@ -533,6 +533,13 @@ extern "C" int32_t costmodel_update(eck_model *m, const void *feat, int32_t feat
     return model_repack(m, st);
 }
 
+extern "C" int32_t eck_k_count(double k, int64_t M, int64_t *count_out)
+{
+    if (!count_out || M < 0 || !(k >= 0.0 && k <= 1.0)) return ECK_EINVAL;
+    *count_out = (int64_t)__builtin_floor(k * (double)M + 0.5);
+    return ECK_OK;
+}
+
 extern "C" int32_t eck_k_step(double k, double snr, double mu, int64_t M, double *k_out)
 {
     if (!k_out || M < 0 || !(k >= 0.0 && k <= 1.0) || mu != mu) return ECK_EINVAL;

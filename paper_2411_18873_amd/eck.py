@@ -31,7 +31,7 @@ EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_in
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
            "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update",
            "eck_trees_create", "eck_trees_destroy", "eck_trees_count", "eck_trees_set", "eck_trees_get",
-           "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step",
+           "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step", "eck_k_count",
            "eck_candidates_dedup", "eck_candidates_dedup_workspace_bytes"]
 
 
@@ -87,6 +87,7 @@ def lib():
         L.eck_candidates_dedup_workspace_bytes.restype = u64
         L.eck_candidates_dedup.argtypes = [vp, u64, u64, i32, vp, i32, vp, u64, vp]
         L.eck_k_step.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int64, C.POINTER(C.c_double)]
+        L.eck_k_count.argtypes = [C.c_double, C.c_int64, C.POINTER(C.c_int64)]
         L.eck_trees_create.argtypes = [i32, i32, i32, f32, C.POINTER(vp)]
         L.eck_trees_destroy.argtypes = [vp]
         L.eck_trees_destroy.restype = None
@@ -414,6 +415,13 @@ def k_step(k, snr, mu, M):
     """next k of the measurement-budget controller (host only)"""
     out = C.c_double()
     _check("eck_k_step", lib().eck_k_step(k, snr, mu, M, C.byref(out)))
+    return out.value
+
+
+def k_count(k, M):
+    """kernels to measure this round: round(k * M) (host only)"""
+    out = C.c_int64()
+    _check("eck_k_count", lib().eck_k_count(k, M, C.byref(out)))
     return out.value
 
 

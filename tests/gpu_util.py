@@ -90,3 +90,28 @@ def within(got, want, magnitude, rtol):
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     return float(np.max(np.abs(got - want) / (rtol * np.asarray(magnitude, dtype=np.float64))))
+
+
+def check_bf16_scores(widths, theta, feat_bits_u16, got, label=""):
+    """The two gates of a bf16 model's scores against the fp64 oracle on the same bf16 feature bits:
+    |g - o| <= 1e-2 * M against the exact forward pass and |g - o_b| <= 1e-4 * M against the oracle mode that
+    rounds the first hidden layer to bf16 where the kernel does (M = the magnitude of the output sum).  Prints
+    both margins and the worst error relative to max(|o|, rms(o))."""
+    import oracle
+    x = oracle.bf16_bits_to_f32(feat_bits_u16)
+    want = oracle.score(widths, theta, x)
+    emu = oracle.score(widths, theta, x, emulate_bf16=True)
+    mag = oracle.score_magnitude(widths, theta, x)
+    got = np.asarray(got, dtype=np.float64)
+    assert np.isfinite(got).all()
+    worst = within(got, want, mag, 1e-2)
+    worst_emu = within(got, emu, mag, 1e-4)
+    rms = float(np.sqrt(np.mean(want * want)))
+    rel = float(np.max(np.abs(got - want) / np.maximum(np.abs(want), rms)))
+    rel_emu = float(np.max(np.abs(got - emu) / np.maximum(np.abs(emu), rms)))
+    print("bf16 scores %s n=%d: worst/(1e-2 M) = %.3f, vs bf16-activation oracle worst/(1e-4 M) = %.4f; "
+          "worst |g-o|/max(|o|, rms) = %.2e (vs bf16-activation oracle %.2e)"
+          % (label, got.size, worst, worst_emu, rel, rel_emu), flush=True)
+    assert worst <= 1.0, worst
+    assert worst_emu <= 1.0, worst_emu
+    return worst, worst_emu, rel

@@ -141,6 +141,10 @@ def test_model_and_score_validation():
     assert L.eck_model_create(3, W(48, 256, 256, 1), eck.F32, C.byref(h)) == eck.EUNSUPPORTED
     assert L.eck_model_create(3, W(64, 250, 256, 1), eck.BF16, C.byref(h)) == eck.EUNSUPPORTED
     assert L.eck_model_create(3, W(64, 1024, 256, 1), eck.BF16, C.byref(h)) == eck.EUNSUPPORTED
+    # bf16 models exist only in the shapes the matrix-core kernels are built for: refused before any allocation
+    assert L.eck_model_create(3, W(64, 384, 384, 1), eck.BF16, C.byref(h)) == eck.EUNSUPPORTED
+    assert L.eck_model_create(3, W(64, 512, 256, 1), eck.BF16, C.byref(h)) == eck.EUNSUPPORTED
+    assert L.eck_model_create(3, W(32, 512, 512, 1), eck.BF16, C.byref(h)) == eck.EUNSUPPORTED
     assert L.eck_model_create(3, W(64, 0, 256, 1), eck.BF16, C.byref(h)) == eck.EINVAL
     p = C.c_uint64()
     assert L.eck_model_param_count(3, W(64, 256, 256, 1), C.byref(p)) == 0 and p.value == 82689
@@ -225,6 +229,15 @@ def test_k_controller_matches_the_oracle_and_validates():
     assert L.eck_k_step(1.5, 1.0, 10.0, 64, C.byref(out)) == eck.EINVAL
     assert L.eck_k_step(0.5, 1.0, 10.0, -1, C.byref(out)) == eck.EINVAL
     assert L.eck_k_step(0.5, 1.0, float("nan"), 64, C.byref(out)) == eck.EINVAL
+    # how many kernels a round measures: round(k M), halves up; Alg. 1's k sequence on M = 64
+    assert [eck.k_count(k, 64) for k in (1.0, 0.8, 0.6000000000000001, 0.4000000000000001, 0.2, 0.0)] == \
+        [64, 51, 38, 26, 13, 0]
+    assert eck.k_count(0.5, 5) == 3 and eck.k_count(0.5, 64) == 32 and eck.k_count(1e-9, 64) == 0
+    cnt = C.c_int64()
+    assert L.eck_k_count(0.5, 64, None) == eck.EINVAL
+    assert L.eck_k_count(1.5, 64, C.byref(cnt)) == eck.EINVAL
+    assert L.eck_k_count(float("nan"), 64, C.byref(cnt)) == eck.EINVAL
+    assert L.eck_k_count(0.5, -1, C.byref(cnt)) == eck.EINVAL
 
 
 def test_dedup_validation():

@@ -1,8 +1,9 @@
 """GPU parity, end to end, on the five workload configurations -- at their full sizes and in the
 launch configuration bench.py times.  Integer stages are compared bit for bit (all candidates where
 the oracle finishes in seconds, a regular sample otherwise); scores on a regular sample plus every
-selected candidate; selection against the oracle run on the GPU's own scores ("given identical
-scores")."""
+selected candidate (config 5: 2^18 strided candidates, every selected one and every one whose energy lies
+within 1 % of its segment's k-th selected energy), each against both oracle modes; selection against the
+oracle run on the GPU's own scores ("given identical scores")."""
 import numpy as np
 import pytest
 import torch
@@ -76,11 +77,8 @@ def _bf16_pipeline(G, mine, n, seed, rnd, mode, widths, thetas, parents=None, p_
     return genes, feat, legal, outs
 
 
-def _check_scores_sample(G, widths, theta, b16_o, got, cols):
-    x = oracle.bf16_bits_to_f32(b16_o[:, cols])
-    want = oracle.score(widths, theta, x)
-    g = got.cpu().numpy()[cols]
-    assert G.within(g, want, oracle.score_magnitude(widths, theta, x), 1e-2) <= 1.0
+def _check_scores_sample(G, widths, theta, b16_o, got, cols, label=""):
+    G.check_bf16_scores(widths, theta, np.ascontiguousarray(b16_o[:, cols]), got.cpu().numpy()[cols], label)
 
 
 def test_config2_sampled_conv_full_size(G):
@@ -97,8 +95,8 @@ def test_config2_sampled_conv_full_size(G):
     idx, cnt = _select_and_check(G, energy, latency, legal, 1, k, cfg["alpha"])
     assert 1 <= cnt[0] <= k  # an untrained latency model leaves few candidates within 1.1x of its minimum
     cols = np.unique(np.concatenate([np.arange(0, n, 97), idx[0][:cnt[0]].astype(np.int64)]))
-    _check_scores_sample(G, widths, thetas[0], b16_o, energy, cols)
-    _check_scores_sample(G, widths, thetas[1], b16_o, latency, cols)
+    _check_scores_sample(G, widths, thetas[0], b16_o, energy, cols, "c2 energy")
+    _check_scores_sample(G, widths, thetas[1], b16_o, latency, cols, "c2 latency")
     # "top-k" without the latency gate, too
     i2, e2, c2 = G.topk_dev(energy, None, legal, 1, k)
     io, eo, co = oracle.topk(energy.cpu().numpy(), None, legal_o, 1, k)
@@ -124,7 +122,7 @@ def test_config3_evolutionary_rounds_full_size(G):
         if rnd in (0, cfg["rounds"] - 1):  # the feature check of a whole generation costs a few seconds
             _, _, b16_o, legal_o = oracle.features(ref, genes_o, 64)
             assert np.array_equal(_bits(feat), b16_o) and np.array_equal(legal.cpu().numpy(), legal_o)
-            _check_scores_sample(G, widths, thetas[0], b16_o, energy, np.arange(0, n, 257))
+            _check_scores_sample(G, widths, thetas[0], b16_o, energy, np.arange(0, n, 257), "c3 round %d" % rnd)
         idx_dev = torch.zeros((1, k), dtype=torch.int32, device="cuda")
         if rnd == 0:
             _select_and_check(G, energy, latency, legal, 1, k, 1.1)
@@ -162,13 +160,12 @@ def test_config4_rescoring_after_the_update(G):
     assert np.array_equal(_bits(genes)[:, cols], genes_o[:, cols])
     _, _, b16_o, _ = oracle.features(ref, np.ascontiguousarray(genes_o[:, cols]), 64)
     assert np.array_equal(_bits(feat)[:, cols], b16_o)
-    x = oracle.bf16_bits_to_f32(b16_o)
-    want = oracle.score(widths, theta, x)
-    got = out.cpu().numpy()[cols]
-    assert G.within(got, want, oracle.score_magnitude(widths, theta, x), 1e-2) <= 1.0
+    G.check_bf16_scores(widths, theta, b16_o, out.cpu().numpy()[cols], "c4 rescoring")
 
 
-def test_config5_sweep_full_size_as_benchmarked(G):
+@pytest.fixture(scope="module")
+def c5(G):
+    """The benchmark's step on the benchmark's buffers: two batched launches, two score launches, one selection."""
     cfg = synth.CONFIGS["c5"]
     shapes, per, widths, K = cfg["shapes"], cfg["n_per_shape"], cfg["widths"], cfg["k"]
     S, N = len(shapes), len(shapes) * cfg["n_per_shape"]
@@ -176,7 +173,6 @@ def test_config5_sweep_full_size_as_benchmarked(G):
     genes = torch.zeros((5, N), dtype=torch.int16, device="cuda")
     feat = torch.zeros((64, N), dtype=torch.bfloat16, device="cuda")
     legal = torch.zeros(N, dtype=torch.uint8, device="cuda")
-    # the two batched launches bench.py times
     eck.candidate_enumerate_batch(spaces, eck.MODE_SAMPLE, per, genes, [cfg["seed_base"] + s for s in range(S)])
     eck.features_compute_batch(spaces, genes, per, 64, eck.BF16, feat_out=feat, legal_out=legal)
     thetas = [synth.mlp_theta(widths, s, bf16=True) for s in cfg["weight_seeds"]]
@@ -186,10 +182,38 @@ def test_config5_sweep_full_size_as_benchmarked(G):
     eck.costmodel_score(G.make_model(widths, eck.BF16, thetas[1]), feat, N, latency)
     idx, cnt = _select_and_check(G, energy, latency, legal, S, K, cfg["alpha"])
     assert cnt.min() > 0
+    # the columns whose scores are checked: 2^18 strided candidates, every selected candidate, and every feasible
+    # candidate whose energy lies within 1 % of its segment's k-th selected energy (the ones a scoring error
+    # could move across the selection boundary)
+    e_h, l_h, legal_h = energy.cpu().numpy(), latency.cpu().numpy(), legal.cpu().numpy()
+    picked, near = [], []
+    for s in range(S):
+        seg = slice(s * per, (s + 1) * per)
+        sel = idx[s][:cnt[s]].astype(np.int64)
+        picked.append(s * per + sel)
+        kth = e_h[seg][sel[-1]]
+        l_ok = legal_h[seg] != 0
+        l_min = l_h[seg][l_ok].min()
+        tau = np.float32(l_min) + np.float32(np.float32(cfg["alpha"]) - np.float32(1.0)) * np.abs(np.float32(l_min))
+        feasible = l_ok & (l_h[seg] <= tau)
+        close = feasible & (np.abs(e_h[seg] - kth) <= 0.01 * abs(kth))
+        near.append(s * per + np.flatnonzero(close))
+    picked, near = np.concatenate(picked), np.concatenate(near)
+    strided = np.arange(0, N, N >> 18)
+    cols = np.unique(np.concatenate([strided, picked, near]))
+    print("c5 score columns: %d strided, %d selected, %d within 1 %% of a k-th energy" % (len(strided), len(picked),
+                                                                                         len(near)), flush=True)
+    return dict(cfg=cfg, genes=genes, feat=feat, legal=legal, energy=e_h, latency=l_h, thetas=thetas, idx=idx, cnt=cnt,
+                cols=cols, picked=picked)
+
+
+def test_config5_sweep_full_size_as_benchmarked(G, c5):
+    cfg = c5["cfg"]
+    shapes, per = cfg["shapes"], cfg["n_per_shape"]
+    idx, cnt = c5["idx"], c5["cnt"]
     # integer stages: every 61st candidate of every shape, plus everything selected
     stride = np.arange(0, per, 61)
-    genes_h, feat_h, legal_h = _bits(genes), None, legal.cpu().numpy()
-    score_cols = []
+    genes_h, legal_h = _bits(c5["genes"]), c5["legal"].cpu().numpy()
     for s, shape in enumerate(shapes):
         ref = oracle.Space(synth.gemm(*shape), oracle.SPACE_SPLIT)
         local = np.unique(np.concatenate([stride, idx[s][:cnt[s]].astype(np.int64)]))
@@ -201,18 +225,36 @@ def test_config5_sweep_full_size_as_benchmarked(G):
         assert np.array_equal(genes_h[:, cols[:64]], want_genes)
         g_sub = np.ascontiguousarray(genes_h[:, cols])
         _, _, b16_o, legal_o = oracle.features(ref, g_sub, 64)
-        got = _bits(feat.index_select(1, torch.from_numpy(cols).cuda()))
+        got = _bits(c5["feat"].index_select(1, torch.from_numpy(cols).cuda()))
         assert np.array_equal(got, b16_o) and np.array_equal(legal_h[cols], legal_o)
-        score_cols.append((cols[::16], b16_o[:, ::16]))
     # whole-shape gene check for two shapes
     for s in (0, 37):
         ref = oracle.Space(synth.gemm(*shapes[s]), oracle.SPACE_SPLIT)
         want = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, per, seed=cfg["seed_base"] + s)
         assert np.array_equal(genes_h[:, s * per:(s + 1) * per], want)
-    cols = np.concatenate([c for c, _ in score_cols])
-    b16 = np.concatenate([b for _, b in score_cols], axis=1)
-    for theta, got in ((thetas[0], energy), (thetas[1], latency)):
-        x = oracle.bf16_bits_to_f32(b16)
-        want = oracle.score(widths, theta, x)
-        g = got.cpu().numpy()[cols]
-        assert G.within(g, want, oracle.score_magnitude(widths, theta, x), 1e-2) <= 1.0
+
+
+@pytest.mark.parametrize("which", ["energy", "latency"])
+def test_config5_scores_of_the_strided_sample_and_around_every_selection_boundary(G, c5, which):
+    """Scores of the 2^24-candidate launch against the oracle, which recomputes genes -> features -> score for
+    each checked column itself: 2^18 strided columns, every selected candidate, every candidate within 1 % of a
+    segment's k-th energy; both gates (1e-2 M exact, 1e-4 M with bf16 activations)."""
+    cfg = c5["cfg"]
+    shapes, per, widths = cfg["shapes"], cfg["n_per_shape"], cfg["widths"]
+    cols = c5["cols"]
+    b16 = np.zeros((64, len(cols)), dtype=np.uint16)
+    for s, shape in enumerate(shapes):
+        lo, hi = np.searchsorted(cols, [s * per, (s + 1) * per])
+        if hi == lo:
+            continue
+        ref = oracle.Space(synth.gemm(*shape), oracle.SPACE_SPLIT)
+        # the oracle's own genes for the whole shape, then its features of the checked columns
+        genes_o = oracle.enumerate_candidates(ref, oracle.MODE_SAMPLE, per, seed=cfg["seed_base"] + s)
+        sub = np.zeros((genes_o.shape[0], hi - lo + ((hi - lo) & 1)), dtype=np.uint16)
+        sub[:, :hi - lo] = genes_o[:, cols[lo:hi] - s * per]
+        _, _, b, _ = oracle.features(ref, sub, 64)
+        b16[:, lo:hi] = b[:, :hi - lo]
+    got_feat = _bits(c5["feat"].index_select(1, torch.from_numpy(cols).cuda()))
+    assert np.array_equal(got_feat, b16)
+    theta = c5["thetas"][0 if which == "energy" else 1]
+    G.check_bf16_scores(widths, theta, b16, c5[which][cols], "c5 " + which)

@@ -101,6 +101,44 @@ def test_bf16_model_determinism_and_tail_tiles(G):
     assert np.all(out.cpu().numpy()[257:] == 123.0)
 
 
+def test_bf16_model_leading_dimensions_that_do_not_fit_the_wide_loads(G):
+    """A lane loads the 2 or 4 neighbouring candidates it owns at once, so ld must be a multiple of that for the
+    last group of a row to end inside the row.  ld = n = 1002 (even, not a multiple of 4) must take the
+    two-candidate kernel and give the scores of the padded matrix bit for bit; an odd ld, a misaligned pointer
+    and a model shape without a kernel are refused on the host."""
+    import ctypes as C
+    widths = [64, 256, 256, 1]
+    n = 1002
+    f32, b16 = _features("c2", 1004, 64)
+    theta = synth.mlp_theta(widths, 3, bf16=True, bias_scale=0.5)
+    model = G.make_model(widths, eck.BF16, theta)
+    padded = G.score_gpu(model, G.bf16_dev(b16), n)                       # ld = 1004: four candidates per load
+    tight = G.score_gpu(model, G.bf16_dev(b16[:, :n]), n)                 # ld = n = 1002: two per load
+    tight32 = G.score_gpu(model, G.to_dev(f32[:, :n]), n)                 # fp32 features, 8-byte loads
+    assert np.array_equal(tight, padded) and np.array_equal(tight32, padded)
+    L = eck.lib()
+    out = torch.zeros(1024, dtype=torch.float32, device="cuda")
+    odd = G.bf16_dev(b16[:, :1001])
+    odd32 = G.to_dev(f32[:, :1001])
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    po = C.c_void_p(out.data_ptr())
+    assert L.costmodel_score(model.h, C.c_void_p(odd.data_ptr()), eck.BF16, 1001, 1001, po, None, 0, stream) == eck.EALIGN
+    assert L.costmodel_score(model.h, C.c_void_p(odd.data_ptr()), eck.BF16, 1001, 999, po, None, 0, stream) == eck.EALIGN
+    assert L.costmodel_score(model.h, C.c_void_p(odd32.data_ptr()), eck.F32, 1001, 1001, po, None, 0, stream) == eck.EALIGN
+    even = G.bf16_dev(b16)
+    assert L.costmodel_score(model.h, C.c_void_p(even.data_ptr() + 2), eck.BF16, 1004, 1000, po, None, 0, stream) == eck.EALIGN
+    even32 = G.to_dev(f32)
+    assert L.costmodel_score(model.h, C.c_void_p(even32.data_ptr() + 4), eck.F32, 1004, 1000, po, None, 0, stream) == eck.EALIGN
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 0)                                  # a refused call touches nothing
+    # a bf16 model is refused at creation when no matrix-core kernel exists for its shape
+    h = C.c_void_p()
+    w = (C.c_int32 * 4)(64, 384, 384, 1)
+    assert L.eck_model_create(3, w, eck.BF16, C.byref(h)) == eck.EUNSUPPORTED and h.value is None
+    assert L.eck_model_create(3, w, eck.F32, C.byref(h)) == eck.OK
+    L.eck_model_destroy(h)
+
+
 def test_bf16_model_rows_wider_than_a_32bit_lane_offset(G):
     """A leading dimension so large that eight feature rows span more than 4 GiB selects the kernel variant
     with 64-bit per-lane addresses; the scores must be those of the compact matrix.  (17 GB of device memory,

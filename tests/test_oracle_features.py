@@ -82,6 +82,25 @@ def test_hand_computed_conv(golden):
     assert legal == want_legal
 
 
+def test_hand_computed_knob_schedules_whose_tiles_do_not_divide_the_problem(golden):
+    """The record a KNOB candidate derives (threads along N and M, outputs per thread along both) feeds the
+    per-thread features 2-5, 14, 17, 20, 28; here all 64 values of two such schedules, worked by hand."""
+    rows = golden("hand_knob.txt")
+    pb = synth.bgemm(3, 40, 100, 20, elem_bytes=2, hw=(6, 64, 16384, 512, 4))
+    sp = oracle.Space(pb, oracle.SPACE_KNOB)
+    tiles, tile_k, threads = [16, 32, 64, 128, 256], [8, 16, 32, 64], [64, 128, 256, 512]
+    for row, (tm, tn, tk, T, U, V) in ((0, (32, 64, 8, 128, 4, 1)), (2, (16, 256, 16, 64, 8, 2))):
+        want, want_legal = [int(t) for t in rows[row]], int(rows[row + 1][0])
+        assert len(want) == 64
+        genes = [tiles.index(tm), tiles.index(tn), tile_k.index(tk), threads.index(T), POW2.index(U), POW2.index(V)]
+        x, legal, _, _ = _one(sp, genes)
+        assert x == want, [(i, a, b) for i, (a, b) in enumerate(zip(x, want)) if a != b]
+        assert legal == want_legal
+        x32, _, _, _ = _one(sp, genes, n_feat=32)
+        assert x32 == want[:32]
+        assert x[1] > x[0]          # padded tiles execute more than the useful flop
+
+
 def test_split_candidates_execute_exactly_the_useful_flops():
     for name in ("c2", "c3"):
         cfg = synth.CONFIGS[name]

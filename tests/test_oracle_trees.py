@@ -147,5 +147,12 @@ def test_bad_labels_and_degenerate_nodes():
     assert np.all(np.isinf(nt[0])) and np.all(nf[0] == 0)
     assert lf[0, 1] == 0 and lf[0, 2] == 0 and lf[0, 3] == 0 and lf[0, 0] != 0
     e[3] = 0.0
-    snr, loss = oracle.trees_boost(2, 2, nf, nt, lf, 0, 1, 0.5, x, e)
+    nf, nt, lf = _empty(2, 3)
+    nf[:], nt[:], lf[:] = 1, 7.0, 9.0
+    snr, loss = oracle.trees_boost(2, 2, nf, nt, lf, 1, 2, 0.5, x, e)
     assert np.isnan(snr) and np.isnan(loss)
+    # a rejected call appends its trees empty: no split anywhere, every leaf 0; earlier trees are not touched
+    assert np.all(nf[0] == 1) and np.all(nt[0] == 7.0) and np.all(lf[0] == 9.0)
+    assert np.all(nf[1:] == 0) and np.all(np.isinf(nt[1:])) and np.all(lf[1:] == 0)
+    grown = oracle.trees_predict(2, 2, nf, nt, lf, 0.5, x)
+    assert np.array_equal(grown, oracle.trees_predict(2, 2, nf[:1], nt[:1], lf[:1], 0.5, x))
