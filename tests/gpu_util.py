@@ -93,10 +93,16 @@ def within(got, want, magnitude, rtol):
 
 
 def check_bf16_scores(widths, theta, feat_bits_u16, got, label=""):
-    """The two gates of a bf16 model's scores against the fp64 oracle on the same bf16 feature bits:
-    |g - o| <= 1e-2 * M against the exact forward pass and |g - o_b| <= 1e-4 * M against the oracle mode that
-    rounds the first hidden layer to bf16 where the kernel does (M = the magnitude of the output sum).  Prints
-    both margins and the worst error relative to max(|o|, rms(o))."""
+    """The gates of a bf16 model's scores against the fp64 oracle on the same bf16 feature bits
+    (M = |b3| + sum |w3_j| h2_j, the magnitude of the output sum):
+      1. |g - o| <= 1e-2 * M for every candidate, o = the exact forward pass;
+      2. against o_b, the oracle mode that rounds the first hidden layer to bf16 where the kernel does:
+         |g - o_b| <= 1e-4 * M for all but a few candidates and <= 1e-3 * M for every candidate.
+    The few: the kernel rounds an fp32 sum to bf16, the oracle an fp64 sum; about 3 in 10^6 activations fall so
+    close to a rounding boundary that the two round differently, and one such activation moves the output by up to
+    ~3e-4 * M (tests/test_oracle_score.py measures both figures on the CPU).  At most 1 + 5e-4 * n candidates may
+    exceed 1e-4 * M; everything else differs by fp32 summation order only (~1e-7 * M).
+    Prints the margins and the worst error relative to max(|o|, rms(o))."""
     import oracle
     x = oracle.bf16_bits_to_f32(feat_bits_u16)
     want = oracle.score(widths, theta, x)
@@ -105,13 +111,16 @@ def check_bf16_scores(widths, theta, feat_bits_u16, got, label=""):
     got = np.asarray(got, dtype=np.float64)
     assert np.isfinite(got).all()
     worst = within(got, want, mag, 1e-2)
-    worst_emu = within(got, emu, mag, 1e-4)
+    err_emu = np.abs(got - emu) / mag
+    worst_emu = float(err_emu.max())
+    flipped = int((err_emu > 1e-4).sum())
+    typical = float(np.median(err_emu))
     rms = float(np.sqrt(np.mean(want * want)))
     rel = float(np.max(np.abs(got - want) / np.maximum(np.abs(want), rms)))
-    rel_emu = float(np.max(np.abs(got - emu) / np.maximum(np.abs(emu), rms)))
-    print("bf16 scores %s n=%d: worst/(1e-2 M) = %.3f, vs bf16-activation oracle worst/(1e-4 M) = %.4f; "
-          "worst |g-o|/max(|o|, rms) = %.2e (vs bf16-activation oracle %.2e)"
-          % (label, got.size, worst, worst_emu, rel, rel_emu), flush=True)
+    print("bf16 scores %s n=%d: worst |g-o| = %.3f x 1e-2 M; vs bf16-activation oracle: median %.1e M, worst %.1e M, "
+          "%d candidates beyond 1e-4 M (allowed %d); worst |g-o|/max(|o|, rms) = %.2e"
+          % (label, got.size, worst, typical, worst_emu, flipped, 1 + int(5e-4 * got.size), rel), flush=True)
     assert worst <= 1.0, worst
-    assert worst_emu <= 1.0, worst_emu
+    assert flipped <= 1 + int(5e-4 * got.size), flipped
+    assert worst_emu <= 1e-3, worst_emu
     return worst, worst_emu, rel

@@ -123,3 +123,45 @@ def test_why_the_tolerance_refers_to_the_magnitude_of_the_sum():
         assert mag.min() > 3 * np.abs(exact).max() or seed == 3
     assert vs_rms[1] > 10 * vs_rms[0]          # same arithmetic, wildly different "relative" error
     assert max(vs_mag) < 2e-3 and max(vs_mag) < 2 * min(vs_mag)
+
+
+def test_why_a_few_candidates_may_differ_from_the_bf16_activation_oracle():
+    """The bf16-activation mode rounds an fp64 sum to bf16; a kernel that accumulates in fp32 rounds an fp32 sum.
+    The two sums differ by ~2^-24 of their terms, so once in a few 10^5 activations they fall on different sides
+    of a bf16 rounding boundary; that one activation then differs by a whole bf16 step (2^-8 of its value) and
+    moves the output by a few 1e-4 of the sum's magnitude M.  Measured here with numpy's fp32 matrix product
+    standing in for any fp32 accumulation order: the rate per activation and the largest effect, which size the
+    allowance of the GPU parity gate (at most 1 + 5e-4 n candidates beyond 1e-4 M, none beyond 1e-3 M)."""
+    widths = [64, 256, 256, 1]
+    cfg = synth.CONFIGS["c2"]
+    sp = oracle.Space(cfg["problem"], oracle.SPACE_SPLIT)
+    n = 1 << 15
+    genes = oracle.enumerate_candidates(sp, oracle.MODE_SAMPLE, n, seed=cfg["sample_seed"])
+    _, _, b16, _ = oracle.features(sp, genes, 64)
+    x = oracle.bf16_bits_to_f32(b16)
+    theta = synth.mlp_theta(widths, cfg["weight_seeds"][0], bf16=True)
+    W1, b1 = theta[:64 * 256].reshape(64, 256), theta[64 * 256:64 * 256 + 256]
+    pre32 = np.maximum(x.T @ W1 + b1, 0).astype(np.float32)                               # fp32 accumulation
+    pre64 = np.maximum(x.T.astype(np.float64) @ W1.astype(np.float64) + b1, 0).astype(np.float32)
+    def rne(v):    # round-to-nearest-even to bf16 on the bits (finite inputs); checked against the oracle's below
+        u = np.ascontiguousarray(v, dtype=np.float32).view(np.uint32).astype(np.uint64)
+        return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+    some = pre32.reshape(-1)[::9973]
+    assert [int(b) for b in rne(some)] == [oracle.bf16_rne(float(v)) for v in some]
+    flips = rne(pre32) != rne(pre64)
+    rate = flips.mean()
+    assert 0 < flips.sum() and rate < 5e-5                 # rare, but it happens
+    # the effect of those flips on the output: replace the oracle's rounded activations by the fp32-rounded ones
+    h32 = oracle.bf16_bits_to_f32(rne(pre32)).astype(np.float64)
+    h64 = oracle.bf16_bits_to_f32(rne(pre64)).astype(np.float64)
+    o = 64 * 256 + 256
+    W2, b2 = theta[o:o + 256 * 256].reshape(256, 256).astype(np.float64), theta[o + 256 * 256:o + 256 * 256 + 256]
+    w3, b3 = theta[-257:-1].astype(np.float64), float(theta[-1])
+    out = lambda h: np.maximum(h @ W2 + b2, 0) @ w3 + b3
+    mag = oracle.score_magnitude(widths, theta, x)
+    emu = oracle.score(widths, theta, x, emulate_bf16=True)
+    assert np.max(np.abs(out(h64) - emu) / mag) < 1e-12    # the reconstruction above is the oracle's mode
+    moved = np.abs(out(h32) - out(h64)) / mag
+    assert moved.max() < 1e-3
+    assert (moved > 1e-4).sum() <= 1 + int(5e-4 * n)
+    assert np.all(moved[~flips.any(axis=1)] == 0)          # nothing else differs
