@@ -264,8 +264,11 @@ int32_t costmodel_score(const eck_model *model, const void *feat, int32_t feat_d
 
 /* ------------------------------------------------------------------ select */
 
-/* Bytes of workspace topk_select needs for these sizes (0 on invalid sizes). */
+/* Bytes of workspace topk_select needs for these sizes in THRESHOLD mode or
+ * without latencies, and in RANK mode with m_latency (which adds the lists of
+ * the latency stage).  0 on invalid sizes. */
 uint64_t topk_select_workspace_bytes(uint64_t n, uint32_t n_segments, uint32_t k);
+uint64_t topk_select_rank_workspace_bytes(uint64_t n, uint32_t n_segments, uint32_t k, uint32_t m_latency);
 
 /* Selection under the paper's objective -- low latency first, then least
  * energy (Sec. 4.3, 4.4; Alg. 1).  The n candidates form n_segments equal
@@ -274,16 +277,20 @@ uint64_t topk_select_workspace_bytes(uint64_t n, uint32_t n_segments, uint32_t k
  *              (alpha-1)*|L_min| (fp32, product and sum rounded separately;
  *              +inf when alpha is +inf); feasible = legal and latency <= tau.
  *   RANK:      feasible = the m_latency legal candidates of least latency
- *              (Alg. 1's "fastest M"), ties to the lower index.
+ *              (Alg. 1's "fastest M"), ties to the lower index.  m_latency is
+ *              at most ECK_MAX_K unless it covers the whole segment.
  *   latency == NULL: feasible = legal.  legal == NULL: all legal.
  * Output per segment: the k feasible candidates of least energy in ascending
  * order (IEEE total order, ties to the lower index): idx_out uint32 [S][k]
  * (index within the segment, 0xFFFFFFFF padding), energy_out float [S][k]
  * (+inf padding), count_out uint32 [S] = min(k, #feasible).  NaN energies or
  * latencies are never feasible.  All pointers device; ws device, 16-byte aligned.
+ * The score arrays are read once (THRESHOLD with a finite alpha reads the
+ * latencies once more, for L_min; RANK reads once per stage); the result does
+ * not depend on the order of execution.
  * Errors: EINVAL (nulls, n == 0, k == 0, bad mode, alpha < 1 or NaN), ESHAPE
  * (n % n_segments, k > n/n_segments, segment longer than 2^32-2), EUNSUPPORTED
- * (k > ECK_MAX_K), EWORKSPACE. */
+ * (k or a partial m_latency > ECK_MAX_K), EWORKSPACE, EALIGN (ws). */
 int32_t topk_select(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
                     uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
                     uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,

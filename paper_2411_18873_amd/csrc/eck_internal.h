@@ -68,4 +68,8 @@ struct eck_model {
 namespace eck {
 // re-derive the packed weights from theta (BF16 models); enqueued on stream
 int32_t model_repack(eck_model *m, hipStream_t stream);
+// topk_select on a workspace of the caller's or of the library's
+int32_t topk_select_impl(const float *energy, const float *latency, const uint8_t *legal, uint64_t n, uint32_t n_segments,
+                         uint32_t k, int32_t mode, float alpha, uint32_t m_latency, uint32_t *idx_out, float *energy_out,
+                         uint32_t *count_out, void *ws, uint64_t ws_bytes, void *stream);
 } // namespace eck

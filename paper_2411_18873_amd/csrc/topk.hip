@@ -1,38 +1,30 @@
 // Selection under the "low latency first, then least energy" objective
 // (Sec. 4.3, 4.4; Alg. 1 LatencyEvaAndPick / EnergyModelEvaAndPick).  HIP, gfx950.
 //
-// Method: radix select on the composite key (order-preserving energy bits,
-// index within segment), 12 bits per pass from the top, with per-block LDS
-// histograms merged by integer atomics; every feasible candidate whose
-// composite is at most the k-th one is then gathered and the (at most k)
-// gathered entries are sorted in LDS.  Composites are distinct, so exactly
-// min(k, #feasible) entries qualify and ties fall to the lower index.  Only
-// integer atomics are used and the gathered set is sorted afterwards, so the
-// result does not depend on execution order.
+// Method: a tournament of exact block-local selections.  Every candidate is the composite key
+// (order-preserving score bits, index within its segment); composites of one segment are distinct, so
+// "the k smallest" is a unique set and ties fall to the lower index.  Level 0 reads the score arrays
+// ONCE: a block takes a chunk of one segment, keeps the composites of its feasible candidates in
+// registers, finds its own k smallest with a radix select on LDS histograms (nothing leaves the
+// block) and writes just those.  Every further level does the same on the lists of the level before
+// it, until one block per segment holds the segment's k smallest, sorts them in LDS and writes the
+// result.  The k smallest of a segment are among the k smallest of each chunk, so the result is exact;
+// no global atomics, no flags between blocks: blocks only meet at kernel boundaries, and the output does
+// not depend on execution order.
 #include "eck_internal.h"
 
 using namespace eck;
 
 namespace {
 
-constexpr int DIGIT_BITS = 12;
+constexpr int DIGIT_BITS = 11;
 constexpr int BINS = 1 << DIGIT_BITS;
-constexpr int MAX_ITEMS = 64; // most candidates per thread in the streaming kernels (a multiple of 4)
-constexpr int BLOCK = 256;
+constexpr int ITEMS = 16;                // composites a thread holds
+constexpr uint64_t NONE = ~0ull;         // no candidate (a NaN score never makes a composite, so no composite is all ones)
+constexpr uint32_t LATMIN_PARTS = 256;   // most per-block latency minima per segment
 
 enum Pred { PRED_PLAIN = 0, PRED_THRESHOLD = 1, PRED_RANK_STAGE_A = 2, PRED_RANK_STAGE_B = 3 };
-
-struct SegState {
-    uint32_t lat_min_key; // least order-key of a legal latency (THRESHOLD)
-    uint32_t remaining;   // rank still to be found inside the current prefix (1-based count)
-    uint32_t done;        // threshold final
-    uint32_t gathered;    // entries appended by the gather kernel
-    uint64_t prefix;      // composite bits fixed so far (in place, low bits zero)
-    uint64_t threshold;   // final: take composites <= threshold
-    uint64_t lat_threshold; // RANK: composite threshold of stage A
-    uint32_t arrived;       // blocks of the running histogram pass that have merged their bins
-    uint32_t pad;
-};
+enum Source { SRC_SCORES_VEC = 0, SRC_SCORES = 1, SRC_LIST = 2 };
 
 __device__ __forceinline__ uint32_t order_key(float x)
 {
@@ -50,98 +42,71 @@ struct SelectArgs {
     const float *latency;
     const uint8_t *legal;
     uint64_t seg_len;
-    uint32_t idx_bits;   // composite = key << idx_bits | idx
-    float slack_factor;  // alpha - 1 (THRESHOLD)
+    uint32_t idx_bits;          // composite = key << idx_bits | idx
+    float slack_factor;         // alpha - 1 (THRESHOLD)
     int alpha_inf;
-    SegState *state;
-    uint32_t *hist;      // [S][BINS]
-    uint64_t *gather;    // [S][k]
+    const uint32_t *lat_parts;  // THRESHOLD: [S][lat_parts_n] least latency order keys, one per block of latmin_kernel
+    uint32_t lat_parts_n;
+    const uint64_t *lat_thr;    // RANK stage B: [S] feasible = latency composite <= lat_thr[s]
+    const uint64_t *list_in;    // SRC_LIST: [S][list_len] composites of the level before, NONE where empty
+    uint64_t list_len;
+    uint64_t *list_out;         // not the last level: [S][gridDim.x][k]
     uint32_t k;
-    uint32_t items;      // candidates per thread in the streaming kernels (multiple of 4)
+    uint32_t *idx_out;          // last level: the result ...
+    float *energy_out;
+    uint32_t *count_out;
+    uint64_t *thr_out;          // ... or (RANK stage A) only the composite the k-th smallest does not exceed
 };
 
-__device__ __forceinline__ float threshold_tau(const SelectArgs &a, const SegState &st)
-{
-    if (a.alpha_inf || st.lat_min_key == 0xFFFFFFFFu) return __builtin_inff();
-    const float lmin = key_to_float(st.lat_min_key);
-    return __fadd_rn(lmin, __fmul_rn(a.slack_factor, fabsf(lmin)));
-}
+// ---------------------------------------------------------------- latency minimum (THRESHOLD)
 
-__global__ void init_kernel(SegState *state, uint32_t n_seg, uint32_t *hist, uint32_t k)
+// least order key of a legal, non-NaN latency in this block's slice of the segment; no atomics, so nothing
+// has to be initialised: every block writes its slot
+template <bool VEC>
+__global__ __launch_bounds__(256) void latmin_kernel(const float *__restrict__ latency, const uint8_t *__restrict__ legal,
+                                                     uint64_t seg_len, uint64_t slice, uint32_t *__restrict__ parts)
 {
-    const uint32_t s = blockIdx.x;
-    for (uint32_t b = threadIdx.x; b < BINS; b += blockDim.x) hist[(uint64_t)s * BINS + b] = 0;
-    if (threadIdx.x == 0) {
-        SegState st;
-        st.lat_min_key = 0xFFFFFFFFu;
-        st.remaining = k;
-        st.done = 0;
-        st.gathered = 0;
-        st.prefix = 0;
-        st.threshold = 0;
-        st.lat_threshold = ~0ull;
-        st.arrived = 0;
-        st.pad = 0;
-        state[s] = st;
-    }
-    (void)n_seg;
-}
-
-// restart the radix rounds (between RANK stage A and B)
-__global__ void restart_kernel(SegState *state, uint32_t k)
-{
-    SegState &st = state[blockIdx.x];
-    if (threadIdx.x == 0) {
-        st.lat_threshold = st.threshold;
-        st.remaining = k;
-        st.done = 0;
-        st.prefix = 0;
-        st.threshold = 0;
-    }
-}
-
-// Streaming order of the three full passes: a thread takes items / 4 groups of four consecutive candidates,
-// consecutive lanes consecutive groups (16-byte loads of the float arrays, 4-byte loads of the flags).  The
-// host launches the VEC form when segment length and pointers allow it, the scalar form otherwise.
-template <bool VEC, class Visit>
-__device__ __forceinline__ void stream_segment(const SelectArgs &a, uint64_t seg_base, bool want_energy,
-                                               bool want_latency, Visit visit)
-{
-    const uint64_t start = (uint64_t)blockIdx.x * ((uint64_t)BLOCK * a.items);
+    const uint32_t s = blockIdx.y;
+    const uint64_t seg_base = (uint64_t)s * seg_len;
+    const uint64_t lo = (uint64_t)blockIdx.x * slice, hi = lo + slice < seg_len ? lo + slice : seg_len;
+    uint32_t best = 0xFFFFFFFFu;
     if (VEC) {
-#pragma unroll 4
-        for (uint32_t j = 0; j < a.items / 4; ++j) {
-            const uint64_t i = start + ((uint64_t)j * BLOCK + threadIdx.x) * 4;
-            if (i >= a.seg_len) break;
+        for (uint64_t i = lo + 4ull * threadIdx.x; i < hi; i += 4ull * 256) {
             const uint64_t g = seg_base + i;
             uint32_t flags = 0x01010101u;
-            if (a.legal) flags = *reinterpret_cast<const uint32_t *>(a.legal + g);
-            float4 e = {0, 0, 0, 0}, l = {0, 0, 0, 0};
-            if (flags) {
-                if (want_energy) e = *reinterpret_cast<const float4 *>(a.energy + g);
-                if (want_latency) l = *reinterpret_cast<const float4 *>(a.latency + g);
-            }
-            const float ev[4] = {e.x, e.y, e.z, e.w}, lv[4] = {l.x, l.y, l.z, l.w};
+            if (legal) flags = *reinterpret_cast<const uint32_t *>(legal + g);
+            if (!flags) continue;
+            const float4 l = *reinterpret_cast<const float4 *>(latency + g);
+            const float lv[4] = {l.x, l.y, l.z, l.w};
 #pragma unroll
             for (int t = 0; t < 4; ++t)
-                if ((flags >> (8 * t)) & 0xFFu) visit((uint32_t)i + t, ev[t], lv[t]);
+                if (((flags >> (8 * t)) & 0xFFu) && lv[t] == lv[t]) best = min(best, order_key(lv[t]));
         }
     } else {
-#pragma unroll 4
-        for (uint32_t j = 0; j < a.items; ++j) {
-            const uint64_t i = start + (uint64_t)j * BLOCK + threadIdx.x;
-            if (i >= a.seg_len) break;
+        for (uint64_t i = lo + threadIdx.x; i < hi; i += 256) {
             const uint64_t g = seg_base + i;
-            if (a.legal && !a.legal[g]) continue;
-            visit((uint32_t)i, want_energy ? a.energy[g] : 0.0f, want_latency ? a.latency[g] : 0.0f);
+            if (legal && !legal[g]) continue;
+            const float l = latency[g];
+            if (l == l) best = min(best, order_key(l));
         }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) best = min(best, (uint32_t)__shfl_xor((int)best, off));
+    __shared__ uint32_t wave_best[4];
+    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) best = min(best, wave_best[w]);
+        parts[(uint64_t)s * gridDim.x + blockIdx.x] = best;
     }
 }
 
-// composite of a legal candidate with scores (e, l) under predicate PRED, or false if infeasible
+// ---------------------------------------------------------------- one level of the tournament
+
+// composite of a legal candidate with scores (e, l) under predicate PRED, or NONE if infeasible
 template <int PRED>
-__device__ __forceinline__ bool composite_from(const SelectArgs &a, uint32_t i, float e, float l, float tau,
-                                               uint64_t lat_thr, uint64_t *comp)
+__device__ __forceinline__ uint64_t composite_of(const SelectArgs &a, uint32_t i, float e, float l, float tau,
+                                                 uint64_t lat_thr)
 {
     float value;
     if (PRED == PRED_RANK_STAGE_A) {
@@ -149,234 +114,297 @@ __device__ __forceinline__ bool composite_from(const SelectArgs &a, uint32_t i, 
     } else {
         value = e;
         if (PRED == PRED_THRESHOLD) {
-            if (!(l <= tau)) return false;
+            if (!(l <= tau)) return NONE;
         } else if (PRED == PRED_RANK_STAGE_B) {
-            if (l != l) return false;
-            if ((((uint64_t)order_key(l) << a.idx_bits) | i) > lat_thr) return false;
+            if (l != l) return NONE;
+            if ((((uint64_t)order_key(l) << a.idx_bits) | i) > lat_thr) return NONE;
         }
     }
-    if (value != value) return false;
-    *comp = ((uint64_t)order_key(value) << a.idx_bits) | i;
-    return true;
+    if (value != value) return NONE;
+    return ((uint64_t)order_key(value) << a.idx_bits) | i;
 }
 
-template <bool VEC>
-__global__ __launch_bounds__(BLOCK) void latmin_kernel(SelectArgs a)
+// LDS of a block: the digit histogram, a handful of words, and (last level) the sort buffer behind them
+template <int T>
+struct Shared {
+    uint32_t hist[BINS];
+    uint32_t wave_sum[T / 64];
+    uint32_t found_digit, found_below, found_count, cursor;
+    uint32_t lat_min;
+};
+
+template <int T>
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, Shared<T> &sh)
 {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += (uint32_t)__shfl_xor((int)v, off);
+    __syncthreads(); // wave_sum may still be read from an earlier use
+    if ((threadIdx.x & 63) == 0) sh.wave_sum[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t total = 0;
+#pragma unroll
+    for (int w = 0; w < T / 64; ++w) total += sh.wave_sum[w];
+    return total;
+}
+
+// The composite that exactly min(k, #valid) of the block's composites do not exceed.  Radix select from the
+// top digit down: histogram of the digit over the composites that match the digits fixed so far, prefix sums
+// over the bins, the bin holding the wanted rank fixes the next digit.  Ends as soon as a whole bin is wanted.
+template <int T>
+__device__ uint64_t block_threshold(const uint64_t (&c)[ITEMS], uint32_t k, uint32_t total_bits, Shared<T> &sh,
+                                    uint32_t *n_selected)
+{
+    uint32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) mine += c[j] != NONE;
+    const uint32_t total = block_sum<T>(mine, sh);
+    if (total <= k) {
+        *n_selected = total;
+        return NONE - 1; // every composite is below NONE
+    }
+    *n_selected = k;
+    constexpr int PER = BINS / T; // consecutive bins per thread in the scan
+    uint64_t prefix = 0;
+    uint32_t remaining = k, top = total_bits;
+    for (;;) {
+        const uint32_t bits = top < (uint32_t)DIGIT_BITS ? top : (uint32_t)DIGIT_BITS;
+        const uint32_t shift = top - bits, mask = (1u << bits) - 1;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) sh.hist[threadIdx.x * PER + j] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const uint64_t v = c[j];
+            // (a shift by 64 is undefined: the first pass of a 64-bit composite has no digits above it)
+            const bool in_prefix = top >= 64 || (v >> top) == (prefix >> top);
+            if (v != NONE && in_prefix) atomicAdd(&sh.hist[(uint32_t)(v >> shift) & mask], 1u);
+        }
+        __syncthreads();
+        uint32_t local[PER], sum = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            local[j] = sh.hist[threadIdx.x * PER + j];
+            sum += local[j];
+        }
+        uint32_t incl = sum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t up = (uint32_t)__shfl_up((int)incl, off);
+            if ((threadIdx.x & 63) >= (uint32_t)off) incl += up;
+        }
+        if ((threadIdx.x & 63) == 63) sh.wave_sum[threadIdx.x >> 6] = incl;
+        __syncthreads();
+        uint32_t below = incl - sum;
+#pragma unroll
+        for (int w = 0; w < T / 64; ++w)
+            if (w < (int)(threadIdx.x >> 6)) below += sh.wave_sum[w];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            if (below < remaining && remaining <= below + local[j]) {
+                sh.found_digit = threadIdx.x * PER + j;
+                sh.found_below = below;
+                sh.found_count = local[j];
+            }
+            below += local[j];
+        }
+        __syncthreads();
+        const uint64_t digit = sh.found_digit;
+        const uint32_t under = sh.found_below, count = sh.found_count;
+        prefix |= digit << shift;
+        remaining -= under;
+        if (shift == 0 || remaining == count) return prefix | ((shift ? (1ull << shift) : 1ull) - 1);
+        top = shift;
+        __syncthreads(); // found_* and the histogram are rewritten in the next pass
+    }
+}
+
+// One block = T threads x ITEMS composites.  Source: a chunk of T * ITEMS candidates of segment blockIdx.y
+// (four consecutive candidates per load where VEC allows it), or the same number of composites of the list
+// the level before wrote.  Not the last level (gridDim.x > 1): the block's selection goes to its k slots of
+// list_out, the unused slots are set to NONE.  Last level: sort, unpack, write the result.
+template <int T, int SRC, int PRED>
+__global__ __launch_bounds__(T) void select_kernel(SelectArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    Shared<T> &sh = *reinterpret_cast<Shared<T> *>(lds_raw);
+    uint64_t *sort_buf = reinterpret_cast<uint64_t *>(lds_raw + ((sizeof(Shared<T>) + 15) & ~(size_t)15));
     const uint32_t s = blockIdx.y;
-    uint32_t best = 0xFFFFFFFFu;
-    stream_segment<VEC>(a, (uint64_t)s * a.seg_len, false, true, [&](uint32_t, float, float l) {
-        if (l == l) best = min(best, order_key(l));
-    });
+    uint64_t c[ITEMS];
+    if (SRC == SRC_LIST) {
+        const uint64_t *in = a.list_in + (uint64_t)s * a.list_len;
+        const uint64_t start = (uint64_t)blockIdx.x * (T * ITEMS);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) best = min(best, (uint32_t)__shfl_xor((int)best, off));
-    __shared__ uint32_t wave_best[BLOCK / 64];
-    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        for (int w = 1; w < BLOCK / 64; ++w) best = min(best, wave_best[w]);
-        if (best != 0xFFFFFFFFu) atomicMin(&a.state[s].lat_min_key, best);
-    }
-}
-
-__device__ void scan_segment(const SelectArgs &a, uint32_t s, uint32_t shift, uint32_t bits, int first_pass);
-
-// histogram of the digit at `shift` (width `bits`) over feasible composites that match the prefix above
-// it.  The block that finishes a segment last (a ticket from an integer atomic, after a device-wide
-// fence) also locates the bin of the wanted rank and prepares the next pass.
-template <int PRED, bool VEC>
-__global__ __launch_bounds__(BLOCK) void hist_kernel(SelectArgs a, uint32_t shift, uint32_t bits, int first_pass)
-{
-    const uint32_t s = blockIdx.y;
-    const SegState st = a.state[s];
-    if (st.done) return;
-    __shared__ uint32_t bins[BINS];
-    for (uint32_t b = threadIdx.x; b < BINS; b += BLOCK) bins[b] = 0;
-    __syncthreads();
-    const float tau = PRED == PRED_THRESHOLD ? threshold_tau(a, st) : 0.0f;
-    const uint32_t top = shift + bits; // bits at and above `top` must equal the prefix
-    const uint32_t mask = (1u << bits) - 1;
-    constexpr bool NEED_E = PRED != PRED_RANK_STAGE_A, NEED_L = PRED != PRED_PLAIN;
-    stream_segment<VEC>(a, (uint64_t)s * a.seg_len, NEED_E, NEED_L, [&](uint32_t i, float e, float l) {
-        uint64_t comp;
-        if (!composite_from<PRED>(a, i, e, l, tau, st.lat_threshold, &comp)) return;
-        if (top < 64 && (comp >> top) != (st.prefix >> top)) return;
-        atomicAdd(&bins[(uint32_t)(comp >> shift) & mask], 1u);
-    });
-    __syncthreads();
-    uint32_t *out = a.hist + (uint64_t)s * BINS;
-    for (uint32_t b = threadIdx.x; b < BINS; b += BLOCK)
-        if (bins[b]) atomicAdd(&out[b], bins[b]);
-    // Last block of the segment?  Every merge above is a device-scope atomic, complete (performed where
-    // all compute units see it) once this wavefront's memory counter has drained, which the barrier's
-    // release makes every wavefront do; the ticket is drawn after that, and the block that draws the last
-    // one reads the bins with device-scope atomic loads.  No cache write-back is involved, so no
-    // device-wide fence (which costs a full L2 write-back per block) is needed.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    __shared__ uint32_t ticket;
-    if (threadIdx.x == 0) ticket = atomicAdd(&a.state[s].arrived, 1u);
-    __syncthreads();
-    if (ticket != gridDim.x - 1) return;
-    scan_segment(a, s, shift, bits, first_pass);
-}
-
-// Run by one block per segment once the segment's histogram is complete: locate the bin that holds the
-// remaining-th smallest, fix its digit, clear the histogram and the arrival count for the next pass.
-__device__ void scan_segment(const SelectArgs &a, uint32_t s, uint32_t shift, uint32_t bits, int first_pass)
-{
-    SegState &st = a.state[s];
-    // read before any thread may update the state (updates happen after the barriers below)
-    const uint32_t remaining = st.remaining;
-    const uint64_t prefix_in = st.prefix;
-    uint32_t *h = a.hist + (uint64_t)s * BINS;
-    const uint32_t nbins = 1u << bits;
-    constexpr int PER = BINS / BLOCK; // consecutive bins per thread
-    uint32_t local[PER], sum = 0;
-    (void)nbins; // bins at and above nbins were never incremented
-    // The other blocks' contributions were made by device-scope atomics and are complete; read them past
-    // every cache level that is not shared by the whole device, then leave zero behind for
-    // the next pass (a later kernel).
-    static_assert(PER == 16, "four 16-byte loads per thread");
-    {
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-        u32x4 q0, q1, q2, q3;
-        const uint32_t *mine = h + threadIdx.x * PER;
-        // the compiler would wait for each cache-bypassing load separately; here all four are in flight
-        asm volatile("global_load_dwordx4 %0, %4, off sc0 sc1\n\t"
-                     "global_load_dwordx4 %1, %4, off offset:16 sc0 sc1\n\t"
-                     "global_load_dwordx4 %2, %4, off offset:32 sc0 sc1\n\t"
-                     "global_load_dwordx4 %3, %4, off offset:48 sc0 sc1\n\t"
-                     "s_waitcnt vmcnt(0)"
-                     : "=&v"(q0), "=&v"(q1), "=&v"(q2), "=&v"(q3)
-                     : "v"(mine)
-                     : "memory");
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            local[e] = q0[e];
-            local[4 + e] = q1[e];
-            local[8 + e] = q2[e];
-            local[12 + e] = q3[e];
+        for (int j = 0; j < ITEMS; ++j) {
+            const uint64_t i = start + (uint64_t)j * T + threadIdx.x;
+            c[j] = i < a.list_len ? in[i] : NONE;
         }
-    }
+    } else {
+        float tau = 0.0f;
+        uint64_t lat_thr = 0;
+        if (PRED == PRED_THRESHOLD) {
+            // tau = L_min + (alpha - 1) |L_min|, product and sum rounded separately; L_min from the per-block minima
+            if (a.alpha_inf) {
+                tau = __builtin_inff();
+            } else {
+                uint32_t best = 0xFFFFFFFFu;
+                for (uint32_t p = threadIdx.x; p < a.lat_parts_n; p += T) best = min(best, a.lat_parts[(uint64_t)s * a.lat_parts_n + p]);
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        h[threadIdx.x * PER + j] = 0;
-        sum += local[j];
-    }
-    // exclusive prefix of the per-thread sums: shuffles inside a wavefront, then the four wavefront totals
-    uint32_t incl = sum;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t up = (uint32_t)__shfl_up((int)incl, off);
-        if ((threadIdx.x & 63) >= (uint32_t)off) incl += up;
-    }
-    __shared__ uint32_t wave_total[BLOCK / 64];
-    if ((threadIdx.x & 63) == 63) wave_total[threadIdx.x >> 6] = incl;
-    __syncthreads();
-    uint32_t before = 0, total = 0;
-#pragma unroll
-    for (int w = 0; w < BLOCK / 64; ++w) {
-        if (w < (int)(threadIdx.x >> 6)) before += wave_total[w];
-        total += wave_total[w];
-    }
-    const uint32_t first_below = before + incl - sum; // candidates in the bins of lower threads
-    if (threadIdx.x == 0) st.arrived = 0;
-    if (first_pass && total < remaining) {
-        // fewer feasible candidates than k: take them all
-        if (threadIdx.x == 0) {
-            st.threshold = ~0ull;
-            st.done = 1;
+                for (int off = 32; off > 0; off >>= 1) best = min(best, (uint32_t)__shfl_xor((int)best, off));
+                if (threadIdx.x == 0) sh.lat_min = 0xFFFFFFFFu;
+                __syncthreads();
+                if ((threadIdx.x & 63) == 0) atomicMin(&sh.lat_min, best);
+                __syncthreads();
+                best = sh.lat_min;
+                if (best == 0xFFFFFFFFu) {
+                    tau = __builtin_inff(); // nothing legal: nothing will be feasible either
+                } else {
+                    const float lmin = key_to_float(best);
+                    tau = __fadd_rn(lmin, __fmul_rn(a.slack_factor, fabsf(lmin)));
+                }
+            }
+        } else if (PRED == PRED_RANK_STAGE_B) {
+            lat_thr = a.lat_thr[s];
         }
-        return;
-    }
-    uint32_t below = first_below;
+        constexpr bool NEED_E = PRED != PRED_RANK_STAGE_A, NEED_L = PRED != PRED_PLAIN;
+        const uint64_t seg_base = (uint64_t)s * a.seg_len;
+        const uint64_t start = (uint64_t)blockIdx.x * (T * ITEMS);
+        if (SRC == SRC_SCORES_VEC) {
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-        const uint32_t c = local[j];
-        if (below < remaining && remaining <= below + c) {
-            // this bin holds the target
-            const uint64_t digit = threadIdx.x * PER + j;
-            const uint64_t prefix = prefix_in | (digit << shift);
-            st.prefix = prefix;
-            st.remaining = remaining - below;
-            if (shift == 0 || remaining == below + c) {
-                // last digit fixed, or the whole bin is wanted: everything up to the bin's top qualifies
-                st.threshold = prefix | ((shift ? (1ull << shift) : 1ull) - 1);
-                st.done = 1;
+            for (int j = 0; j < ITEMS / 4; ++j) {
+                const uint64_t i = start + ((uint64_t)j * T + threadIdx.x) * 4;
+                uint32_t flags = 0;
+                float4 e = {0, 0, 0, 0}, l = {0, 0, 0, 0};
+                if (i < a.seg_len) { // seg_len is a multiple of 4 on this path
+                    const uint64_t g = seg_base + i;
+                    flags = 0x01010101u;
+                    if (a.legal) flags = *reinterpret_cast<const uint32_t *>(a.legal + g);
+                    if (flags) {
+                        if (NEED_L) l = *reinterpret_cast<const float4 *>(a.latency + g);
+                        if (NEED_E) e = *reinterpret_cast<const float4 *>(a.energy + g);
+                    }
+                }
+                const float ev[4] = {e.x, e.y, e.z, e.w}, lv[4] = {l.x, l.y, l.z, l.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    c[4 * j + t] = ((flags >> (8 * t)) & 0xFFu) ? composite_of<PRED>(a, (uint32_t)i + t, ev[t], lv[t], tau, lat_thr)
+                                                                : NONE;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                const uint64_t i = start + (uint64_t)j * T + threadIdx.x;
+                uint64_t v = NONE;
+                if (i < a.seg_len) {
+                    const uint64_t g = seg_base + i;
+                    if (!a.legal || a.legal[g])
+                        v = composite_of<PRED>(a, (uint32_t)i, NEED_E ? a.energy[g] : 0.0f, NEED_L ? a.latency[g] : 0.0f, tau,
+                                               lat_thr);
+                }
+                c[j] = v;
             }
         }
-        below += c;
     }
-}
 
-template <int PRED, bool VEC>
-__global__ __launch_bounds__(BLOCK) void gather_kernel(SelectArgs a)
-{
-    const uint32_t s = blockIdx.y;
-    const SegState st = a.state[s];
-    const float tau = PRED == PRED_THRESHOLD ? threshold_tau(a, st) : 0.0f;
-    constexpr bool NEED_E = PRED != PRED_RANK_STAGE_A, NEED_L = PRED != PRED_PLAIN;
-    stream_segment<VEC>(a, (uint64_t)s * a.seg_len, NEED_E, NEED_L, [&](uint32_t i, float e, float l) {
-        uint64_t comp;
-        if (!composite_from<PRED>(a, i, e, l, tau, st.lat_threshold, &comp)) return;
-        if (comp > st.threshold) return;
-        const uint32_t slot = atomicAdd(&a.state[s].gathered, 1u);
-        if (slot < a.k) a.gather[(uint64_t)s * a.k + slot] = comp; // never more than k qualify
-    });
-}
-
-// one block per segment: bitonic sort of the gathered composites, then unpack
-__global__ __launch_bounds__(BLOCK) void sort_kernel(SelectArgs a, uint32_t pow2, uint32_t *idx_out, float *energy_out,
-                                                     uint32_t *count_out)
-{
-    extern __shared__ uint64_t keys[];
-    const uint32_t s = blockIdx.x;
-    const uint32_t count = min(a.state[s].gathered, a.k);
-    for (uint32_t i = threadIdx.x; i < pow2; i += BLOCK) keys[i] = i < count ? a.gather[(uint64_t)s * a.k + i] : ~0ull;
+    uint32_t n_selected;
+    const uint64_t thr = block_threshold<T>(c, a.k, 32 + a.idx_bits, sh, &n_selected);
+    const bool last_level = gridDim.x == 1;
+    if (last_level && a.thr_out) {
+        // RANK stage A: feasible = latency composite <= thr (everything legal when fewer than k exist)
+        if (threadIdx.x == 0) a.thr_out[s] = n_selected < a.k ? NONE : thr;
+        return;
+    }
+    if (threadIdx.x == 0) sh.cursor = 0;
+    __syncthreads();
+    if (!last_level) {
+        uint64_t *out = a.list_out + ((uint64_t)s * gridDim.x + blockIdx.x) * a.k;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if (c[j] <= thr) out[atomicAdd(&sh.cursor, 1u)] = c[j]; // NONE > thr; exactly n_selected qualify
+        for (uint32_t i = n_selected + threadIdx.x; i < a.k; i += T) out[i] = NONE;
+        return;
+    }
+    // last level: bitonic sort of the selection (padded to a power of two with NONE), then unpack
+    uint32_t pow2 = 2;
+    while (pow2 < a.k) pow2 <<= 1;
+    for (uint32_t i = threadIdx.x; i < pow2; i += T) sort_buf[i] = NONE;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j)
+        if (c[j] <= thr) sort_buf[atomicAdd(&sh.cursor, 1u)] = c[j];
     __syncthreads();
     for (uint32_t size = 2; size <= pow2; size <<= 1)
         for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (uint32_t t = threadIdx.x; t < pow2 / 2; t += BLOCK) {
+            for (uint32_t t = threadIdx.x; t < pow2 / 2; t += T) {
                 const uint32_t lo = 2 * t - (t & (stride - 1)); // index with the `stride` bit clear
                 const uint32_t hi = lo + stride;
                 const bool ascending = (lo & size) == 0;
-                const uint64_t x = keys[lo], y = keys[hi];
+                const uint64_t x = sort_buf[lo], y = sort_buf[hi];
                 if ((x > y) == ascending) {
-                    keys[lo] = y;
-                    keys[hi] = x;
+                    sort_buf[lo] = y;
+                    sort_buf[hi] = x;
                 }
             }
             __syncthreads();
         }
     const uint64_t idx_mask = (1ull << a.idx_bits) - 1;
-    for (uint32_t i = threadIdx.x; i < a.k; i += BLOCK) {
-        const uint64_t c = keys[i];
-        const bool valid = i < count;
-        idx_out[(uint64_t)s * a.k + i] = valid ? (uint32_t)(c & idx_mask) : 0xFFFFFFFFu;
-        energy_out[(uint64_t)s * a.k + i] = valid ? key_to_float((uint32_t)(c >> a.idx_bits)) : __builtin_inff();
+    for (uint32_t i = threadIdx.x; i < a.k; i += T) {
+        const uint64_t v = sort_buf[i];
+        const bool valid = i < n_selected;
+        a.idx_out[(uint64_t)s * a.k + i] = valid ? (uint32_t)(v & idx_mask) : 0xFFFFFFFFu;
+        a.energy_out[(uint64_t)s * a.k + i] = valid ? key_to_float((uint32_t)(v >> a.idx_bits)) : __builtin_inff();
     }
-    if (threadIdx.x == 0) count_out[s] = count;
+    if (threadIdx.x == 0) a.count_out[s] = n_selected;
 }
 
-uint32_t next_pow2(uint32_t v)
+// ---------------------------------------------------------------- host side
+
+// Threads per block for a selection of k per block: 1024 (chunks of 16384) when k is large, so that a level
+// still shrinks its input at least fourfold, or when the whole job is too small to fill the chip anyway and
+// fewer levels matter more; 256 (chunks of 4096) otherwise.
+int threads_for(uint64_t seg_len, uint32_t n_seg, uint32_t k)
 {
-    uint32_t p = 1;
-    while (p < v) p <<= 1;
+    if (k > 256) return 1024;
+    const uint64_t blocks = (uint64_t)n_seg * ((seg_len + 4095) / 4096);
+    return blocks < 512 ? 1024 : 256;
+}
+
+struct Plan {
+    int threads;
+    uint64_t blocks0;     // level-0 blocks per segment
+    uint64_t list_a, list_b; // composites per segment in the two list buffers (level 0 writes A)
+};
+
+Plan plan_for(uint64_t seg_len, uint32_t n_seg, uint32_t k)
+{
+    Plan p;
+    p.threads = threads_for(seg_len, n_seg, k);
+    const uint64_t chunk = (uint64_t)p.threads * ITEMS;
+    p.blocks0 = (seg_len + chunk - 1) / chunk;
+    p.list_a = p.blocks0 > 1 ? p.blocks0 * k : 0;
+    const uint64_t blocks1 = (p.list_a + chunk - 1) / chunk;
+    p.list_b = blocks1 > 1 ? blocks1 * k : 0;
     return p;
 }
 
 struct WsLayout {
-    uint64_t state, hist, gather, total;
+    uint64_t lat_parts, lat_thr, list_a, list_b, total;
 };
 
-WsLayout ws_layout(uint32_t n_seg, uint32_t k)
+// k_lists: the largest per-block selection any stage of the call makes (k, or m_latency in RANK mode)
+WsLayout ws_layout(uint64_t seg_len, uint32_t n_seg, uint32_t k, uint32_t m_latency)
 {
+    Plan p = plan_for(seg_len, n_seg, k);
+    if (m_latency && m_latency < seg_len) {
+        const Plan q = plan_for(seg_len, n_seg, m_latency);
+        p.list_a = p.list_a > q.list_a ? p.list_a : q.list_a;
+        p.list_b = p.list_b > q.list_b ? p.list_b : q.list_b;
+    }
     WsLayout w;
-    w.state = 0;
-    w.hist = w.state + (uint64_t)n_seg * sizeof(SegState);
-    w.gather = w.hist + (uint64_t)n_seg * BINS * sizeof(uint32_t);
-    w.total = w.gather + (uint64_t)n_seg * k * sizeof(uint64_t);
+    w.lat_parts = 0;
+    w.lat_thr = w.lat_parts + (uint64_t)n_seg * LATMIN_PARTS * sizeof(uint32_t);
+    w.list_a = w.lat_thr + (((uint64_t)n_seg * sizeof(uint64_t) + 15) & ~15ull);
+    w.list_b = w.list_a + (uint64_t)n_seg * p.list_a * sizeof(uint64_t);
+    w.total = w.list_b + (uint64_t)n_seg * p.list_b * sizeof(uint64_t);
     return w;
 }
 
@@ -386,30 +414,51 @@ bool sizes_ok(uint64_t n, uint32_t n_seg, uint32_t k)
            n_seg <= 65535;
 }
 
-template <int PRED>
-int32_t radix_rounds(const SelectArgs &a, uint32_t n_seg, bool vec, hipStream_t st)
+template <int T, int SRC, int PRED>
+void launch_select(const SelectArgs &a, uint32_t blocks, uint32_t n_seg, hipStream_t st)
 {
-    const uint32_t total_bits = 32 + a.idx_bits;
-    const uint32_t blocks = (uint32_t)((a.seg_len + (uint64_t)BLOCK * a.items - 1) / ((uint64_t)BLOCK * a.items));
-    int first = 1;
-    for (uint32_t consumed = 0; consumed < total_bits; consumed += DIGIT_BITS) {
-        const uint32_t bits = total_bits - consumed < DIGIT_BITS ? total_bits - consumed : DIGIT_BITS;
-        const uint32_t shift = total_bits - consumed - bits;
-        if (vec)
-            hipLaunchKernelGGL((hist_kernel<PRED, true>), dim3(blocks, n_seg), dim3(BLOCK), 0, st, a, shift, bits, first);
-        else
-            hipLaunchKernelGGL((hist_kernel<PRED, false>), dim3(blocks, n_seg), dim3(BLOCK), 0, st, a, shift, bits, first);
-        first = 0;
+    size_t lds = (sizeof(Shared<T>) + 15) & ~(size_t)15;
+    if (blocks == 1 && !a.thr_out) {
+        uint32_t pow2 = 2;
+        while (pow2 < a.k) pow2 <<= 1;
+        lds += (size_t)pow2 * sizeof(uint64_t);
+    }
+    hipLaunchKernelGGL((select_kernel<T, SRC, PRED>), dim3(blocks, n_seg), dim3(T), lds, st, a);
+}
+
+template <int T, int PRED>
+void launch_level0(const SelectArgs &a, uint32_t blocks, uint32_t n_seg, bool vec, hipStream_t st)
+{
+    if (vec) launch_select<T, SRC_SCORES_VEC, PRED>(a, blocks, n_seg, st);
+    else launch_select<T, SRC_SCORES, PRED>(a, blocks, n_seg, st);
+}
+
+// All levels of one selection of a.k per segment: level 0 on the score arrays, further levels on the lists.
+// The last level writes idx/energy/count (or thr_out when that is set).
+template <int PRED>
+int32_t run_tournament(SelectArgs a, uint32_t n_seg, bool vec, uint64_t *list_a, uint64_t *list_b, hipStream_t st)
+{
+    const Plan p = plan_for(a.seg_len, n_seg, a.k);
+    const uint64_t chunk = (uint64_t)p.threads * ITEMS;
+    uint64_t blocks = p.blocks0;
+    if (blocks > 0x7FFFFFFFull) return ECK_EUNSUPPORTED;
+    a.list_out = list_a;
+    if (p.threads == 256) launch_level0<256, PRED>(a, (uint32_t)blocks, n_seg, vec, st);
+    else launch_level0<1024, PRED>(a, (uint32_t)blocks, n_seg, vec, st);
+    uint64_t *in = list_a, *out = list_b;
+    while (blocks > 1) {
+        a.list_in = in;
+        a.list_len = blocks * a.k;
+        a.list_out = out;
+        blocks = (a.list_len + chunk - 1) / chunk;
+        if (p.threads == 256) launch_select<256, SRC_LIST, PRED_PLAIN>(a, (uint32_t)blocks, n_seg, st);
+        else launch_select<1024, SRC_LIST, PRED_PLAIN>(a, (uint32_t)blocks, n_seg, st);
+        uint64_t *t = in;
+        in = out;
+        out = t;
     }
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
-}
-
-template <int PRED>
-void launch_gather(const SelectArgs &a, dim3 grid, bool vec, hipStream_t st)
-{
-    if (vec) hipLaunchKernelGGL((gather_kernel<PRED, true>), grid, dim3(BLOCK), 0, st, a);
-    else hipLaunchKernelGGL((gather_kernel<PRED, false>), grid, dim3(BLOCK), 0, st, a);
 }
 
 } // namespace
@@ -417,13 +466,21 @@ void launch_gather(const SelectArgs &a, dim3 grid, bool vec, hipStream_t st)
 extern "C" uint64_t topk_select_workspace_bytes(uint64_t n, uint32_t n_segments, uint32_t k)
 {
     if (!sizes_ok(n, n_segments, k)) return 0;
-    return ws_layout(n_segments, k).total;
+    return ws_layout(n / n_segments, n_segments, k, 0).total;
 }
 
-extern "C" int32_t topk_select(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
-                               uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
-                               uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
-                               void *stream)
+extern "C" uint64_t topk_select_rank_workspace_bytes(uint64_t n, uint32_t n_segments, uint32_t k, uint32_t m_latency)
+{
+    if (!sizes_ok(n, n_segments, k) || m_latency == 0) return 0;
+    const uint64_t seg_len = n / n_segments;
+    if (m_latency < seg_len && m_latency > ECK_MAX_K) return 0;
+    return ws_layout(seg_len, n_segments, k, m_latency < seg_len ? m_latency : 0).total;
+}
+
+int32_t eck::topk_select_impl(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                              uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
+                              uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
+                              void *stream)
 {
     if (!energy || !idx_out || !energy_out || !count_out || n == 0 || k == 0 || n_segments == 0) return ECK_EINVAL;
     if (mode != ECK_SELECT_THRESHOLD && mode != ECK_SELECT_RANK) return ECK_EINVAL;
@@ -431,65 +488,75 @@ extern "C" int32_t topk_select(const float *energy, const float *latency, const 
     if (latency && mode == ECK_SELECT_RANK && m_latency == 0) return ECK_EINVAL;
     if (n % n_segments || k > n / n_segments || n / n_segments > 0xFFFFFFFEull || n_segments > 65535) return ECK_ESHAPE;
     if (k > ECK_MAX_K) return ECK_EUNSUPPORTED;
-    const WsLayout w = ws_layout(n_segments, k);
+    const uint64_t seg_len = n / n_segments;
+    const bool rank = latency && mode == ECK_SELECT_RANK;
+    // a latency gate that admits the whole segment needs no first stage
+    const bool stage_a = rank && m_latency < seg_len;
+    if (stage_a && m_latency > ECK_MAX_K) return ECK_EUNSUPPORTED;
+    const WsLayout w = ws_layout(seg_len, n_segments, k, stage_a ? m_latency : 0);
     if (!ws || ws_bytes < w.total) return ECK_EWORKSPACE;
     if ((uintptr_t)ws & 15) return ECK_EALIGN;
 
-    SelectArgs a;
+    SelectArgs a = {};
     a.energy = energy;
     a.latency = latency;
     a.legal = legal;
-    a.seg_len = n / n_segments;
+    a.seg_len = seg_len;
     a.idx_bits = 1;
     while (a.idx_bits < 32 && (1ull << a.idx_bits) < a.seg_len) ++a.idx_bits;
     a.slack_factor = alpha - 1.0f;
     a.alpha_inf = __builtin_isinf(alpha) ? 1 : 0;
-    a.state = reinterpret_cast<SegState *>((char *)ws + w.state);
-    a.hist = reinterpret_cast<uint32_t *>((char *)ws + w.hist);
-    a.gather = reinterpret_cast<uint64_t *>((char *)ws + w.gather);
     a.k = k;
-    // Work per block: every block pays for clearing and merging a 4096-bin histogram and for one ticket,
-    // so blocks are made as large as keeps about eight of them per compute unit.
-    {
-        int cus = 256;
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        const uint64_t per_thread = n / ((uint64_t)BLOCK * 8 * (uint64_t)cus);
-        a.items = 4;
-        while (a.items < MAX_ITEMS && a.items < per_thread) a.items *= 2;
-    }
+    a.idx_out = idx_out;
+    a.energy_out = energy_out;
+    a.count_out = count_out;
+    uint32_t *lat_parts = reinterpret_cast<uint32_t *>((char *)ws + w.lat_parts);
+    uint64_t *lat_thr = reinterpret_cast<uint64_t *>((char *)ws + w.lat_thr);
+    uint64_t *list_a = reinterpret_cast<uint64_t *>((char *)ws + w.list_a);
+    uint64_t *list_b = reinterpret_cast<uint64_t *>((char *)ws + w.list_b);
 
     hipStream_t st = as_stream(stream);
-    const uint32_t blocks = (uint32_t)((a.seg_len + (uint64_t)BLOCK * a.items - 1) / ((uint64_t)BLOCK * a.items));
-    const dim3 stream_grid(blocks, n_segments);
-    hipLaunchKernelGGL(init_kernel, dim3(n_segments), dim3(BLOCK), 0, st, a.state, n_segments, a.hist, k);
     // four candidates per load when every group of four is aligned in all three arrays
-    const bool vec = a.seg_len % 4 == 0 && ((uintptr_t)energy & 15) == 0 && (!latency || ((uintptr_t)latency & 15) == 0) &&
+    const bool vec = seg_len % 4 == 0 && ((uintptr_t)energy & 15) == 0 && (!latency || ((uintptr_t)latency & 15) == 0) &&
                      (!legal || ((uintptr_t)legal & 3) == 0);
-    int32_t rc = ECK_OK;
-    if (!latency) {
-        rc = radix_rounds<PRED_PLAIN>(a, n_segments, vec, st);
-        if (rc == ECK_OK) launch_gather<PRED_PLAIN>(a, stream_grid, vec, st);
-    } else if (mode == ECK_SELECT_THRESHOLD) {
-        if (vec) hipLaunchKernelGGL(latmin_kernel<true>, stream_grid, dim3(BLOCK), 0, st, a);
-        else hipLaunchKernelGGL(latmin_kernel<false>, stream_grid, dim3(BLOCK), 0, st, a);
-        rc = radix_rounds<PRED_THRESHOLD>(a, n_segments, vec, st);
-        if (rc == ECK_OK) launch_gather<PRED_THRESHOLD>(a, stream_grid, vec, st);
-    } else {
-        SelectArgs stage_a = a;
-        stage_a.k = m_latency;
-        hipLaunchKernelGGL(restart_kernel, dim3(n_segments), dim3(64), 0, st, a.state, m_latency);
-        rc = radix_rounds<PRED_RANK_STAGE_A>(stage_a, n_segments, vec, st);
-        if (rc == ECK_OK) {
-            hipLaunchKernelGGL(restart_kernel, dim3(n_segments), dim3(64), 0, st, a.state, k);
-            rc = radix_rounds<PRED_RANK_STAGE_B>(a, n_segments, vec, st);
+    if (!latency) return run_tournament<PRED_PLAIN>(a, n_segments, vec, list_a, list_b, st);
+    if (mode == ECK_SELECT_THRESHOLD) {
+        if (!a.alpha_inf) {
+            // L_min first: one pass over the latencies, a slice of the segment per block
+            uint64_t parts = (seg_len + 4095) / 4096;
+            if (parts > LATMIN_PARTS) parts = LATMIN_PARTS;
+            uint64_t slice = (seg_len + parts - 1) / parts;
+            slice = (slice + 1023) & ~1023ull; // whole groups of four per thread
+            parts = (seg_len + slice - 1) / slice;
+            if (vec) hipLaunchKernelGGL(latmin_kernel<true>, dim3((uint32_t)parts, n_segments), dim3(256), 0, st, latency, legal,
+                                        seg_len, slice, lat_parts);
+            else hipLaunchKernelGGL(latmin_kernel<false>, dim3((uint32_t)parts, n_segments), dim3(256), 0, st, latency, legal,
+                                    seg_len, slice, lat_parts);
+            a.lat_parts = lat_parts;
+            a.lat_parts_n = (uint32_t)parts;
         }
-        if (rc == ECK_OK) launch_gather<PRED_RANK_STAGE_B>(a, stream_grid, vec, st);
+        return run_tournament<PRED_THRESHOLD>(a, n_segments, vec, list_a, list_b, st);
     }
+    if (!stage_a) {
+        // every legal candidate with a latency that is a number passes the gate
+        SelectArgs b = a;
+        b.alpha_inf = 1;
+        return run_tournament<PRED_THRESHOLD>(b, n_segments, vec, list_a, list_b, st);
+    }
+    SelectArgs first = a;
+    first.k = m_latency;
+    first.thr_out = lat_thr;
+    const int32_t rc = run_tournament<PRED_RANK_STAGE_A>(first, n_segments, vec, list_a, list_b, st);
     if (rc != ECK_OK) return rc;
-    const uint32_t pow2 = next_pow2(k < 2 ? 2 : k);
-    hipLaunchKernelGGL(sort_kernel, dim3(n_segments), dim3(BLOCK), pow2 * sizeof(uint64_t), st, a, pow2, idx_out,
-                       energy_out, count_out);
-    ECK_HIP_TRY(hipGetLastError());
-    return ECK_OK;
+    a.lat_thr = lat_thr;
+    return run_tournament<PRED_RANK_STAGE_B>(a, n_segments, vec, list_a, list_b, st);
+}
+
+extern "C" int32_t topk_select(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                               uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
+                               uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
+                               void *stream)
+{
+    return topk_select_impl(energy, latency, legal, n, n_segments, k, mode, alpha, m_latency, idx_out, energy_out,
+                            count_out, ws, ws_bytes, stream);
 }

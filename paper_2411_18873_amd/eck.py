@@ -29,7 +29,7 @@ EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_in
            "candidate_enumerate", "candidate_enumerate_batch", "eck_candidates_gather", "features_compute",
            "features_compute_batch", "eck_model_create", "eck_model_destroy",
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
-           "topk_select_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update",
+           "topk_select_workspace_bytes", "topk_select_rank_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update",
            "eck_trees_create", "eck_trees_destroy", "eck_trees_count", "eck_trees_set", "eck_trees_get",
            "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step", "eck_k_count",
            "eck_candidates_dedup", "eck_candidates_dedup_workspace_bytes"]
@@ -100,6 +100,8 @@ def lib():
         L.treemodel_update.argtypes = [vp, vp, i32, u64, vp, u64, i32, f32, f32, vp, vp, vp, u64, vp]
         L.topk_select_workspace_bytes.argtypes = [u64, u32, u32]
         L.topk_select_workspace_bytes.restype = u64
+        L.topk_select_rank_workspace_bytes.argtypes = [u64, u32, u32, u32]
+        L.topk_select_rank_workspace_bytes.restype = u64
         L.topk_select.argtypes = [vp, vp, vp, u64, u32, u32, i32, f32, u32, vp, vp, vp, vp, u64, vp]
         L.costmodel_update_workspace_bytes.argtypes = [vp, u64, i32]
         L.costmodel_update_workspace_bytes.restype = u64
@@ -107,6 +109,8 @@ def lib():
         for name in EXPORTS:
             fn = getattr(L, name)
             if name not in ("eck_space_destroy", "eck_model_destroy", "topk_select_workspace_bytes",
+                            "topk_select_rank_workspace_bytes", "eck_trees_destroy",
+                            "eck_candidates_dedup_workspace_bytes", "treemodel_update_workspace_bytes",
                             "costmodel_update_workspace_bytes"):
                 fn.restype = i32
         _lib = L
@@ -349,7 +353,10 @@ def costmodel_score(model, feat, n, score_out):
                                                     _ptr(score_out), None, 0, _stream()))
 
 
-def topk_select_workspace_bytes(n, n_segments, k):
+def topk_select_workspace_bytes(n, n_segments, k, m_latency=0):
+    """m_latency > 0: the workspace of a RANK-mode call with that latency gate"""
+    if m_latency:
+        return int(lib().topk_select_rank_workspace_bytes(n, n_segments, k, m_latency))
     return int(lib().topk_select_workspace_bytes(n, n_segments, k))
 
 

@@ -50,7 +50,8 @@ class EnergySearch:
         self.idx = torch.zeros((1, self.M), dtype=torch.int32, device=dev)
         self.e_sel = torch.zeros((1, self.M), dtype=torch.float32, device=dev)
         self.count = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.ws_topk = torch.empty(eck.topk_select_workspace_bytes(N, 1, self.M), dtype=torch.uint8, device=dev)
+        self.ws_topk = torch.empty(eck.topk_select_workspace_bytes(N, 1, self.M, m_latency=self.M), dtype=torch.uint8,
+                                   device=dev)
         self.ws_dedup = torch.empty(eck.candidates_dedup_workspace_bytes(N), dtype=torch.uint8, device=dev) if dedup else None
         # everything measured so far: genes and features side by side, energies, in order of measurement
         self.cap = self.M * (max_rounds + 2)
@@ -71,7 +72,7 @@ class EnergySearch:
         self.par_val = torch.zeros((1, self.P), dtype=torch.float32, device=dev)
         self.par_count = torch.zeros(1, dtype=torch.int32, device=dev)
         self.new_pred = torch.zeros(pad, dtype=torch.float32, device=dev)
-        self.ws_par = torch.empty(max(eck.topk_select_workspace_bytes(N, 1, self.P),
+        self.ws_par = torch.empty(max(eck.topk_select_workspace_bytes(N, 1, self.P, m_latency=self.M),
                                       eck.topk_select_workspace_bytes(self.M, 1, min(self.P, self.M))),
                                   dtype=torch.uint8, device=dev)
         # host-side record of the measured kernels (a few hundred rows)

@@ -67,7 +67,9 @@ def topk_dev(e, lat, lg, n_segments, k, mode=eck.SELECT_THRESHOLD, alpha=1.1, m_
     idx = torch.zeros((n_segments, k), dtype=torch.int32, device="cuda")
     eo = torch.zeros((n_segments, k), dtype=torch.float32, device="cuda")
     cnt = torch.zeros((n_segments,), dtype=torch.int32, device="cuda")
-    ws = torch.empty(eck.topk_select_workspace_bytes(e.numel(), n_segments, k), dtype=torch.uint8, device="cuda")
+    rank_gate = m_latency if (mode == eck.SELECT_RANK and lat is not None) else 0
+    ws = torch.empty(eck.topk_select_workspace_bytes(e.numel(), n_segments, k, m_latency=rank_gate), dtype=torch.uint8,
+                     device="cuda")
     eck.topk_select(e, lat, lg, n_segments, k, idx, eo, cnt, ws, mode=mode, alpha=alpha, m_latency=m_latency)
     torch.cuda.synchronize()
     return idx.cpu().numpy().view(np.uint32), eo.cpu().numpy(), cnt.cpu().numpy().view(np.uint32)

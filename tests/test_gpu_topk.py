@@ -128,3 +128,45 @@ def test_scalar_and_vector_streaming_paths_agree_with_the_oracle(G):
     _same(G.topk_dev(pad_f(e2), pad_f(l2), pad_b, 4, 77, alpha=1.1), want2)
     # and the aligned (vector) path on the same data
     _same(G.topk_gpu(e2, l2, g2, 4, 77, alpha=1.1), want2)
+
+
+@pytest.mark.parametrize("n,S,k", [(1 << 22, 1, 4096), (1 << 22, 1, 300), (1 << 22, 1, 1), (3 * ((1 << 20) + 4), 3, 257),
+                                   (1 << 21, 512, 16), (40000, 1, 4096)])
+def test_selections_that_take_several_levels(G, n, S, k):
+    """A block selects among 4096 (k <= 256 on a full chip) or 16384 candidates; longer segments go through
+    further levels over the lists of the level before.  Sizes here take one to four levels, with k from 1 to the
+    largest the library accepts, ties included so that index digits decide."""
+    e = synth.gaussian_scores(n, 31, ties=0.4, quantum=0.02)
+    lat = synth.gaussian_scores(n, 32) * 0.3 + 2.0
+    legal = synth.legal_mask(n, 33, 0.7)
+    _same(G.topk_gpu(e, None, legal, S, k), oracle.topk(e, None, legal, S, k))
+    _same(G.topk_gpu(e, lat, legal, S, k, alpha=1.3), oracle.topk(e, lat, legal, S, k, alpha=1.3))
+    m = min(4096, max(k, 1000))
+    _same(G.topk_gpu(e, lat, legal, S, k, mode=eck.SELECT_RANK, m_latency=m),
+          oracle.topk(e, lat, legal, S, k, mode=oracle.SEL_RANK, m_latency=m))
+
+
+def test_rank_gate_limits_and_workspace(G):
+    import ctypes as C
+    import torch
+    L = eck.lib()
+    n = 1 << 16
+    # a gate wider than the library's largest selection is refused unless it admits the whole segment anyway
+    assert L.topk_select_rank_workspace_bytes(n, 1, 16, 5000) == 0
+    assert L.topk_select_rank_workspace_bytes(n, 1, 16, n) > 0
+    assert L.topk_select_rank_workspace_bytes(n, 1, 16, 0) == 0
+    need = eck.topk_select_workspace_bytes(n, 1, 16, m_latency=4096)
+    assert need >= eck.topk_select_workspace_bytes(n, 1, 16)
+    e = torch.zeros(n, dtype=torch.float32, device="cuda")
+    idx = torch.zeros(16, dtype=torch.int32, device="cuda")
+    eo = torch.zeros(16, dtype=torch.float32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    p = lambda t: C.c_void_p(t.data_ptr())
+    call = lambda m, ws_bytes: L.topk_select(p(e), p(e), None, n, 1, 16, eck.SELECT_RANK, 1.1, m, p(idx), p(eo), p(cnt),
+                                             p(ws), ws_bytes, None)
+    assert call(5000, need) == eck.EUNSUPPORTED
+    assert call(4096, eck.topk_select_workspace_bytes(n, 1, 16) - 8) == eck.EWORKSPACE
+    assert call(4096, need) == eck.OK and call(n, need) == eck.OK
+    torch.cuda.synchronize()
+    assert cnt.item() == 16 and idx.cpu().numpy().tolist() == list(range(16))
