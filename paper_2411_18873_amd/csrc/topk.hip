@@ -10,7 +10,9 @@
 // it, until one block per segment holds the segment's k smallest, sorts them in LDS and writes the
 // result.  The k smallest of a segment are among the k smallest of each chunk, so the result is exact;
 // no global atomics, no flags between blocks: blocks only meet at kernel boundaries, and the output does
-// not depend on execution order.
+// not depend on execution order.  Inside a block: a cheap upper bound on its k-th smallest key first (from
+// the least key of every thread), then the few candidates under the bound are ranked against each other,
+// which selects and orders them at once; a radix select on LDS histograms takes over when many remain.
 #include "eck_internal.h"
 
 using namespace eck;
@@ -19,7 +21,10 @@ namespace {
 
 constexpr int DIGIT_BITS = 11;
 constexpr int BINS = 1 << DIGIT_BITS;
-constexpr int ITEMS = 16;                // composites a thread holds
+#ifndef ECK_TOPK_ITEMS
+#define ECK_TOPK_ITEMS 16
+#endif
+constexpr int ITEMS = ECK_TOPK_ITEMS;                // composites a thread holds
 constexpr uint64_t NONE = ~0ull;         // no candidate (a NaN score never makes a composite, so no composite is all ones)
 constexpr uint32_t LATMIN_PARTS = 256;   // most per-block latency minima per segment
 
@@ -103,9 +108,12 @@ __global__ __launch_bounds__(256) void latmin_kernel(const float *__restrict__ l
 
 // ---------------------------------------------------------------- one level of the tournament
 
-// composite of a legal candidate with scores (e, l) under predicate PRED, or NONE if infeasible
+constexpr uint32_t NO_KEY = 0xFFFFFFFFu; // the order key of no number (only a NaN pattern maps to it): "not a candidate"
+constexpr uint32_t SMALL = 512;          // a selection among at most this many composites is ranked directly
+
+// order key of a legal candidate's value under predicate PRED, or NO_KEY if infeasible
 template <int PRED>
-__device__ __forceinline__ uint64_t composite_of(const SelectArgs &a, uint32_t i, float e, float l, float tau,
+__device__ __forceinline__ uint32_t feasible_key(const SelectArgs &a, uint32_t i, float e, float l, float tau,
                                                  uint64_t lat_thr)
 {
     float value;
@@ -114,24 +122,66 @@ __device__ __forceinline__ uint64_t composite_of(const SelectArgs &a, uint32_t i
     } else {
         value = e;
         if (PRED == PRED_THRESHOLD) {
-            if (!(l <= tau)) return NONE;
+            if (!(l <= tau)) return NO_KEY;
         } else if (PRED == PRED_RANK_STAGE_B) {
-            if (l != l) return NONE;
-            if ((((uint64_t)order_key(l) << a.idx_bits) | i) > lat_thr) return NONE;
+            if (l != l) return NO_KEY;
+            if ((((uint64_t)order_key(l) << a.idx_bits) | i) > lat_thr) return NO_KEY;
         }
     }
-    if (value != value) return NONE;
-    return ((uint64_t)order_key(value) << a.idx_bits) | i;
+    if (value != value) return NO_KEY;
+    return order_key(value);
 }
 
-// LDS of a block: the digit histogram, a handful of words, and (last level) the sort buffer behind them
+// LDS of a block: the digit histogram of the radix select, or the arrays of the direct ranking (never both at
+// once), a handful of words, and (last level) the sort buffer behind them
 template <int T>
 struct Shared {
-    uint32_t hist[BINS];
+    union {
+        uint32_t hist[BINS];
+        struct {
+            uint64_t pool[SMALL];   // the composites left after the bound ...
+            uint64_t ranked[SMALL]; // ... the selection in ascending order ...
+            uint32_t rank[SMALL];   // ... and the number of smaller composites of each pool entry
+        } small;
+    };
     uint32_t wave_sum[T / 64];
+    uint64_t wave_bound[T / 64];
     uint32_t found_digit, found_below, found_count, cursor;
     uint32_t lat_min;
 };
+
+// one compare-exchange step of a bitonic network over the 64 lanes of a wavefront
+template <class V>
+__device__ __forceinline__ V lane_exchange(V v, uint32_t stride);
+template <>
+__device__ __forceinline__ uint32_t lane_exchange<uint32_t>(uint32_t v, uint32_t stride)
+{
+    return (uint32_t)__shfl_xor((int)v, (int)stride);
+}
+template <>
+__device__ __forceinline__ uint64_t lane_exchange<uint64_t>(uint64_t v, uint32_t stride)
+{
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, (int)stride);
+    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), (int)stride);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// the 64 values of a wavefront in ascending order over the lanes (bitonic sorting network)
+template <class V>
+__device__ __forceinline__ V wave_sort(V v)
+{
+    const uint32_t lane = threadIdx.x & 63;
+#pragma unroll
+    for (uint32_t size = 2; size <= 64; size <<= 1)
+#pragma unroll
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            const V other = lane_exchange<V>(v, stride);
+            const bool keep_min = ((lane & stride) == 0) == ((lane & size) == 0);
+            const V lo = v < other ? v : other, hi = v < other ? other : v;
+            v = keep_min ? lo : hi;
+        }
+    return v;
+}
 
 template <int T>
 __device__ __forceinline__ uint32_t block_sum(uint32_t v, Shared<T> &sh)
@@ -147,28 +197,91 @@ __device__ __forceinline__ uint32_t block_sum(uint32_t v, Shared<T> &sh)
     return total;
 }
 
-// The composite that exactly min(k, #valid) of the block's composites do not exceed.  Radix select from the
-// top digit down: histogram of the digit over the composites that match the digits fixed so far, prefix sums
-// over the bins, the bin holding the wanted rank fixes the next digit.  Ends as soon as a whole bin is wanted.
-template <int T>
-__device__ uint64_t block_threshold(const uint64_t (&c)[ITEMS], uint32_t k, uint32_t total_bits, Shared<T> &sh,
-                                    uint32_t *n_selected)
+// A bound on the block's k-th smallest value, from the least value of every thread (V = order key or composite,
+// `none` = the largest value of V, which stands for "nothing").  Each of the W wavefronts contributes
+// need = ceil(k / W) values that are at most its part of the bound, k or more in all, so the k-th smallest of the
+// block does not exceed the largest part.  A wavefront's part: the need-th smallest of its 64 sorted values (for
+// need <= 2 the larger of the minima of `need` halves of the wavefront does: six exchange steps instead of 21).  `none` when some wavefront has too few values (then nothing may be dropped) or k is too
+// large for this.
+template <int T, class V>
+__device__ __forceinline__ V block_bound(V least, uint32_t k, V none, Shared<T> &sh)
 {
-    uint32_t mine = 0;
+    constexpr uint32_t W = T / 64;
+    const uint32_t need = (k + W - 1) / W;
+    if (need > 64) return none;
+    V part;
+    if (need <= 2) {
+        const uint32_t groups = need, lanes = 64 / groups;
+        part = least;
 #pragma unroll
-    for (int j = 0; j < ITEMS; ++j) mine += c[j] != NONE;
-    const uint32_t total = block_sum<T>(mine, sh);
-    if (total <= k) {
-        *n_selected = total;
-        return NONE - 1; // every composite is below NONE
+        for (uint32_t stride = 1; stride < 64; stride <<= 1) {
+            const V other = lane_exchange<V>(part, stride);
+            const V lo = part < other ? part : other, hi = part < other ? other : part;
+            part = stride < lanes ? lo : hi;
+        }
+    } else {
+        const V sorted = wave_sort<V>(least);
+        uint64_t picked = (uint32_t)__shfl((int)(uint32_t)sorted, (int)(need - 1));
+        if (sizeof(V) == 8)
+            picked |= (uint64_t)(uint32_t)__shfl((int)(uint32_t)((uint64_t)sorted >> 32), (int)(need - 1)) << 32;
+        part = (V)picked;
     }
-    *n_selected = k;
+    if ((threadIdx.x & 63) == 0) sh.wave_bound[threadIdx.x >> 6] = part;
+    __syncthreads();
+    uint64_t bound = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < W; ++w) bound = sh.wave_bound[w] > bound ? sh.wave_bound[w] : bound;
+    return (V)bound; // one wavefront without enough values makes `none` the bound
+}
+
+// Ranks the `kept` (<= SMALL) composites of sh.small.pool: the rank of a composite is the number of smaller ones,
+// which is selection and order at once (composites are distinct, so the ranks are a permutation).  With fewer
+// entries than threads the counting of one entry is shared by as many threads as the block can spare.  On return
+// sh.small.ranked[0 .. min(kept, k)) is the selection in ascending order.  sh.small.rank must be zero on entry.
+template <int T>
+__device__ __forceinline__ void rank_pool(uint32_t kept, uint32_t k, Shared<T> &sh)
+{
+    if (kept > T) {
+        for (uint32_t entry = threadIdx.x; entry < kept; entry += T) {
+            const uint64_t mine = sh.small.pool[entry];
+            uint32_t smaller = 0;
+            for (uint32_t j = 0; j < kept; ++j) smaller += sh.small.pool[j] < mine;
+            sh.small.rank[entry] = smaller;
+        }
+    } else if (kept) {
+        const uint32_t sharers = T / kept;                      // threads per entry, >= 1
+        const uint32_t span = (kept + sharers - 1) / sharers;   // pool entries each of them compares with
+        const uint32_t entry = threadIdx.x % kept, part = threadIdx.x / kept;
+        if (part < sharers) {
+            const uint64_t mine = sh.small.pool[entry];
+            const uint32_t lo = part * span, hi = lo + span < kept ? lo + span : kept;
+            uint32_t smaller = 0;
+            for (uint32_t j = lo; j < hi; ++j) smaller += sh.small.pool[j] < mine;
+            if (smaller) atomicAdd(&sh.small.rank[entry], smaller);
+        }
+    }
+    __syncthreads();
+    for (uint32_t entry = threadIdx.x; entry < kept; entry += T) {
+        const uint32_t r = sh.small.rank[entry];
+        if (r < k) sh.small.ranked[r] = sh.small.pool[entry];
+    }
+    __syncthreads();
+}
+
+// Radix select from the top digit down over the composites a thread holds (NONE entries do not count): the
+// composite that exactly k of them do not exceed (there are at least k).  Histogram of the digit over the
+// composites that match the digits fixed so far, prefix sums over the bins, the bin holding the wanted rank
+// fixes the next digit; ends as soon as a whole bin is wanted.
+template <int T>
+__device__ uint64_t radix_threshold(const uint64_t (&c)[ITEMS], uint32_t k, uint32_t total_bits, Shared<T> &sh)
+{
     constexpr int PER = BINS / T; // consecutive bins per thread in the scan
     uint64_t prefix = 0;
     uint32_t remaining = k, top = total_bits;
     for (;;) {
         const uint32_t bits = top < (uint32_t)DIGIT_BITS ? top : (uint32_t)DIGIT_BITS;
         const uint32_t shift = top - bits, mask = (1u << bits) - 1;
+        __syncthreads(); // the histogram's space and found_* may still be read from the pass (or the use) before
 #pragma unroll
         for (int j = 0; j < PER; ++j) sh.hist[threadIdx.x * PER + j] = 0;
         __syncthreads();
@@ -214,14 +327,272 @@ __device__ uint64_t block_threshold(const uint64_t (&c)[ITEMS], uint32_t k, uint
         remaining -= under;
         if (shift == 0 || remaining == count) return prefix | ((shift ? (1ull << shift) : 1ull) - 1);
         top = shift;
-        __syncthreads(); // found_* and the histogram are rewritten in the next pass
     }
 }
 
-// One block = T threads x ITEMS composites.  Source: a chunk of T * ITEMS candidates of segment blockIdx.y
-// (four consecutive candidates per load where VEC allows it), or the same number of composites of the list
-// the level before wrote.  Not the last level (gridDim.x > 1): the block's selection goes to its k slots of
-// list_out, the unused slots are set to NONE.  Last level: sort, unpack, write the result.
+// The block's min(k, #candidates) smallest composites, c[j] = NONE standing for "no candidate" (entries above the
+// bound are set to NONE on the way).  Returns their number n.  Either *ranked is set and sh.small.ranked[0 .. n)
+// holds them in ascending order, or it is clear and they are the composites c[j] <= *thr.
+// `kept`: how many entries of c are candidates within the bound; when at most SMALL, they are already in
+// sh.small.pool (the caller compacted them while it built c) and get ranked directly; more go through the radix
+// select.  `bounded`: a bound was applied, which only happens when at least k candidates lie within it.
+template <int T>
+__device__ uint32_t select_kept(const uint64_t (&c)[ITEMS], uint32_t kept, bool bounded, uint32_t k, uint32_t total_bits,
+                                Shared<T> &sh, bool *ranked, uint64_t *thr)
+{
+    const uint32_t n = kept < k ? kept : k;
+    *thr = NONE - 1; // every composite is below NONE
+    *ranked = false;
+    if (kept <= SMALL) {
+        rank_pool<T>(kept, k, sh);
+        *ranked = true;
+        return n;
+    }
+    if (!bounded && kept <= k) return n; // all of them, in no order
+    *thr = radix_threshold<T>(c, k, total_bits, sh);
+    return n;
+}
+
+// The block's share of a list of composites (the selections of the level before): held in c, bounded, the
+// survivors compacted into the pool.
+template <int T>
+__device__ __forceinline__ void gather_list(const uint64_t *in, uint64_t list_len, uint64_t start, uint32_t k,
+                                            Shared<T> &sh, uint64_t (&c)[ITEMS], uint32_t *kept, bool *bounded)
+{
+    // a thread takes consecutive entries, the block's share spread evenly over its threads: the lists of blocks
+    // that ranked their selection are ascending, so the least entries of the threads are spread over the lists'
+    // quantiles and the bound comes out tight
+    const uint64_t share = list_len - start < (uint64_t)(T * ITEMS) ? list_len - start : (uint64_t)(T * ITEMS);
+    const uint32_t per_thread = (uint32_t)((share + T - 1) / T); // <= ITEMS
+    uint64_t least = NONE;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        const uint64_t i = (uint64_t)threadIdx.x * per_thread + j;
+        uint64_t v = NONE;
+        if ((uint32_t)j < per_thread && i < share) v = in[start + i];
+        c[j] = v;
+        least = v < least ? v : least;
+    }
+    const uint64_t bound = block_bound<T, uint64_t>(least, k, NONE, sh);
+    *bounded = bound != NONE;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        if (c[j] > bound) c[j] = NONE; // bound == NONE keeps everything
+        if (c[j] != NONE) {
+            const uint32_t slot = atomicAdd(&sh.cursor, 1u);
+            if (slot < SMALL) sh.small.pool[slot] = c[j];
+        }
+    }
+    __syncthreads();
+    *kept = sh.cursor;
+}
+
+// The block's chunk of T * ITEMS candidates of segment s (four consecutive candidates per load where VEC allows
+// it): order keys of the feasible ones, bounded, the survivors turned into composites (held in c and compacted into
+// the pool).
+template <int T, int SRC, int PRED>
+__device__ __forceinline__ void gather_scores(const SelectArgs &a, uint32_t s, Shared<T> &sh, uint64_t (&c)[ITEMS],
+                                              uint32_t *kept, bool *bounded)
+{
+    constexpr bool NEED_E = PRED != PRED_RANK_STAGE_A, NEED_L = PRED != PRED_PLAIN;
+    const uint64_t seg_base = (uint64_t)s * a.seg_len;
+    const uint64_t start = (uint64_t)blockIdx.x * (T * ITEMS);
+    // VEC: every load of the thread is issued here, before anything waits; none depends on another (the flags
+    // decide afterwards).  Groups past the end of the segment re-read its first group and are discarded.
+    // Exception: under a finite latency gate few candidates are feasible as a rule, so the energies are fetched
+    // afterwards and only for groups of four that hold a feasible candidate -- a second round trip for those, but
+    // close to half the bytes of the pass stay unread.
+    constexpr bool ENERGY_LATER = PRED == PRED_THRESHOLD && SRC == SRC_SCORES_VEC;
+    const bool energy_later = ENERGY_LATER && !a.alpha_inf;
+    uint32_t flags[ITEMS / 4];
+    float4 e[ITEMS / 4], l[ITEMS / 4];
+    if (SRC == SRC_SCORES_VEC) {
+#pragma unroll
+        for (int j = 0; j < ITEMS / 4; ++j) {
+            const uint64_t i = start + ((uint64_t)j * T + threadIdx.x) * 4;
+            const uint64_t g = seg_base + (i < a.seg_len ? i : 0); // seg_len is a multiple of 4 on this path
+            flags[j] = a.legal ? *reinterpret_cast<const uint32_t *>(a.legal + g) : 0x01010101u;
+            if (NEED_L) l[j] = *reinterpret_cast<const float4 *>(a.latency + g);
+            if (NEED_E && !energy_later) e[j] = *reinterpret_cast<const float4 *>(a.energy + g);
+        }
+    }
+    // the gate, while the loads are under way
+    float tau = 0.0f;
+    uint64_t lat_thr = 0;
+    if (PRED == PRED_THRESHOLD) {
+        // tau = L_min + (alpha - 1) |L_min|, product and sum rounded separately; L_min from the per-block minima
+        if (a.alpha_inf) {
+            tau = __builtin_inff();
+        } else {
+            uint32_t best = 0xFFFFFFFFu;
+            for (uint32_t p = threadIdx.x; p < a.lat_parts_n; p += T) best = min(best, a.lat_parts[(uint64_t)s * a.lat_parts_n + p]);
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) best = min(best, (uint32_t)__shfl_xor((int)best, off));
+            if (threadIdx.x == 0) sh.lat_min = 0xFFFFFFFFu;
+            __syncthreads();
+            if ((threadIdx.x & 63) == 0) atomicMin(&sh.lat_min, best);
+            __syncthreads();
+            best = sh.lat_min;
+            if (best == 0xFFFFFFFFu) {
+                tau = __builtin_inff(); // nothing legal: nothing will be feasible either
+            } else {
+                const float lmin = key_to_float(best);
+                tau = __fadd_rn(lmin, __fmul_rn(a.slack_factor, fabsf(lmin)));
+            }
+        }
+    } else if (PRED == PRED_RANK_STAGE_B) {
+        lat_thr = a.lat_thr[s];
+    }
+    // order keys of the feasible candidates (32 bits each: the index is implied by the position), their least
+    // per thread, the bound from those
+    uint32_t key[ITEMS], least = NO_KEY;
+    auto index_of = [&](int j) -> uint32_t {
+        if (SRC == SRC_SCORES_VEC) return (uint32_t)(start + ((uint64_t)(j / 4) * T + threadIdx.x) * 4 + (j % 4));
+        return (uint32_t)(start + (uint64_t)j * T + threadIdx.x);
+    };
+    if (SRC == SRC_SCORES_VEC) {
+        if (ENERGY_LATER && energy_later) {
+            // keep the flags of the feasible candidates only, then fetch the energies of the groups that have any
+#pragma unroll
+            for (int j = 0; j < ITEMS / 4; ++j) {
+                const float lv[4] = {l[j].x, l[j].y, l[j].z, l[j].w};
+                uint32_t f = flags[j];
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (!(lv[t] <= tau)) f &= ~(0xFFu << (8 * t));
+                flags[j] = f;
+            }
+#pragma unroll
+            for (int j = 0; j < ITEMS / 4; ++j) {
+                const uint64_t i = start + ((uint64_t)j * T + threadIdx.x) * 4;
+                e[j] = float4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (flags[j] && i < a.seg_len) e[j] = *reinterpret_cast<const float4 *>(a.energy + seg_base + i);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < ITEMS / 4; ++j) {
+            const uint64_t i = start + ((uint64_t)j * T + threadIdx.x) * 4;
+            const uint32_t f = i < a.seg_len ? flags[j] : 0u;
+            const float ev[4] = {NEED_E ? e[j].x : 0.0f, NEED_E ? e[j].y : 0.0f, NEED_E ? e[j].z : 0.0f, NEED_E ? e[j].w : 0.0f};
+            const float lv[4] = {NEED_L ? l[j].x : 0.0f, NEED_L ? l[j].y : 0.0f, NEED_L ? l[j].z : 0.0f, NEED_L ? l[j].w : 0.0f};
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                key[4 * j + t] = ((f >> (8 * t)) & 0xFFu) ? feasible_key<PRED>(a, (uint32_t)i + t, ev[t], lv[t], tau, lat_thr)
+                                                          : NO_KEY;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const uint64_t i = start + (uint64_t)j * T + threadIdx.x;
+            uint32_t v = NO_KEY;
+            if (i < a.seg_len) {
+                const uint64_t g = seg_base + i;
+                if (!a.legal || a.legal[g])
+                    v = feasible_key<PRED>(a, (uint32_t)i, NEED_E ? a.energy[g] : 0.0f, NEED_L ? a.latency[g] : 0.0f, tau,
+                                           lat_thr);
+            }
+            key[j] = v;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) least = min(least, key[j]);
+    const uint32_t bound = block_bound<T, uint32_t>(least, a.k, NO_KEY, sh);
+    *bounded = bound != NO_KEY;
+    __syncthreads();
+    // the candidates within the bound (all of one key, ties included) become composites
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) {
+        c[j] = NONE;
+        if (key[j] != NO_KEY && key[j] <= bound) {
+            c[j] = ((uint64_t)key[j] << a.idx_bits) | index_of(j);
+            const uint32_t slot = atomicAdd(&sh.cursor, 1u);
+            if (slot < SMALL) sh.small.pool[slot] = c[j];
+        }
+    }
+    __syncthreads();
+    *kept = sh.cursor;
+}
+
+// Selection among the gathered composites, then either the block's k slots of list_out (unused slots NONE) or,
+// last level, the result.
+template <int T>
+__device__ __forceinline__ void select_and_emit(const SelectArgs &a, uint32_t s, const uint64_t (&c)[ITEMS], uint32_t kept,
+                                                bool bounded, bool last_level, Shared<T> &sh, uint64_t *sort_buf)
+{
+    bool ranked;
+    uint64_t thr;
+    const uint32_t n_selected = select_kept<T>(c, kept, bounded, a.k, 32 + a.idx_bits, sh, &ranked, &thr);
+    if (last_level && a.thr_out) {
+        // RANK stage A: feasible = latency composite <= the k-th smallest (everything legal when fewer than k exist)
+        if (threadIdx.x == 0) {
+            uint64_t gate = NONE;
+            if (n_selected == a.k) gate = ranked ? sh.small.ranked[a.k - 1] : thr;
+            a.thr_out[s] = gate;
+        }
+        return;
+    }
+    if (!last_level) {
+        uint64_t *out = a.list_out + ((uint64_t)s * gridDim.x + blockIdx.x) * a.k;
+        if (ranked) {
+            for (uint32_t i = threadIdx.x; i < n_selected; i += T) out[i] = sh.small.ranked[i];
+        } else {
+            __syncthreads(); // the histogram's space is done with
+            if (threadIdx.x == 0) sh.cursor = 0;
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j)
+                if (c[j] <= thr) out[atomicAdd(&sh.cursor, 1u)] = c[j]; // NONE > thr; exactly n_selected qualify
+        }
+        for (uint32_t i = n_selected + threadIdx.x; i < a.k; i += T) out[i] = NONE;
+        return;
+    }
+    // last level: the selection in ascending order, then unpack
+    const uint64_t *sorted = sh.small.ranked;
+    if (!ranked) {
+        // bitonic sort of the selection (padded to a power of two with NONE)
+        uint32_t pow2 = 2;
+        while (pow2 < a.k) pow2 <<= 1;
+        for (uint32_t i = threadIdx.x; i < pow2; i += T) sort_buf[i] = NONE;
+        if (threadIdx.x == 0) sh.cursor = 0;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j)
+            if (c[j] <= thr) sort_buf[atomicAdd(&sh.cursor, 1u)] = c[j];
+        __syncthreads();
+        for (uint32_t size = 2; size <= pow2; size <<= 1)
+            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                for (uint32_t t = threadIdx.x; t < pow2 / 2; t += T) {
+                    const uint32_t lo = 2 * t - (t & (stride - 1)); // index with the `stride` bit clear
+                    const uint32_t hi = lo + stride;
+                    const bool ascending = (lo & size) == 0;
+                    const uint64_t x = sort_buf[lo], y = sort_buf[hi];
+                    if ((x > y) == ascending) {
+                        sort_buf[lo] = y;
+                        sort_buf[hi] = x;
+                    }
+                }
+                __syncthreads();
+            }
+        sorted = sort_buf;
+    }
+    const uint64_t idx_mask = (1ull << a.idx_bits) - 1;
+    for (uint32_t i = threadIdx.x; i < a.k; i += T) {
+        const bool valid = i < n_selected;
+        const uint64_t v = valid ? sorted[i] : 0;
+        a.idx_out[(uint64_t)s * a.k + i] = valid ? (uint32_t)(v & idx_mask) : 0xFFFFFFFFu;
+        a.energy_out[(uint64_t)s * a.k + i] = valid ? key_to_float((uint32_t)(v >> a.idx_bits)) : __builtin_inff();
+    }
+    if (threadIdx.x == 0) a.count_out[s] = n_selected;
+}
+
+// One block = T threads x ITEMS candidates of segment blockIdx.y: a chunk of the score arrays, or the same number
+// of composites of the list the level before wrote.  With one block per segment (gridDim.x == 1) this is the
+// last level and writes the result; otherwise the block's selection goes to its k slots of list_out and a further
+// launch works on the lists.  (Letting the block that finishes a segment last merge the lists inside the same
+// launch was tried: on this chip blocks of one launch sit on eight dies with separate L2 caches, so lists and
+// tickets have to be written through to memory -- device-scope stores and atomics, or a release fence, which
+// writes the whole L2 back -- and that costs far more than the second launch: 73 us and 400 us against 32.)
 template <int T, int SRC, int PRED>
 __global__ __launch_bounds__(T) void select_kernel(SelectArgs a)
 {
@@ -230,130 +601,15 @@ __global__ __launch_bounds__(T) void select_kernel(SelectArgs a)
     uint64_t *sort_buf = reinterpret_cast<uint64_t *>(lds_raw + ((sizeof(Shared<T>) + 15) & ~(size_t)15));
     const uint32_t s = blockIdx.y;
     uint64_t c[ITEMS];
-    if (SRC == SRC_LIST) {
-        const uint64_t *in = a.list_in + (uint64_t)s * a.list_len;
-        const uint64_t start = (uint64_t)blockIdx.x * (T * ITEMS);
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const uint64_t i = start + (uint64_t)j * T + threadIdx.x;
-            c[j] = i < a.list_len ? in[i] : NONE;
-        }
-    } else {
-        float tau = 0.0f;
-        uint64_t lat_thr = 0;
-        if (PRED == PRED_THRESHOLD) {
-            // tau = L_min + (alpha - 1) |L_min|, product and sum rounded separately; L_min from the per-block minima
-            if (a.alpha_inf) {
-                tau = __builtin_inff();
-            } else {
-                uint32_t best = 0xFFFFFFFFu;
-                for (uint32_t p = threadIdx.x; p < a.lat_parts_n; p += T) best = min(best, a.lat_parts[(uint64_t)s * a.lat_parts_n + p]);
-#pragma unroll
-                for (int off = 32; off > 0; off >>= 1) best = min(best, (uint32_t)__shfl_xor((int)best, off));
-                if (threadIdx.x == 0) sh.lat_min = 0xFFFFFFFFu;
-                __syncthreads();
-                if ((threadIdx.x & 63) == 0) atomicMin(&sh.lat_min, best);
-                __syncthreads();
-                best = sh.lat_min;
-                if (best == 0xFFFFFFFFu) {
-                    tau = __builtin_inff(); // nothing legal: nothing will be feasible either
-                } else {
-                    const float lmin = key_to_float(best);
-                    tau = __fadd_rn(lmin, __fmul_rn(a.slack_factor, fabsf(lmin)));
-                }
-            }
-        } else if (PRED == PRED_RANK_STAGE_B) {
-            lat_thr = a.lat_thr[s];
-        }
-        constexpr bool NEED_E = PRED != PRED_RANK_STAGE_A, NEED_L = PRED != PRED_PLAIN;
-        const uint64_t seg_base = (uint64_t)s * a.seg_len;
-        const uint64_t start = (uint64_t)blockIdx.x * (T * ITEMS);
-        if (SRC == SRC_SCORES_VEC) {
-#pragma unroll
-            for (int j = 0; j < ITEMS / 4; ++j) {
-                const uint64_t i = start + ((uint64_t)j * T + threadIdx.x) * 4;
-                uint32_t flags = 0;
-                float4 e = {0, 0, 0, 0}, l = {0, 0, 0, 0};
-                if (i < a.seg_len) { // seg_len is a multiple of 4 on this path
-                    const uint64_t g = seg_base + i;
-                    flags = 0x01010101u;
-                    if (a.legal) flags = *reinterpret_cast<const uint32_t *>(a.legal + g);
-                    if (flags) {
-                        if (NEED_L) l = *reinterpret_cast<const float4 *>(a.latency + g);
-                        if (NEED_E) e = *reinterpret_cast<const float4 *>(a.energy + g);
-                    }
-                }
-                const float ev[4] = {e.x, e.y, e.z, e.w}, lv[4] = {l.x, l.y, l.z, l.w};
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    c[4 * j + t] = ((flags >> (8 * t)) & 0xFFu) ? composite_of<PRED>(a, (uint32_t)i + t, ev[t], lv[t], tau, lat_thr)
-                                                                : NONE;
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < ITEMS; ++j) {
-                const uint64_t i = start + (uint64_t)j * T + threadIdx.x;
-                uint64_t v = NONE;
-                if (i < a.seg_len) {
-                    const uint64_t g = seg_base + i;
-                    if (!a.legal || a.legal[g])
-                        v = composite_of<PRED>(a, (uint32_t)i, NEED_E ? a.energy[g] : 0.0f, NEED_L ? a.latency[g] : 0.0f, tau,
-                                               lat_thr);
-                }
-                c[j] = v;
-            }
-        }
-    }
-
-    uint32_t n_selected;
-    const uint64_t thr = block_threshold<T>(c, a.k, 32 + a.idx_bits, sh, &n_selected);
-    const bool last_level = gridDim.x == 1;
-    if (last_level && a.thr_out) {
-        // RANK stage A: feasible = latency composite <= thr (everything legal when fewer than k exist)
-        if (threadIdx.x == 0) a.thr_out[s] = n_selected < a.k ? NONE : thr;
-        return;
-    }
+    uint32_t kept;
+    bool bounded;
+    // the direct ranking's counters start at zero, the pool's cursor too (ordered before their use by the barriers
+    // of the gather step)
+    for (uint32_t i = threadIdx.x; i < SMALL; i += T) sh.small.rank[i] = 0;
     if (threadIdx.x == 0) sh.cursor = 0;
-    __syncthreads();
-    if (!last_level) {
-        uint64_t *out = a.list_out + ((uint64_t)s * gridDim.x + blockIdx.x) * a.k;
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-            if (c[j] <= thr) out[atomicAdd(&sh.cursor, 1u)] = c[j]; // NONE > thr; exactly n_selected qualify
-        for (uint32_t i = n_selected + threadIdx.x; i < a.k; i += T) out[i] = NONE;
-        return;
-    }
-    // last level: bitonic sort of the selection (padded to a power of two with NONE), then unpack
-    uint32_t pow2 = 2;
-    while (pow2 < a.k) pow2 <<= 1;
-    for (uint32_t i = threadIdx.x; i < pow2; i += T) sort_buf[i] = NONE;
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j)
-        if (c[j] <= thr) sort_buf[atomicAdd(&sh.cursor, 1u)] = c[j];
-    __syncthreads();
-    for (uint32_t size = 2; size <= pow2; size <<= 1)
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            for (uint32_t t = threadIdx.x; t < pow2 / 2; t += T) {
-                const uint32_t lo = 2 * t - (t & (stride - 1)); // index with the `stride` bit clear
-                const uint32_t hi = lo + stride;
-                const bool ascending = (lo & size) == 0;
-                const uint64_t x = sort_buf[lo], y = sort_buf[hi];
-                if ((x > y) == ascending) {
-                    sort_buf[lo] = y;
-                    sort_buf[hi] = x;
-                }
-            }
-            __syncthreads();
-        }
-    const uint64_t idx_mask = (1ull << a.idx_bits) - 1;
-    for (uint32_t i = threadIdx.x; i < a.k; i += T) {
-        const uint64_t v = sort_buf[i];
-        const bool valid = i < n_selected;
-        a.idx_out[(uint64_t)s * a.k + i] = valid ? (uint32_t)(v & idx_mask) : 0xFFFFFFFFu;
-        a.energy_out[(uint64_t)s * a.k + i] = valid ? key_to_float((uint32_t)(v >> a.idx_bits)) : __builtin_inff();
-    }
-    if (threadIdx.x == 0) a.count_out[s] = n_selected;
+    if (SRC == SRC_LIST) gather_list<T>(a.list_in + (uint64_t)s * a.list_len, a.list_len, (uint64_t)blockIdx.x * (T * ITEMS), a.k, sh, c, &kept, &bounded);
+    else gather_scores<T, SRC, PRED>(a, s, sh, c, &kept, &bounded);
+    select_and_emit<T>(a, s, c, kept, bounded, gridDim.x == 1, sh, sort_buf);
 }
 
 // ---------------------------------------------------------------- host side
@@ -390,7 +646,7 @@ struct WsLayout {
     uint64_t lat_parts, lat_thr, list_a, list_b, total;
 };
 
-// k_lists: the largest per-block selection any stage of the call makes (k, or m_latency in RANK mode)
+// m_latency: the latency gate of a RANK-mode call when it needs a stage of its own, else 0
 WsLayout ws_layout(uint64_t seg_len, uint32_t n_seg, uint32_t k, uint32_t m_latency)
 {
     Plan p = plan_for(seg_len, n_seg, k);
