@@ -733,10 +733,12 @@ extern "C" uint64_t topk_select_rank_workspace_bytes(uint64_t n, uint32_t n_segm
     return ws_layout(seg_len, n_segments, k, m_latency < seg_len ? m_latency : 0).total;
 }
 
-int32_t eck::topk_select_impl(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
-                              uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
-                              uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
-                              void *stream)
+namespace {
+
+// argument checks shared by the entry points; *need = bytes of workspace the call takes
+int32_t check_arguments(const float *energy, const float *latency, uint64_t n, uint32_t n_segments, uint32_t k, int32_t mode,
+                        float alpha, uint32_t m_latency, const uint32_t *idx_out, const float *energy_out,
+                        const uint32_t *count_out, bool *stage_a, WsLayout *layout)
 {
     if (!energy || !idx_out || !energy_out || !count_out || n == 0 || k == 0 || n_segments == 0) return ECK_EINVAL;
     if (mode != ECK_SELECT_THRESHOLD && mode != ECK_SELECT_RANK) return ECK_EINVAL;
@@ -745,13 +747,28 @@ int32_t eck::topk_select_impl(const float *energy, const float *latency, const u
     if (n % n_segments || k > n / n_segments || n / n_segments > 0xFFFFFFFEull || n_segments > 65535) return ECK_ESHAPE;
     if (k > ECK_MAX_K) return ECK_EUNSUPPORTED;
     const uint64_t seg_len = n / n_segments;
-    const bool rank = latency && mode == ECK_SELECT_RANK;
     // a latency gate that admits the whole segment needs no first stage
-    const bool stage_a = rank && m_latency < seg_len;
-    if (stage_a && m_latency > ECK_MAX_K) return ECK_EUNSUPPORTED;
-    const WsLayout w = ws_layout(seg_len, n_segments, k, stage_a ? m_latency : 0);
+    *stage_a = latency && mode == ECK_SELECT_RANK && m_latency < seg_len;
+    if (*stage_a && m_latency > ECK_MAX_K) return ECK_EUNSUPPORTED;
+    *layout = ws_layout(seg_len, n_segments, k, *stage_a ? m_latency : 0);
+    return ECK_OK;
+}
+
+} // namespace
+
+int32_t eck::topk_select_impl(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                              uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
+                              uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
+                              void *stream)
+{
+    bool stage_a;
+    WsLayout w;
+    const int32_t bad = check_arguments(energy, latency, n, n_segments, k, mode, alpha, m_latency, idx_out, energy_out,
+                                        count_out, &stage_a, &w);
+    if (bad != ECK_OK) return bad;
     if (!ws || ws_bytes < w.total) return ECK_EWORKSPACE;
     if ((uintptr_t)ws & 15) return ECK_EALIGN;
+    const uint64_t seg_len = n / n_segments;
 
     SelectArgs a = {};
     a.energy = energy;
