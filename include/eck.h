@@ -296,6 +296,25 @@ int32_t topk_select(const float *energy, const float *latency, const uint8_t *le
                     uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
                     void *stream);
 
+/* topk_select for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same result, no ws: the
+ * intermediate lists live in an array of ECK_TOPK_STATIC_BYTES that is part of
+ * the library's device image (one copy per GPU, held until the process ends).
+ * The call allocates and frees nothing; its kernels are those of topk_select.
+ * Sizes whose workspace (topk_select_workspace_bytes /
+ * topk_select_rank_workspace_bytes) exceeds ECK_TOPK_STATIC_BYTES are refused
+ * with ECK_EWORKSPACE before anything is launched.  All calls on one GPU share
+ * the one array: calls that overlap in time on the same GPU (different streams
+ * or host threads) race and must be serialised by the caller; calls on
+ * different GPUs are independent.  Nothing in the array has to be cleared
+ * between calls.  Other errors as topk_select; ECK_EUNSUPPORTED also for a
+ * device ordinal of 64 or more. */
+#define ECK_TOPK_STATIC_BYTES (8u << 20)
+int32_t topk_select_static(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                           uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
+                           uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *stream);
+
 /* ------------------------------------------------------------------ update */
 
 uint64_t costmodel_update_workspace_bytes(const eck_model *model, uint64_t n_pairs, int32_t minibatch);

@@ -13,6 +13,8 @@
 // not depend on execution order.  Inside a block: a cheap upper bound on its k-th smallest key first (from
 // the least key of every thread), then the few candidates under the bound are ranked against each other,
 // which selects and orders them at once; a radix select on LDS histograms takes over when many remain.
+#include <mutex>
+
 #include "eck_internal.h"
 
 using namespace eck;
@@ -832,4 +834,50 @@ extern "C" int32_t topk_select(const float *energy, const float *latency, const 
 {
     return topk_select_impl(energy, latency, legal, n, n_segments, k, mode, alpha, m_latency, idx_out, energy_out,
                             count_out, ws, ws_bytes, stream);
+}
+
+// ---------------------------------------------------------------- the entry point that allocates nothing
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+// the workspace of topk_select_static: one copy per GPU the library runs on, held until the process ends
+__device__ __align__(256) unsigned char scratch[ECK_TOPK_STATIC_BYTES];
+void *scratch_address[MAX_DEVICES]; // per device: where that device's copy of `scratch` lives
+std::mutex scratch_mutex;
+} // namespace
+
+extern "C" int32_t topk_select_static(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                                      uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
+                                      uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *stream)
+{
+    bool stage_a;
+    WsLayout w;
+    const int32_t bad = check_arguments(energy, latency, n, n_segments, k, mode, alpha, m_latency, idx_out, energy_out,
+                                        count_out, &stage_a, &w);
+    if (bad != ECK_OK) return bad;
+    if (w.total > ECK_TOPK_STATIC_BYTES) return ECK_EWORKSPACE;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return ECK_EDEVICE;
+    }
+    if (dev < 0 || dev >= MAX_DEVICES) return ECK_EUNSUPPORTED;
+    void *ws;
+    {
+        // the array's name is a host-side stand-in; its address on the current device is looked up once per device
+        std::lock_guard<std::mutex> guard(scratch_mutex);
+        if (!scratch_address[dev]) {
+            void *found = nullptr;
+            if (hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)) != hipSuccess || !found) {
+                (void)hipGetLastError();
+                return ECK_EDEVICE;
+            }
+            scratch_address[dev] = found;
+        }
+        ws = scratch_address[dev];
+    }
+    // nothing in the workspace has to start at zero: every word a kernel reads was written by an earlier kernel of
+    // the same call
+    return topk_select_impl(energy, latency, legal, n, n_segments, k, mode, alpha, m_latency, idx_out, energy_out,
+                            count_out, ws, ECK_TOPK_STATIC_BYTES, stream);
 }

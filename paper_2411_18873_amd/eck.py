@@ -29,7 +29,7 @@ EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_in
            "candidate_enumerate", "candidate_enumerate_batch", "eck_candidates_gather", "features_compute",
            "features_compute_batch", "eck_model_create", "eck_model_destroy",
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
-           "topk_select_workspace_bytes", "topk_select_rank_workspace_bytes", "topk_select", "costmodel_update_workspace_bytes", "costmodel_update",
+           "topk_select_workspace_bytes", "topk_select_rank_workspace_bytes", "topk_select", "topk_select_static", "costmodel_update_workspace_bytes", "costmodel_update",
            "eck_trees_create", "eck_trees_destroy", "eck_trees_count", "eck_trees_set", "eck_trees_get",
            "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step", "eck_k_count",
            "eck_candidates_dedup", "eck_candidates_dedup_workspace_bytes"]
@@ -103,6 +103,7 @@ def lib():
         L.topk_select_rank_workspace_bytes.argtypes = [u64, u32, u32, u32]
         L.topk_select_rank_workspace_bytes.restype = u64
         L.topk_select.argtypes = [vp, vp, vp, u64, u32, u32, i32, f32, u32, vp, vp, vp, vp, u64, vp]
+        L.topk_select_static.argtypes = [vp, vp, vp, u64, u32, u32, i32, f32, u32, vp, vp, vp, vp]
         L.costmodel_update_workspace_bytes.argtypes = [vp, u64, i32]
         L.costmodel_update_workspace_bytes.restype = u64
         L.costmodel_update.argtypes = [vp, vp, i32, u64, vp, u64, i32, i32, f32, f32, f32, f32, vp, vp, vp, u64, vp]
@@ -373,6 +374,25 @@ def topk_select(energy, latency, legal, n_segments, k, idx_out, energy_out, coun
     _check("topk_select", lib().topk_select(
         _ptr(energy), _ptr(latency), _ptr(legal), energy.numel(), n_segments, k, mode, alpha, m_latency,
         _ptr(idx_out), _ptr(energy_out), _ptr(count_out), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+TOPK_STATIC_BYTES = 8 << 20
+
+
+def topk_select_static(energy, latency, legal, n_segments, k, idx_out, energy_out, count_out, mode=SELECT_THRESHOLD,
+                       alpha=1.1, m_latency=0):
+    """topk_select on the library's own fixed workspace: allocates nothing; sizes needing more than
+    TOPK_STATIC_BYTES are refused"""
+    _dev(energy, torch.float32, "energy")
+    _dev(latency, torch.float32, "latency")
+    if legal is not None:
+        assert legal.is_cuda and legal.element_size() == 1 and legal.is_contiguous()
+    assert idx_out.is_cuda and idx_out.element_size() == 4 and idx_out.numel() >= n_segments * k
+    _dev(energy_out, torch.float32, "energy_out")
+    assert count_out.is_cuda and count_out.element_size() == 4 and count_out.numel() >= n_segments
+    _check("topk_select_static", lib().topk_select_static(
+        _ptr(energy), _ptr(latency), _ptr(legal), energy.numel(), n_segments, k, mode, alpha, m_latency,
+        _ptr(idx_out), _ptr(energy_out), _ptr(count_out), _stream()))
 
 
 def costmodel_update_workspace_bytes(model, n_pairs, minibatch):
