@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIBDIR = os.path.join(HERE, "lib")
 LIB = os.path.join(LIBDIR, "libeck.so")
-SOURCES = ["space.hip", "model.hip", "topk.hip", "update.hip", "trees.hip"]
+SOURCES = ["space.hip", "model.hip", "topk.hip", "update.hip", "refit.hip", "trees.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
     # compiler-generated packed fp32 math is switched off for device code
@@ -37,7 +37,7 @@ def _compile(src):
 
 def build_lib(verbose=True):
     os.makedirs(LIBDIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as pool:
+    with ThreadPoolExecutor(max_workers=6) as pool:
         objs = list(pool.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     if verbose:

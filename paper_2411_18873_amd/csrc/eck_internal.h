@@ -68,6 +68,14 @@ struct eck_model {
 namespace eck {
 // re-derive the packed weights from theta (BF16 models); enqueued on stream
 int32_t model_repack(eck_model *m, hipStream_t stream);
+// Adam steps of a BF16 model in two launches per step (refit.hip): whether that path takes this call, the bytes it
+// needs behind the other buffers of costmodel_update's workspace, and the steps themselves (labels y and the
+// data-error flag come from the caller's kernels; the last step's mean loss goes to *loss_scalar, device memory)
+bool refit_applies(const eck_model *m, const void *feat, int32_t feat_dtype, uint64_t ld, int minibatch);
+uint64_t refit_workspace_bytes(const eck_model *m, int minibatch);
+int32_t refit_steps(const eck_model *m, const void *feat, int32_t feat_dtype, uint64_t ld, const float *y, uint64_t n_pairs,
+                    int32_t n_steps, int32_t minibatch, float lr, float beta1, float beta2, float eps,
+                    const uint32_t *bad_flag, float *loss_scalar, void *ws, hipStream_t st);
 // topk_select on a workspace of the caller's or of the library's
 int32_t topk_select_impl(const float *energy, const float *latency, const uint8_t *legal, uint64_t n, uint32_t n_segments,
                          uint32_t k, int32_t mode, float alpha, uint32_t m_latency, uint32_t *idx_out, float *energy_out,

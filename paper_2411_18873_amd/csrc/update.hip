@@ -418,7 +418,7 @@ __global__ __launch_bounds__(1024) void output_grad_kernel(const float *__restri
 }
 
 struct UpdWs {
-    uint64_t scalars, y, pred, h1, h2, dy, lterm, d2, d1, grad, total;
+    uint64_t scalars, y, pred, h1, h2, dy, lterm, d2, d1, grad, refit, total;
 };
 
 UpdWs upd_layout(const eck_model *m, uint64_t n_pairs, int mb)
@@ -436,6 +436,8 @@ UpdWs upd_layout(const eck_model *m, uint64_t n_pairs, int mb)
     w.d2 = o;      o = align(o + (uint64_t)mb * m->widths[2] * 4);
     w.d1 = o;      o = align(o + (uint64_t)mb * m->widths[1] * 4);
     w.grad = o;    o = align(o + m->n_params * 4);
+    w.refit = o;   // the two-launch step of BF16 models keeps its own buffers behind the others
+    if (m->dtype == ECK_BF16 && mb % 64 == 0) o += refit_workspace_bytes(m, mb);
     w.total = o;
     return w;
 }
@@ -498,6 +500,15 @@ extern "C" int32_t costmodel_update(eck_model *m, const void *feat, int32_t feat
     if (rc != ECK_OK) return rc;
     hipLaunchKernelGGL(snr_kernel, dim3(1), dim3(1024), 0, st, pred, y, n_pairs, sc);
 
+    if (refit_applies(m, feat, feat_dtype, ld, minibatch)) {
+        // BF16 model: two launches per step
+        rc = refit_steps(m, feat, feat_dtype, ld, y, n_pairs, n_steps, minibatch, lr, beta1, beta2, eps, &sc->bad, &sc->loss,
+                         base + w.refit, st);
+        if (rc != ECK_OK) return rc;
+        hipLaunchKernelGGL(finish_kernel, dim3(1), dim3(64), 0, st, theta, P, n_steps, sc, snr_out, loss_out);
+        ECK_HIP_TRY(hipGetLastError());
+        return model_repack(m, st);
+    }
     const uint64_t nb = n_pairs / (uint64_t)B;
     for (int s = 0; s < n_steps; ++s) {
         const uint64_t row0 = ((uint64_t)s % nb) * (uint64_t)B;
