@@ -147,3 +147,47 @@ def test_zero_steps_reports_snr_only(G):
     st = _oracle_state(theta)
     snr_o, _ = oracle.update(widths, st, f32, e, 0, 256)
     assert abs(snr_g - snr_o) <= 1e-4 * snr_o and math.isnan(loss_g)
+
+
+@pytest.mark.parametrize("widths,mb", [([64, 512, 512, 1], 512), ([64, 128, 128, 1], 128), ([32, 64, 64, 1], 64),
+                                       ([64, 256, 256, 1], 96)])
+def test_bf16_refit_every_model_shape_and_both_step_paths(G, widths, mb):
+    """BF16 models refit in two launches per step when the minibatch is a multiple of 64 (every shape the library
+    builds), else product by product (minibatch 96 here); either way: one step against the oracle at the bf16
+    tolerance, a 12-step run that lowers the loss as the oracle's does, fp32 features that hold bf16 values giving
+    the bf16-feature result bit for bit, and the same call twice giving the same bits."""
+    F = widths[0]
+    n = 4 * mb
+    if F == 64:
+        f32, b16, e = _pairs(n + (n & 1))
+    else:
+        ref = oracle.Space(synth.CONFIGS["c1"]["problem"], oracle.SPACE_KNOB)
+        genes = oracle.enumerate_candidates(ref, oracle.MODE_EXHAUSTIVE, n)
+        _, f32, b16, _ = oracle.features(ref, genes, 32)
+        e = synth.measured_energy(f32, 5)
+    f32, b16, e = f32[:, :n], b16[:, :n], e[:n]
+    P = synth.param_count(widths)
+    theta = synth.mlp_theta(widths, 6, bf16=True, bias_scale=0.2)
+    feat_o = oracle.bf16_bits_to_f32(b16)
+    st = _oracle_state(theta)
+    model = G.make_model(widths, eck.BF16, theta)
+    feat = G.bf16_dev(np.ascontiguousarray(b16))
+    snr_g, loss_g = G.update_gpu(model, feat, e, 1, mb)
+    snr_o, loss_o = oracle.update(widths, st, feat_o, e, 1, mb, bf16_weights=True)
+    assert abs(snr_g - snr_o) <= 2e-2 * snr_o and abs(loss_g - loss_o) <= 2e-2 * loss_o
+    got = model.get_state().cpu().numpy().astype(np.float64)
+    d = np.abs(got[:P] - st[:P])
+    assert d.max() <= 2.001e-3 and np.mean(d > 1e-4) < 0.03      # Adam's first step is lr * sign(g)
+    snr_g, loss_g = G.update_gpu(model, feat, e, 12, mb)
+    snr_o, loss_o = oracle.update(widths, st, feat_o, e, 12, mb, bf16_weights=True)
+    assert abs(loss_g - loss_o) <= 0.05 * loss_o and abs(snr_g - snr_o) <= 0.05 * snr_o
+    assert model.get_state().cpu().numpy()[3 * P] == 13.0
+    # fp32 features holding the same values; and a repeat
+    a = G.make_model(widths, eck.BF16, theta)
+    G.update_gpu(a, feat, e, 5, mb)
+    b = G.make_model(widths, eck.BF16, theta)
+    G.update_gpu(b, G.to_dev(np.ascontiguousarray(feat_o)), e, 5, mb)
+    c = G.make_model(widths, eck.BF16, theta)
+    G.update_gpu(c, feat, e, 5, mb)
+    sa = a.get_state().cpu().numpy()
+    assert np.array_equal(sa, b.get_state().cpu().numpy()) and np.array_equal(sa, c.get_state().cpu().numpy())
