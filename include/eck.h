@@ -262,6 +262,25 @@ int32_t eck_model_get_state(const eck_model *model, float *blob, uint64_t n_floa
 int32_t costmodel_score(const eck_model *model, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n,
                         float *score_out, void *ws, uint64_t ws_bytes, void *stream);
 
+/* costmodel_score that also reduces the scores it writes: min_key_out[s] =
+ * the least score among the legal candidates of segment s (n_segments equal
+ * consecutive segments, as in topk_select), as an order-preserving key
+ *     key(x) = bits(x) ^ (x < 0 ? 0xFFFFFFFF : 0x80000000)
+ * (unsigned comparison of keys = comparison of the floats, -0 < +0), or
+ * 0xFFFFFFFF when the segment has no legal candidate with a score that is a
+ * number.  Run on the latency model it yields the L_min of every segment
+ * (Alg. 1 LatencyEvaAndPick; the latency gate of Sec. 4.3) in the pass that
+ * produces the latencies, so that topk_select_known_min need not read them a
+ * second time.  legal: device uint8 [n] or NULL (all legal); min_key_out:
+ * device uint32 [n_segments], overwritten.  BF16 models fold the reduction
+ * into the scoring kernel (integer atomics: the result does not depend on the
+ * order of execution).
+ * Errors as costmodel_score; also EINVAL (min_key_out NULL, n_segments 0),
+ * ESHAPE (n % n_segments, more than 65535 segments), EALIGN (legal odd). */
+int32_t costmodel_score_min(const eck_model *model, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n,
+                            float *score_out, const uint8_t *legal, uint32_t n_segments, uint32_t *min_key_out,
+                            void *stream);
+
 /* ------------------------------------------------------------------ select */
 
 /* Bytes of workspace topk_select needs for these sizes in THRESHOLD mode or
@@ -295,6 +314,18 @@ int32_t topk_select(const float *energy, const float *latency, const uint8_t *le
                     uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
                     uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
                     void *stream);
+
+/* topk_select in THRESHOLD mode when the least latency of every segment is
+ * already known: latency_min_key = what costmodel_score_min wrote for the
+ * latency model with the same legal flags and segments (device uint32
+ * [n_segments]).  The score arrays are then read exactly once.  Same result as
+ * topk_select(..., ECK_SELECT_THRESHOLD, alpha, ...), same workspace
+ * (topk_select_workspace_bytes), same errors; EINVAL also for a NULL latency
+ * or latency_min_key. */
+int32_t topk_select_known_min(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                              uint32_t n_segments, uint32_t k, float alpha, const uint32_t *latency_min_key,
+                              uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
+                              void *stream);
 
 /* topk_select for callers that cannot allocate device memory and have no
  * workspace to hand over: code under HIP graph capture, tight serving loops,

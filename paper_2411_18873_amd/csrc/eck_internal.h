@@ -76,8 +76,9 @@ uint64_t refit_workspace_bytes(const eck_model *m, int minibatch);
 int32_t refit_steps(const eck_model *m, const void *feat, int32_t feat_dtype, uint64_t ld, const float *y, uint64_t n_pairs,
                     int32_t n_steps, int32_t minibatch, float lr, float beta1, float beta2, float eps,
                     const uint32_t *bad_flag, float *loss_scalar, void *ws, hipStream_t st);
-// topk_select on a workspace of the caller's or of the library's
+// topk_select on a workspace of the caller's or of the library's; known_min: THRESHOLD mode with the least latency
+// of every segment already known (device, one order key per segment), else NULL
 int32_t topk_select_impl(const float *energy, const float *latency, const uint8_t *legal, uint64_t n, uint32_t n_segments,
                          uint32_t k, int32_t mode, float alpha, uint32_t m_latency, uint32_t *idx_out, float *energy_out,
-                         uint32_t *count_out, void *ws, uint64_t ws_bytes, void *stream);
+                         uint32_t *count_out, void *ws, uint64_t ws_bytes, void *stream, const uint32_t *known_min);
 } // namespace eck

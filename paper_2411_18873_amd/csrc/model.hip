@@ -444,14 +444,33 @@ __device__ __forceinline__ void wait_vm(bool dma_after, bool x_after)
     }
 }
 
-template <int F, int H1, int H2, int NC, bool FEAT_BF16, bool WIDE_ROWS>
+// WITH_MIN: the kernel also reduces its scores to the least one per segment of seg_len candidates, over the legal
+// candidates (a number, not NaN), as order keys -- what the selection's latency gate needs, without a pass of
+// its own over the scores.  Every lane keeps a running minimum for the segment its wavefront is in; the lanes are
+// combined and handed to memory with one integer atomic when the wavefront moves on to another segment or ends; a
+// wavefront whose 32 NC candidates straddle two segments sends them one by one.  The legality flags of a tile travel with its features.
+struct MinArgs {
+    const uint8_t *legal; // or NULL: all legal
+    uint64_t seg_len;
+    uint32_t *min_key;    // [n / seg_len], preset to 0xFFFFFFFF
+    uint32_t tiles_per_seg; // seg_len / (candidates per tile) when that is whole (set by the launcher), else 0
+};
+
+__device__ __forceinline__ uint32_t score_order_key(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+template <int F, int H1, int H2, int NC, bool FEAT_BF16, bool WIDE_ROWS, bool WITH_MIN>
 __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__restrict__ packed, PackedLayout L,
                                                          const void *__restrict__ feat, uint64_t ld, uint64_t n,
-                                                         float *__restrict__ out, uint32_t n_tiles)
+                                                         float *__restrict__ out, uint32_t n_tiles, MinArgs mn)
 {
     constexpr int KS1 = F / 16, OC1 = H1 / 32, KS2 = H1 / 16, OC2 = H2 / 32;
     constexpr int TILE = 4 * NC * 32;
     constexpr int NXLOADS = KS1 * 8;                 // feature loads per lane per tile
+    constexpr int NX = NXLOADS + (WITH_MIN ? 1 : 0); // ... and the load of the legality flags that goes with them
     constexpr int KSP = KS2 / 2;                     // k-steps (= 1 KB fragments) per piece
     constexpr int PIECES = 2 * OC2;                  // pieces per tile
     constexpr int RING = KSP < 4 ? KSP : 4;          // weight fragments held in registers
@@ -460,7 +479,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     constexpr uint32_t W1_BYTES = F * H1 * 2, W1B_BYTES = H1 * 4, PIECE_BYTES = KSP * 1024;
     static_assert(KS2 % 2 == 0 && KSP % RING == 0 && OC2 % 2 == 0 && PIECES % 4 == 0, "unsupported shape");
     static_assert(NC == 2 || NC == 4, "unsupported tile width");
-    static_assert(N_DMA + NXLOADS < 63, "outstanding loads must fit the load counter");
+    static_assert(N_DMA + NX < 63, "outstanding loads must fit the load counter");
     using Raw = RawFeat<NC, FEAT_BF16>;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const bf16x8 *lds_w1 = reinterpret_cast<const bf16x8 *>(lds);
@@ -468,6 +487,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     unsigned char *lds_ring = lds + W1_BYTES + W1B_BYTES; // four slots of PIECE_BYTES; piece p uses slot p & 3
     float *lds_b2 = reinterpret_cast<float *>(lds_ring + 4 * PIECE_BYTES);
     float *lds_w3 = lds_b2 + H2;
+    uint32_t *lds_run = reinterpret_cast<uint32_t *>(lds_w3 + H2); // WITH_MIN: [256] least key of the lane's segment
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, col = lane & 31;
@@ -521,6 +541,18 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         }
     };
 
+    // legality flags of this lane's NC candidates (one byte each): requested early in the tile whose epilogue reads
+    // them, just before the features of the next tile (so the waits on the load counter see one more load there)
+    uint32_t legal_bits = 0x01010101u;
+    auto load_legal = [&](uint32_t tile) {
+        const uint64_t cand = first_candidate(tile);
+        // without flags the load still happens (the waits on the load counter count it): any readable address does.
+        // The host checks that the flags are aligned to the NC-byte word, so a word whose first byte is a flag lies
+        // in that flag's page even when its last bytes are past the array (those are ignored below).
+        const unsigned char *p = mn.legal ? mn.legal + (cand < n ? cand : (uint64_t)tile * TILE)
+                                          : reinterpret_cast<const unsigned char *>(feat);
+        legal_bits = NC == 2 ? (uint32_t)*reinterpret_cast<const uint16_t *>(p) : *reinterpret_cast<const uint32_t *>(p);
+    };
     Raw raw[NXLOADS];
     if (blockIdx.x < n_tiles) {
         fetch_piece(0);
@@ -539,6 +571,19 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     const float b3 = *reinterpret_cast<const float *>(packed + L.b3);
     __syncthreads();
 
+    // WITH_MIN: the segment of this wavefront's candidates in the tile before and, per lane, the least key it has
+    // seen there; the lanes are only combined when the segment changes and at the end
+    uint64_t seg = 0, seg_begin = 0;
+    uint32_t seg_tile0 = 0; // first tile of that segment, when segments are whole tiles
+    if (WITH_MIN) lds_run[tid] = 0xFFFFFFFFu; // only this lane ever touches its word
+    auto flush_running_min = [&]() {
+        uint32_t best = lds_run[tid];
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) best = min(best, (uint32_t)__shfl_xor((int)best, off));
+        if (lane == 0 && best != 0xFFFFFFFFu) // both halves of the wavefront hold the same scores
+            (void)__hip_atomic_fetch_min(mn.min_key + seg, best, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lds_run[tid] = 0xFFFFFFFFu;
+    };
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const bool more_tiles = tile + gridDim.x < n_tiles;
 
@@ -619,7 +664,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
             const int p = 2 * oc + HALF;
             // piece p+1 must have landed.  Operations issued after its fetch: the fetch of piece p+2 (if
             // there is one) and, for p = 2 and 3, the feature loads of the next tile (issued in piece 1).
-            wait_vm<N_DMA, NXLOADS>(p + 2 < PIECES || more_tiles, p == 2 || p == 3);
+            wait_vm<N_DMA, NX>(p + 2 < PIECES || more_tiles, p == 2 || p == 3);
             __syncthreads();
             if (p + 3 < PIECES) fetch_piece(p + 3);
             else if (more_tiles) fetch_piece(p + 3 - PIECES);
@@ -627,6 +672,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                 // the feature loads must be issued after the piece fetch: the counter waits rely on that order
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_sched_barrier(0);
+                if (WITH_MIN) load_legal(tile);
                 load_tile(more_tiles ? tile + gridDim.x : tile, raw);
             }
             const bf16x8 *mine = reinterpret_cast<const bf16x8 *>(lds_ring + SLOT * PIECE_BYTES);
@@ -710,17 +756,67 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
             }
         }
         const uint64_t cand = first_candidate(tile);
+        uint32_t key[NC];
 #pragma unroll
         for (int c = 0; c < NC; ++c) {
             const float total = y[c] + __shfl_xor(y[c], 32);
-            if (h == 0 && cand + c < n) out[cand + c] = total + b3;
+            const float score = total + b3;
+            if (h == 0 && cand + c < n) out[cand + c] = score;
+            if (WITH_MIN) {
+                const bool legal = !mn.legal || ((legal_bits >> (8 * c)) & 0xFFu);
+                key[c] = (legal && cand + c < n && score == score) ? score_order_key(score) : 0xFFFFFFFFu;
+            }
+        }
+        if (WITH_MIN && mn.tiles_per_seg) {
+            // segments are whole tiles: 32-bit scalar bookkeeping per tile, no wavefront straddles two segments
+            if (tile - seg_tile0 >= mn.tiles_per_seg) {
+                flush_running_min();
+                seg = tile / mn.tiles_per_seg;
+                seg_tile0 = (uint32_t)seg * mn.tiles_per_seg;
+            }
+            uint32_t best = key[0];
+#pragma unroll
+            for (int c = 1; c < NC; ++c) best = min(best, key[c]);
+            (void)atomicMin(&lds_run[tid], best); // in LDS: no register is held across tiles
+        } else if (WITH_MIN) {
+            // this wavefront's candidates; everything about the segment is the same in every lane and is kept in
+            // scalar registers (the wavefront's number, derived from the thread's, is uniform but not known to be)
+            const uint64_t first = (uint64_t)tile * TILE + (uint64_t)__builtin_amdgcn_readfirstlane(wave) * (NC * 32);
+            if (first < n) {
+                const uint64_t last = first + NC * 32 - 1 < n ? first + NC * 32 - 1 : n - 1;
+                // the segment of `first`: tiles come in increasing order, so it is usually the one of the tile before
+                // or the next one (a 64-bit division costs as much as a twentieth of a tile's matrix work)
+                if (first - seg_begin >= mn.seg_len) {
+                    flush_running_min();
+                    if (first - seg_begin < 2 * mn.seg_len) {
+                        seg += 1;
+                        seg_begin += mn.seg_len;
+                    } else {
+                        seg = first / mn.seg_len;
+                        seg_begin = seg * mn.seg_len;
+                    }
+                }
+                if (last - seg_begin < mn.seg_len) {
+                    uint32_t best = key[0];
+#pragma unroll
+                    for (int c = 1; c < NC; ++c) best = min(best, key[c]);
+                    (void)atomicMin(&lds_run[tid], best); // in LDS: no register is held across tiles
+                } else if (h == 0) {
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+                        if (key[c] != 0xFFFFFFFFu)
+                            (void)__hip_atomic_fetch_min(mn.min_key + (cand + c) / mn.seg_len, key[c], __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
         }
     }
+    if (WITH_MIN) flush_running_min();
 }
 
-template <int F, int H1, int H2, int NC>
+template <int F, int H1, int H2, int NC, bool WITH_MIN>
 int32_t launch_bf16(const eck_model *m, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n, float *out,
-                    hipStream_t st)
+                    const MinArgs &mn, hipStream_t st)
 {
     const PackedLayout L = packed_layout(F, H1, H2);
     constexpr int TILE = 4 * NC * 32;
@@ -730,20 +826,93 @@ int32_t launch_bf16(const eck_model *m, const void *feat, int32_t feat_dtype, ui
     int cus = 256;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device);
     const uint32_t grid = n_tiles < (uint32_t)cus ? n_tiles : (uint32_t)cus;
-    // W1 and b1, four ring slots of half a W2 chunk, b2 and w3
-    const size_t lds = (size_t)F * H1 * 2 + (size_t)H1 * 4 + 4 * (size_t)(H1 / 32) * 1024 + 2 * H2 * 4;
+    // W1 and b1, four ring slots of half a W2 chunk, b2 and w3, a running minimum per lane
+    const size_t lds = (size_t)F * H1 * 2 + (size_t)H1 * 4 + 4 * (size_t)(H1 / 32) * 1024 + 2 * H2 * 4 + (WITH_MIN ? 1024 : 0);
     // the per-lane part of a feature address is a 32-bit offset unless eight rows exceed it
     const uint64_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
     const bool wide = 8 * ld * elem > 0xFFFFFFFFull - TILE * elem;
-    auto kern = feat_dtype == ECK_BF16
-                    ? (wide ? score_bf16_kernel<F, H1, H2, NC, true, true> : score_bf16_kernel<F, H1, H2, NC, true, false>)
-                    : (wide ? score_bf16_kernel<F, H1, H2, NC, false, true> : score_bf16_kernel<F, H1, H2, NC, false, false>);
+    auto kern = feat_dtype == ECK_BF16 ? (wide ? score_bf16_kernel<F, H1, H2, NC, true, true, WITH_MIN>
+                                                : score_bf16_kernel<F, H1, H2, NC, true, false, WITH_MIN>)
+                                       : (wide ? score_bf16_kernel<F, H1, H2, NC, false, true, WITH_MIN>
+                                               : score_bf16_kernel<F, H1, H2, NC, false, false, WITH_MIN>);
     ECK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)lds));
+    MinArgs mn_tiles = mn;
+    mn_tiles.tiles_per_seg = (mn.seg_len % TILE == 0 && mn.seg_len / TILE <= 0xFFFFFFFFull) ? (uint32_t)(mn.seg_len / TILE) : 0;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, (const unsigned char *)m->d_packed, L, feat, ld, n, out,
-                       n_tiles);
+                       n_tiles, mn_tiles);
     ECK_HIP_TRY(hipGetLastError());
     return ECK_OK;
+}
+
+// least order key per segment of fp32 scores (the small fp32 models, whose forward kernel has no matrix-core epilogue)
+__global__ __launch_bounds__(256) void min_key_kernel(const float *__restrict__ score, const uint8_t *__restrict__ legal,
+                                                      uint64_t n, uint64_t seg_len, uint32_t *__restrict__ min_key)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float v = score[i];
+    if ((legal && !legal[i]) || v != v) return;
+    (void)__hip_atomic_fetch_min(min_key + i / seg_len, score_order_key(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void fill_keys_kernel(uint32_t *p, uint32_t n)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0xFFFFFFFFu;
+}
+
+template <bool WITH_MIN>
+int32_t score_any(const eck_model *m, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n, float *score_out,
+                  const MinArgs &mn, uint32_t n_segments, void *stream)
+{
+    if (!m || !feat || !score_out || n == 0) return ECK_EINVAL;
+    if (feat_dtype != ECK_F32 && feat_dtype != ECK_BF16) return ECK_EINVAL;
+    if (ld < n) return ECK_ESHAPE;
+    if (n > (1ull << 40)) return ECK_EINVAL;
+    hipStream_t st = as_stream(stream);
+    const int F = m->widths[0], H1 = m->widths[1], H2 = m->widths[2];
+    if (m->dtype == ECK_F32 && feat_dtype != ECK_F32) return ECK_EUNSUPPORTED;
+    if (m->dtype == ECK_BF16) {
+        // A lane fetches the NC consecutive candidates it owns with one load per feature row.  Groups start at
+        // multiples of NC, so with ld a multiple of NC a group that starts below n ends inside its row; otherwise
+        // the last group of a row would run into the next row and, in the last row, past the matrix.  The pointer
+        // must be aligned to the load as well.
+        const uint64_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
+        if ((ld & 1) || ((uintptr_t)feat & (2 * elem - 1))) return ECK_EALIGN;
+    }
+    if (WITH_MIN) {
+        hipLaunchKernelGGL(fill_keys_kernel, dim3((n_segments + 255) / 256), dim3(256), 0, st, mn.min_key, n_segments);
+    }
+    if (m->dtype == ECK_F32) {
+        const size_t lds = (size_t)(F + H1 + H2) * F32_TILE * sizeof(float);
+        ECK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(score_f32_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        const uint64_t blocks = (n + F32_TILE - 1) / F32_TILE;
+        if (blocks > 0x7FFFFFFFull) return ECK_EUNSUPPORTED;
+        hipLaunchKernelGGL(score_f32_kernel, dim3((unsigned)blocks), dim3(256), lds, st, m->d_state, F, H1, H2,
+                           m->off_w[0], m->off_b[0], m->off_w[1], m->off_b[1], m->off_w[2], m->off_b[2], (const float *)feat,
+                           ld, n, score_out);
+        if (WITH_MIN)
+            hipLaunchKernelGGL(min_key_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, score_out, mn.legal, n,
+                               mn.seg_len, mn.min_key);
+        ECK_HIP_TRY(hipGetLastError());
+        return ECK_OK;
+    }
+    // four candidate tiles per wavefront (half the weight traffic per candidate) where 256 or fewer hidden units
+    // leave the registers for it, the features arrive as bf16 and groups of four stay inside a row (the flags of
+    // four candidates are then one 4-byte load)
+    const bool four = feat_dtype == ECK_BF16 && ld % 4 == 0 && ((uintptr_t)feat & 7) == 0 &&
+                      (!WITH_MIN || !mn.legal || ((uintptr_t)mn.legal & 3) == 0);
+    if (F == 64 && H1 == 512 && H2 == 512) return launch_bf16<64, 512, 512, 2, WITH_MIN>(m, feat, feat_dtype, ld, n, score_out, mn, st);
+    if (F == 64 && H1 == 256 && H2 == 256 && four)
+        return launch_bf16<64, 256, 256, 4, WITH_MIN>(m, feat, feat_dtype, ld, n, score_out, mn, st);
+    if (F == 64 && H1 == 256 && H2 == 256) return launch_bf16<64, 256, 256, 2, WITH_MIN>(m, feat, feat_dtype, ld, n, score_out, mn, st);
+    if (F == 64 && H1 == 128 && H2 == 128 && four)
+        return launch_bf16<64, 128, 128, 4, WITH_MIN>(m, feat, feat_dtype, ld, n, score_out, mn, st);
+    if (F == 64 && H1 == 128 && H2 == 128) return launch_bf16<64, 128, 128, 2, WITH_MIN>(m, feat, feat_dtype, ld, n, score_out, mn, st);
+    if (F == 32 && H1 == 64 && H2 == 64) return launch_bf16<32, 64, 64, 2, WITH_MIN>(m, feat, feat_dtype, ld, n, score_out, mn, st);
+    return ECK_EUNSUPPORTED;
 }
 
 } // namespace
@@ -753,41 +922,17 @@ extern "C" int32_t costmodel_score(const eck_model *m, const void *feat, int32_t
 {
     (void)ws;
     (void)ws_bytes;
-    if (!m || !feat || !score_out || n == 0) return ECK_EINVAL;
-    if (feat_dtype != ECK_F32 && feat_dtype != ECK_BF16) return ECK_EINVAL;
-    if (ld < n) return ECK_ESHAPE;
-    if (n > (1ull << 40)) return ECK_EINVAL;
-    hipStream_t st = as_stream(stream);
-    const int F = m->widths[0], H1 = m->widths[1], H2 = m->widths[2];
-    if (m->dtype == ECK_F32) {
-        if (feat_dtype != ECK_F32) return ECK_EUNSUPPORTED;
-        const size_t lds = (size_t)(F + H1 + H2) * F32_TILE * sizeof(float);
-        ECK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(score_f32_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        const uint64_t blocks = (n + F32_TILE - 1) / F32_TILE;
-        if (blocks > 0x7FFFFFFFull) return ECK_EUNSUPPORTED;
-        hipLaunchKernelGGL(score_f32_kernel, dim3((unsigned)blocks), dim3(256), lds, st, m->d_state, F, H1, H2,
-                           m->off_w[0], m->off_b[0], m->off_w[1], m->off_b[1], m->off_w[2], m->off_b[2], (const float *)feat,
-                           ld, n, score_out);
-        ECK_HIP_TRY(hipGetLastError());
-        return ECK_OK;
-    }
-    // A lane fetches the NC consecutive candidates it owns with one load per feature row.  Groups start at
-    // multiples of NC, so with ld a multiple of NC a group that starts below n ends inside its row; otherwise
-    // the last group of a row would run into the next row and, in the last row, past the matrix.  The pointer
-    // must be aligned to the load as well.
-    const uint64_t elem = feat_dtype == ECK_BF16 ? 2 : 4;
-    if ((ld & 1) || ((uintptr_t)feat & (2 * elem - 1))) return ECK_EALIGN;
-    // four candidate tiles per wavefront (half the weight traffic per candidate) where 256 or fewer hidden units
-    // leave the registers for it, the features arrive as bf16 and groups of four stay inside a row
-    const bool four = feat_dtype == ECK_BF16 && ld % 4 == 0 && ((uintptr_t)feat & 7) == 0;
-    if (F == 64 && H1 == 512 && H2 == 512) return launch_bf16<64, 512, 512, 2>(m, feat, feat_dtype, ld, n, score_out, st);
-    if (F == 64 && H1 == 256 && H2 == 256 && four)
-        return launch_bf16<64, 256, 256, 4>(m, feat, feat_dtype, ld, n, score_out, st);
-    if (F == 64 && H1 == 256 && H2 == 256) return launch_bf16<64, 256, 256, 2>(m, feat, feat_dtype, ld, n, score_out, st);
-    if (F == 64 && H1 == 128 && H2 == 128 && four)
-        return launch_bf16<64, 128, 128, 4>(m, feat, feat_dtype, ld, n, score_out, st);
-    if (F == 64 && H1 == 128 && H2 == 128) return launch_bf16<64, 128, 128, 2>(m, feat, feat_dtype, ld, n, score_out, st);
-    if (F == 32 && H1 == 64 && H2 == 64) return launch_bf16<32, 64, 64, 2>(m, feat, feat_dtype, ld, n, score_out, st);
-    return ECK_EUNSUPPORTED;
+    return score_any<false>(m, feat, feat_dtype, ld, n, score_out, MinArgs{nullptr, 1, nullptr, 0}, 0, stream);
+}
+
+extern "C" int32_t costmodel_score_min(const eck_model *m, const void *feat, int32_t feat_dtype, uint64_t ld, uint64_t n,
+                                       float *score_out, const uint8_t *legal, uint32_t n_segments, uint32_t *min_key_out,
+                                       void *stream)
+{
+    if (!min_key_out || n_segments == 0) return ECK_EINVAL;
+    if (n == 0 || n % n_segments) return n == 0 ? ECK_EINVAL : ECK_ESHAPE;
+    if (n / n_segments > 0xFFFFFFFEull || n_segments > 65535) return ECK_ESHAPE;
+    if (legal && ((uintptr_t)legal & 1)) return ECK_EALIGN; // two flags per load
+    return score_any<true>(m, feat, feat_dtype, ld, n, score_out, MinArgs{legal, n / n_segments, min_key_out, 0}, n_segments,
+                           stream);
 }

@@ -761,7 +761,7 @@ int32_t check_arguments(const float *energy, const float *latency, uint64_t n, u
 int32_t eck::topk_select_impl(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
                               uint32_t n_segments, uint32_t k, int32_t mode, float alpha, uint32_t m_latency,
                               uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws, uint64_t ws_bytes,
-                              void *stream)
+                              void *stream, const uint32_t *known_min)
 {
     bool stage_a;
     WsLayout w;
@@ -796,7 +796,11 @@ int32_t eck::topk_select_impl(const float *energy, const float *latency, const u
                      (!legal || ((uintptr_t)legal & 3) == 0);
     if (!latency) return run_tournament<PRED_PLAIN>(a, n_segments, vec, list_a, list_b, st);
     if (mode == ECK_SELECT_THRESHOLD) {
-        if (!a.alpha_inf) {
+        if (!a.alpha_inf && known_min) {
+            // L_min came with the call (one order key per segment)
+            a.lat_parts = known_min;
+            a.lat_parts_n = 1;
+        } else if (!a.alpha_inf) {
             // L_min first: one pass over the latencies, a slice of the segment per block
             uint64_t parts = (seg_len + 4095) / 4096;
             if (parts > LATMIN_PARTS) parts = LATMIN_PARTS;
@@ -833,7 +837,17 @@ extern "C" int32_t topk_select(const float *energy, const float *latency, const 
                                void *stream)
 {
     return topk_select_impl(energy, latency, legal, n, n_segments, k, mode, alpha, m_latency, idx_out, energy_out,
-                            count_out, ws, ws_bytes, stream);
+                            count_out, ws, ws_bytes, stream, nullptr);
+}
+
+extern "C" int32_t topk_select_known_min(const float *energy, const float *latency, const uint8_t *legal, uint64_t n,
+                                         uint32_t n_segments, uint32_t k, float alpha, const uint32_t *latency_min_key,
+                                         uint32_t *idx_out, float *energy_out, uint32_t *count_out, void *ws,
+                                         uint64_t ws_bytes, void *stream)
+{
+    if (!latency || !latency_min_key) return ECK_EINVAL;
+    return topk_select_impl(energy, latency, legal, n, n_segments, k, ECK_SELECT_THRESHOLD, alpha, 0, idx_out, energy_out,
+                            count_out, ws, ws_bytes, stream, latency_min_key);
 }
 
 // ---------------------------------------------------------------- the entry point that allocates nothing
@@ -879,5 +893,5 @@ extern "C" int32_t topk_select_static(const float *energy, const float *latency,
     // nothing in the workspace has to start at zero: every word a kernel reads was written by an earlier kernel of
     // the same call
     return topk_select_impl(energy, latency, legal, n, n_segments, k, mode, alpha, m_latency, idx_out, energy_out,
-                            count_out, ws, ECK_TOPK_STATIC_BYTES, stream);
+                            count_out, ws, ECK_TOPK_STATIC_BYTES, stream, nullptr);
 }

@@ -28,7 +28,8 @@ MAX_BATCH = 128
 EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_info", "eck_space_table",
            "candidate_enumerate", "candidate_enumerate_batch", "eck_candidates_gather", "features_compute",
            "features_compute_batch", "eck_model_create", "eck_model_destroy",
-           "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score",
+           "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score", "costmodel_score_min",
+           "topk_select_known_min",
            "topk_select_workspace_bytes", "topk_select_rank_workspace_bytes", "topk_select", "topk_select_static", "costmodel_update_workspace_bytes", "costmodel_update",
            "eck_trees_create", "eck_trees_destroy", "eck_trees_count", "eck_trees_set", "eck_trees_get",
            "treemodel_score", "treemodel_update_workspace_bytes", "treemodel_update", "eck_k_step", "eck_k_count",
@@ -83,6 +84,8 @@ def lib():
         L.eck_model_set_state.argtypes = [vp, vp, u64, vp]
         L.eck_model_get_state.argtypes = [vp, vp, u64, vp]
         L.costmodel_score.argtypes = [vp, vp, i32, u64, u64, vp, vp, u64, vp]
+        L.costmodel_score_min.argtypes = [vp, vp, i32, u64, u64, vp, vp, u32, vp, vp]
+        L.topk_select_known_min.argtypes = [vp, vp, vp, u64, u32, u32, f32, vp, vp, vp, vp, vp, u64, vp]
         L.eck_candidates_dedup_workspace_bytes.argtypes = [u64]
         L.eck_candidates_dedup_workspace_bytes.restype = u64
         L.eck_candidates_dedup.argtypes = [vp, u64, u64, i32, vp, i32, vp, u64, vp]
@@ -352,6 +355,37 @@ def costmodel_score(model, feat, n, score_out):
     assert score_out.numel() >= n
     _check("costmodel_score", lib().costmodel_score(model.h, _ptr(feat), feat_dtype, feat.shape[1], n,
                                                     _ptr(score_out), None, 0, _stream()))
+
+
+def costmodel_score_min(model, feat, n, score_out, legal, n_segments, min_key_out):
+    """costmodel_score plus the least score of the legal candidates of every segment (uint32 order keys)"""
+    feat_dtype = {torch.float32: F32, torch.bfloat16: BF16}[feat.dtype]
+    assert feat.is_cuda and feat.is_contiguous() and feat.shape[0] == model.widths[0]
+    _dev(score_out, torch.float32, "score_out")
+    assert score_out.numel() >= n
+    if legal is not None:
+        assert legal.is_cuda and legal.element_size() == 1 and legal.is_contiguous() and legal.numel() >= n
+    assert min_key_out.is_cuda and min_key_out.element_size() == 4 and min_key_out.numel() >= n_segments
+    _check("costmodel_score_min", lib().costmodel_score_min(model.h, _ptr(feat), feat_dtype, feat.shape[1], n,
+                                                            _ptr(score_out), _ptr(legal), n_segments, _ptr(min_key_out),
+                                                            _stream()))
+
+
+def topk_select_known_min(energy, latency, legal, n_segments, k, latency_min_key, idx_out, energy_out, count_out, ws,
+                          alpha=1.1):
+    """topk_select in THRESHOLD mode with the per-segment least latency from costmodel_score_min"""
+    _dev(energy, torch.float32, "energy")
+    _dev(latency, torch.float32, "latency")
+    if legal is not None:
+        assert legal.is_cuda and legal.element_size() == 1 and legal.is_contiguous()
+    assert latency_min_key.is_cuda and latency_min_key.element_size() == 4 and latency_min_key.numel() >= n_segments
+    assert idx_out.is_cuda and idx_out.element_size() == 4 and idx_out.numel() >= n_segments * k
+    _dev(energy_out, torch.float32, "energy_out")
+    assert count_out.is_cuda and count_out.element_size() == 4 and count_out.numel() >= n_segments
+    assert ws.is_cuda and ws.is_contiguous()
+    _check("topk_select_known_min", lib().topk_select_known_min(
+        _ptr(energy), _ptr(latency), _ptr(legal), energy.numel(), n_segments, k, alpha, _ptr(latency_min_key),
+        _ptr(idx_out), _ptr(energy_out), _ptr(count_out), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def topk_select_workspace_bytes(n, n_segments, k, m_latency=0):

@@ -171,6 +171,11 @@ def test_topk_validation_and_workspace():
     assert T(*args(1024, 1, 8, ws=None)) == eck.EWORKSPACE
     assert T(*args(1024, 1, 8, wsb=16)) == eck.EWORKSPACE
     assert T(*args(1024, 1, 8, ws=C.c_void_p(0x1008))) == eck.EALIGN
+    K = L.topk_select_known_min
+    assert K(FAKE, None, None, 1024, 1, 8, f(1.1), FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == eck.EINVAL
+    assert K(FAKE, FAKE, None, 1024, 1, 8, f(1.1), None, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == eck.EINVAL
+    assert K(FAKE, FAKE, None, 1000, 3, 8, f(1.1), FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == eck.ESHAPE
+    assert L.costmodel_score_min(None, FAKE, 0, 16, 16, FAKE, None, 1, FAKE, None) == eck.EINVAL
     need = L.topk_select_workspace_bytes(1 << 24, 64, 32)
     assert 0 < need < (8 << 20)
     assert L.topk_select_workspace_bytes(1000, 3, 8) == 0
