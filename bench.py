@@ -33,7 +33,7 @@ PEAK_HBM = 8e12
 
 # HBM bytes of one score launch on c5 as the counters saw them (FETCH_SIZE x calibration + WRITE_SIZE, rocprofv3 --pmc):
 # a constant of the profile named here, not a measurement of this run
-TRAFFIC = {"file": "profiles/c5_hbm_traffic_pmc.txt", "score_bf16_kernel<64,512,512>": 2.155e9 + 0.0692e9}
+TRAFFIC = {"file": "profiles/c5_hbm_traffic_pmc.txt", "score_bf16_kernel<64,512,512>": 2.167e9 + 0.0671e9}
 
 
 def cpu_baseline(cfg, sample_log2=18):
