@@ -150,6 +150,7 @@ struct Shared {
     uint64_t wave_bound[T / 64];
     uint32_t found_digit, found_below, found_count, cursor;
     uint32_t lat_min;
+    uint64_t any_composite; // radix select: one of the block's composites, to find the leading bits all of them share
 };
 
 // one compare-exchange step of a bitonic network over the 64 lanes of a wavefront
@@ -278,8 +279,31 @@ template <int T>
 __device__ uint64_t radix_threshold(const uint64_t (&c)[ITEMS], uint32_t k, uint32_t total_bits, Shared<T> &sh)
 {
     constexpr int PER = BINS / T; // consecutive bins per thread in the scan
-    uint64_t prefix = 0;
-    uint32_t remaining = k, top = total_bits;
+    // The leading bits that all composites of the block share select nothing: scores of one segment lie in a narrow
+    // range, so without this the first digit (sign, exponent, two mantissa bits) sends every composite to a
+    // handful of bins, whose LDS atomics serialise, and a pass is spent on it.
+    uint64_t mine = NONE;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) mine = c[j] != NONE ? c[j] : mine;
+    __syncthreads(); // the words used below may still be read from what came before
+    if (mine != NONE) sh.any_composite = mine; // whichever thread's store lands last
+    __syncthreads();
+    const uint64_t ref = sh.any_composite;
+    uint64_t differ = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) differ |= c[j] != NONE ? c[j] ^ ref : 0;
+#pragma unroll
+    for (uint32_t stride = 32; stride > 0; stride >>= 1) differ |= lane_exchange<uint64_t>(differ, stride);
+    if ((threadIdx.x & 63) == 0) sh.wave_bound[threadIdx.x >> 6] = differ;
+    __syncthreads();
+    differ = 0;
+#pragma unroll
+    for (int w = 0; w < T / 64; ++w) differ |= sh.wave_bound[w];
+    if (differ == 0) return ref; // a single composite
+    uint32_t top = 64 - (uint32_t)__clzll((long long)differ);
+    top = top < total_bits ? top : total_bits;
+    uint64_t prefix = top < 64 ? (ref >> top) << top : 0;
+    uint32_t remaining = k;
     for (;;) {
         const uint32_t bits = top < (uint32_t)DIGIT_BITS ? top : (uint32_t)DIGIT_BITS;
         const uint32_t shift = top - bits, mask = (1u << bits) - 1;
@@ -355,6 +379,33 @@ __device__ uint32_t select_kept(const uint64_t (&c)[ITEMS], uint32_t kept, bool 
     return n;
 }
 
+// Number of the block's candidates c[j] != NONE when no bound is applied (k > SMALL: at least k candidates survive
+// any bound, so the direct ranking only applies when the block has few candidates to begin with): per-thread
+// counts, added within the wavefront, one LDS atomic per wavefront.  With SMALL or fewer the candidates are
+// compacted into the pool for the direct ranking after all.  sh.cursor must have been set to zero.
+template <int T>
+__device__ __forceinline__ uint32_t count_candidates(const uint64_t (&c)[ITEMS], Shared<T> &sh)
+{
+    uint32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j) mine += c[j] != NONE;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine += (uint32_t)__shfl_xor((int)mine, off);
+    __syncthreads(); // the cursor's zero is in place
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&sh.cursor, mine);
+    __syncthreads();
+    const uint32_t kept = sh.cursor;
+    if (kept > SMALL) return kept;
+    __syncthreads();
+    if (threadIdx.x == 0) sh.cursor = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j)
+        if (c[j] != NONE) sh.small.pool[atomicAdd(&sh.cursor, 1u)] = c[j];
+    __syncthreads();
+    return kept;
+}
+
 // The block's share of a list of composites (the selections of the level before): held in c, bounded, the
 // survivors compacted into the pool.
 template <int T>
@@ -365,6 +416,17 @@ __device__ __forceinline__ void gather_list(const uint64_t *in, uint64_t list_le
     // that ranked their selection are ascending, so the least entries of the threads are spread over the lists'
     // quantiles and the bound comes out tight
     const uint64_t share = list_len - start < (uint64_t)(T * ITEMS) ? list_len - start : (uint64_t)(T * ITEMS);
+    if (k > SMALL) {
+        // no bound can leave few enough for the direct ranking: plain coalesced loads, everything kept
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const uint64_t i = (uint64_t)j * T + threadIdx.x;
+            c[j] = i < share ? in[start + i] : NONE;
+        }
+        *bounded = false;
+        *kept = count_candidates<T>(c, sh);
+        return;
+    }
     const uint32_t per_thread = (uint32_t)((share + T - 1) / T); // <= ITEMS
     uint64_t least = NONE;
 #pragma unroll
@@ -497,6 +559,13 @@ __device__ __forceinline__ void gather_scores(const SelectArgs &a, uint32_t s, S
             key[j] = v;
         }
     }
+    if (a.k > SMALL) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) c[j] = key[j] != NO_KEY ? ((uint64_t)key[j] << a.idx_bits) | index_of(j) : NONE;
+        *bounded = false;
+        *kept = count_candidates<T>(c, sh);
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < ITEMS; ++j) least = min(least, key[j]);
     const uint32_t bound = block_bound<T, uint32_t>(least, a.k, NO_KEY, sh);
@@ -550,42 +619,67 @@ __device__ __forceinline__ void select_and_emit(const SelectArgs &a, uint32_t s,
         return;
     }
     // last level: the selection in ascending order, then unpack
-    const uint64_t *sorted = sh.small.ranked;
-    if (!ranked) {
-        // bitonic sort of the selection (padded to a power of two with NONE)
-        uint32_t pow2 = 2;
-        while (pow2 < a.k) pow2 <<= 1;
-        for (uint32_t i = threadIdx.x; i < pow2; i += T) sort_buf[i] = NONE;
-        if (threadIdx.x == 0) sh.cursor = 0;
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j)
-            if (c[j] <= thr) sort_buf[atomicAdd(&sh.cursor, 1u)] = c[j];
-        __syncthreads();
-        for (uint32_t size = 2; size <= pow2; size <<= 1)
-            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-                for (uint32_t t = threadIdx.x; t < pow2 / 2; t += T) {
-                    const uint32_t lo = 2 * t - (t & (stride - 1)); // index with the `stride` bit clear
-                    const uint32_t hi = lo + stride;
-                    const bool ascending = (lo & size) == 0;
-                    const uint64_t x = sort_buf[lo], y = sort_buf[hi];
-                    if ((x > y) == ascending) {
-                        sort_buf[lo] = y;
-                        sort_buf[hi] = x;
-                    }
-                }
-                __syncthreads();
-            }
-        sorted = sort_buf;
-    }
     const uint64_t idx_mask = (1ull << a.idx_bits) - 1;
-    for (uint32_t i = threadIdx.x; i < a.k; i += T) {
+    auto emit = [&](uint32_t i, uint64_t v) {
         const bool valid = i < n_selected;
-        const uint64_t v = valid ? sorted[i] : 0;
         a.idx_out[(uint64_t)s * a.k + i] = valid ? (uint32_t)(v & idx_mask) : 0xFFFFFFFFu;
         a.energy_out[(uint64_t)s * a.k + i] = valid ? key_to_float((uint32_t)(v >> a.idx_bits)) : __builtin_inff();
-    }
+    };
     if (threadIdx.x == 0) a.count_out[s] = n_selected;
+    if (ranked) {
+        for (uint32_t i = threadIdx.x; i < a.k; i += T) emit(i, i < n_selected ? sh.small.ranked[i] : 0);
+        return;
+    }
+    // bitonic sort of the selection (padded to a power of two with NONE)
+    uint32_t pow2 = 2;
+    while (pow2 < a.k) pow2 <<= 1;
+    for (uint32_t i = threadIdx.x; i < pow2; i += T) sort_buf[i] = NONE;
+    if (threadIdx.x == 0) sh.cursor = 0;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < ITEMS; ++j)
+        if (c[j] <= thr) sort_buf[atomicAdd(&sh.cursor, 1u)] = c[j];
+    __syncthreads();
+    if (pow2 <= (uint32_t)T) {
+        // one element per thread: steps whose partner sits in the same wavefront exchange registers, only the
+        // wider ones go through LDS (10 of the 55 steps for 1024 elements)
+        const uint32_t i = threadIdx.x;
+        uint64_t v = i < pow2 ? sort_buf[i] : NONE;
+        for (uint32_t size = 2; size <= pow2; size <<= 1) {
+            const bool ascending = (i & size) == 0;
+            for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+                uint64_t other;
+                if (stride < 64) {
+                    other = lane_exchange<uint64_t>(v, stride);
+                } else {
+                    __syncthreads(); // the reads of the step before are done
+                    if (i < pow2) sort_buf[i] = v;
+                    __syncthreads();
+                    other = i < pow2 ? sort_buf[i ^ stride] : NONE;
+                }
+                const bool lower = (i & stride) == 0; // this thread keeps the smaller one of an ascending pair
+                const uint64_t lo = v < other ? v : other, hi = v < other ? other : v;
+                v = (lower == ascending) ? lo : hi;
+            }
+        }
+        if (i < a.k) emit(i, v);
+        return;
+    }
+    for (uint32_t size = 2; size <= pow2; size <<= 1)
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            for (uint32_t t = threadIdx.x; t < pow2 / 2; t += T) {
+                const uint32_t lo = 2 * t - (t & (stride - 1)); // index with the `stride` bit clear
+                const uint32_t hi = lo + stride;
+                const bool ascending = (lo & size) == 0;
+                const uint64_t x = sort_buf[lo], y = sort_buf[hi];
+                if ((x > y) == ascending) {
+                    sort_buf[lo] = y;
+                    sort_buf[hi] = x;
+                }
+            }
+            __syncthreads();
+        }
+    for (uint32_t i = threadIdx.x; i < a.k; i += T) emit(i, i < n_selected ? sort_buf[i] : 0);
 }
 
 // One block = T threads x ITEMS candidates of segment blockIdx.y: a chunk of the score arrays, or the same number
