@@ -43,12 +43,15 @@
  * a hand-worked ensemble, the closed-form weighted means of a one-split fit,
  * brute-force search of the best split, a library regression tree on the same
  * weighted problem, monotone training loss.
- * Reduction-parallel schedules (space kind SPLIT_XRED): a matrix-vector
- * schedule worked by hand and a walker that executes tiny loop nests literally
- * and counts operations, operand elements and tree steps.
- * parity unpinned: feature 20 (shared-load element count) -- Table 5's
- * shared_ld column is not reproduced by any simple register-tile formula; and
- * the 100-step bf16 update trajectory (checked statistically only).
+ * Staged schedules (SPLIT) and reduction-parallel schedules (SPLIT_XRED): a
+ * schedule of each kind worked by hand and, for each kind, a walker that
+ * executes tiny loop nests literally and counts operations, staged and
+ * per-step operand elements and tree steps; feature 20 (shared-load element
+ * count) is pinned that way, against the loop nest it is read from -- Table 5's
+ * shared_ld column depends on a thread layout the paper does not print and is
+ * not reproduced.
+ * parity unpinned: the 100-step bf16 update trajectory weight for weight
+ * (checked statistically only).
  *
  * Floating point: scores and the update run in fp64 on the fp32/bf16 values
  * handed in.  Integer parts are exact.
