@@ -165,7 +165,8 @@ def test_config4_rescoring_after_the_update(G):
 
 @pytest.fixture(scope="module")
 def c5(G):
-    """The benchmark's step on the benchmark's buffers: two batched launches, two score launches, one selection."""
+    """The benchmark's step on the benchmark's buffers and through the benchmark's calls: two batched launches, the two
+    score launches (the second with the per-shape least latency), the selection on known minima."""
     cfg = synth.CONFIGS["c5"]
     shapes, per, widths, K = cfg["shapes"], cfg["n_per_shape"], cfg["widths"], cfg["k"]
     S, N = len(shapes), len(shapes) * cfg["n_per_shape"]
@@ -179,8 +180,28 @@ def c5(G):
     energy = torch.zeros(N, dtype=torch.float32, device="cuda")
     latency = torch.zeros(N, dtype=torch.float32, device="cuda")
     eck.costmodel_score(G.make_model(widths, eck.BF16, thetas[0]), feat, N, energy)
-    eck.costmodel_score(G.make_model(widths, eck.BF16, thetas[1]), feat, N, latency)
+    # as the benchmark runs it: the latency launch also reduces its scores to the least legal latency of every shape,
+    # and the selection takes those minima instead of a pass of its own over the latencies
+    m_latency = G.make_model(widths, eck.BF16, thetas[1])
+    lat_min = torch.zeros(S, dtype=torch.int32, device="cuda")
+    eck.costmodel_score_min(m_latency, feat, N, latency, legal, S, lat_min)
+    idx_b = torch.zeros((S, K), dtype=torch.int32, device="cuda")
+    e_b = torch.zeros((S, K), dtype=torch.float32, device="cuda")
+    cnt_b = torch.zeros(S, dtype=torch.int32, device="cuda")
+    ws = torch.empty(eck.topk_select_workspace_bytes(N, S, K), dtype=torch.uint8, device="cuda")
+    eck.topk_select_known_min(energy, latency, legal, S, K, lat_min, idx_b, e_b, cnt_b, ws, alpha=cfg["alpha"])
+    # the same latencies, bit for bit, as the plain scoring call; the minima as numpy finds them; the same selection
+    # as the oracle's (and as topk_select's own two passes)
+    plain = torch.zeros(N, dtype=torch.float32, device="cuda")
+    eck.costmodel_score(m_latency, feat, N, plain)
+    assert torch.equal(plain.view(torch.int32), latency.view(torch.int32))
+    del plain
+    bits = latency.cpu().numpy().view(np.uint32)
+    keys = np.where(bits >> 31 != 0, ~bits, bits | np.uint32(0x80000000)).astype(np.uint32)
+    keys[(legal.cpu().numpy() == 0) | np.isnan(latency.cpu().numpy())] = 0xFFFFFFFF
+    assert np.array_equal(lat_min.cpu().numpy().view(np.uint32), keys.reshape(S, per).min(axis=1))
     idx, cnt = _select_and_check(G, energy, latency, legal, S, K, cfg["alpha"])
+    assert np.array_equal(idx_b.cpu().numpy().view(np.uint32), idx) and np.array_equal(cnt_b.cpu().numpy().view(np.uint32), cnt)
     assert cnt.min() > 0
     # the columns whose scores are checked: 2^18 strided candidates, every selected candidate, and every feasible
     # candidate whose energy lies within 1 % of its segment's k-th selected energy (the ones a scoring error
