@@ -607,7 +607,8 @@ __device__ __forceinline__ uint64_t floor_div_f64(uint64_t a, uint64_t b)
 // benchmark workload (the tables are staged once per 1024 candidates and a block writes 2 KB of every row).
 constexpr uint32_t kFeatBlock = 1024;
 
-template <int OUT_DTYPE, bool TABLES_IN_LDS, int N_FEAT, bool WANT_RAW, bool XRED>
+// WANT_X: the transformed features are wanted (feat_out is not NULL; without them OUT_DTYPE means nothing).
+template <int OUT_DTYPE, bool TABLES_IN_LDS, int N_FEAT, bool WANT_RAW, bool XRED, bool WANT_X>
 __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces, const uint16_t *__restrict__ genes,
                                                        uint64_t ld, uint64_t n, void *__restrict__ feat_out,
                                                        uint64_t *__restrict__ raw_out,
@@ -710,11 +711,27 @@ __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces,
     // bfloat16 output: features come in order, an even one waits for its odd neighbour, one instruction converts
     // both (round to nearest even) and the two halves go to their rows
     float held = 0.0f;
+    // Features are emitted below in increasing order, each exactly once, so the address of a row is the address of
+    // the row before plus the row stride: two scalar additions per row.  (Computed as f * ld + column for every
+    // store, the 64-bit products and sums were most of the kernel's 562 scalar instructions, and scalar and vector
+    // instructions of one wavefront do not issue together.)  The empty asm keeps the compiler from folding the
+    // chain of additions back into products.
+    typedef __attribute__((address_space(1))) unsigned char global_byte;
+    const uint64_t feat_stride = ld * (OUT_DTYPE == ECK_F32 ? 4 : 2);
+    uint64_t feat_row = reinterpret_cast<uint64_t>(feat_out) + block_col * (OUT_DTYPE == ECK_F32 ? 4 : 2);
+    uint64_t raw_row = reinterpret_cast<uint64_t>(raw_out) + block_col * 8;
+    const uint32_t lane_x = threadIdx.x * (OUT_DTYPE == ECK_F32 ? 4 : 2), lane_raw = threadIdx.x * 8;
+    auto next_row = [&](uint64_t &row, uint64_t stride) {
+        row += stride;
+        asm volatile("" : "+s"(row));
+    };
+    // (a scalar base plus a 32-bit lane offset: the store's address costs no vector instruction)
+    auto at = [&](uint64_t row, uint32_t lane_bytes) { return reinterpret_cast<global_byte *>(row) + lane_bytes; };
     auto store_x = [&](int f, float x) {
-        if (!feat_out) return;
-        const uint64_t row = (uint64_t)f * ld + block_col;
+        if (!WANT_X) return;
         if (OUT_DTYPE == ECK_F32) {
-            (reinterpret_cast<float *>(feat_out) + row)[threadIdx.x] = x;
+            *reinterpret_cast<__attribute__((address_space(1))) float *>(at(feat_row, lane_x)) = x;
+            next_row(feat_row, feat_stride);
         } else if (!(f & 1)) {
             held = x;
         } else {
@@ -722,12 +739,18 @@ __global__ __launch_bounds__(kFeatBlock) void features_kernel(SpaceBatch spaces,
             typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
             const float2_t both = {held, x};
             const uint32_t packed = __builtin_bit_cast(uint32_t, __builtin_convertvector(both, bf16x2_t));
-            (reinterpret_cast<uint16_t *>(feat_out) + (row - ld))[threadIdx.x] = (uint16_t)packed;
-            (reinterpret_cast<uint16_t *>(feat_out) + row)[threadIdx.x] = (uint16_t)(packed >> 16);
+            *reinterpret_cast<__attribute__((address_space(1))) uint16_t *>(at(feat_row, lane_x)) = (uint16_t)packed;
+            next_row(feat_row, feat_stride);
+            *reinterpret_cast<__attribute__((address_space(1))) uint16_t *>(at(feat_row, lane_x)) = (uint16_t)(packed >> 16);
+            next_row(feat_row, feat_stride);
         }
     };
     auto store_raw = [&](int f, uint64_t raw) {
-        if (WANT_RAW) (raw_out + ((uint64_t)f * ld + block_col))[threadIdx.x] = raw;
+        (void)f;
+        if (WANT_RAW) {
+            *reinterpret_cast<__attribute__((address_space(1))) uint64_t *>(at(raw_row, lane_raw)) = raw;
+            next_row(raw_row, ld * 8);
+        }
     };
     auto emit_const = [&](int f, int slot, uint64_t raw) {
         if (f >= N_FEAT) return;
@@ -951,9 +974,15 @@ int32_t features_launch(const eck_space *const *spaces, uint32_t n_spaces, const
     const dim3 block(kFeatBlock), grid((unsigned)((n + kFeatBlock - 1) / kFeatBlock), n_spaces);
     hipStream_t st = as_stream(stream);
     const bool raw = raw_out != nullptr;
-#define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW, XR)                                                                \
-    hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW, XR>), grid, block, lds, st, batch, genes, ld, n, feat_out, \
-                       raw_out, legal_out, spaces[0]->prm.n_genes)
+#define ECK_LAUNCH_FEATURES(DT, INLDS, NF, RAW, XR)                                                                 \
+    do {                                                                                                           \
+        if (feat_out)                                                                                              \
+            hipLaunchKernelGGL((features_kernel<DT, INLDS, NF, RAW, XR, true>), grid, block, lds, st, batch, genes, ld, \
+                               n, feat_out, raw_out, legal_out, spaces[0]->prm.n_genes);                           \
+        else                                                                                                       \
+            hipLaunchKernelGGL((features_kernel<ECK_F32, INLDS, NF, RAW, XR, false>), grid, block, lds, st, batch,   \
+                               genes, ld, n, feat_out, raw_out, legal_out, spaces[0]->prm.n_genes);                \
+    } while (0)
 #define ECK_PICK_RAW(DT, INLDS, NF)                    \
     do {                                               \
         if (raw && xred) ECK_LAUNCH_FEATURES(DT, INLDS, NF, true, true);        \
