@@ -285,6 +285,52 @@ __global__ __launch_bounds__(256) void score_f32_kernel(const float *__restrict_
     }
 }
 
+// The same network with four consecutive units per thread and pass (hidden widths that are multiples of four): one
+// activation read and one 16-byte weight load feed four multiply-adds, a quarter of the loads per multiply-add.  Every
+// output is still the same in-order chain, so the scores are the bits the kernel above gives.
+__global__ __launch_bounds__(256) void score_f32x4_kernel(const float *__restrict__ theta, int F, int H1, int H2,
+                                                          uint64_t off_w1, uint64_t off_b1, uint64_t off_w2,
+                                                          uint64_t off_b2, uint64_t off_w3, uint64_t off_b3,
+                                                          const float *__restrict__ feat, uint64_t ld, uint64_t n,
+                                                          float *__restrict__ out)
+{
+    extern __shared__ float act[];
+    float *a0 = act, *a1 = a0 + F * F32_TILE, *a2 = a1 + H1 * F32_TILE;
+    const int c = threadIdx.x & 31, ug = threadIdx.x >> 5;
+    const uint64_t cand = (uint64_t)blockIdx.x * F32_TILE + c;
+    for (int i = ug; i < F; i += 8) a0[i * F32_TILE + c] = cand < n ? feat[(uint64_t)i * ld + cand] : 0.0f;
+    __syncthreads();
+    auto layer = [&](const float *in, float *res, int K, int H, uint64_t off_w, uint64_t off_b) {
+        for (int j = 4 * ug; j < H; j += 32) {
+            float4 acc = *reinterpret_cast<const float4 *>(theta + off_b + j);
+            const float *w = theta + off_w + j;
+#pragma unroll 8
+            for (int i = 0; i < K; ++i) {
+                const float a = in[i * F32_TILE + c];
+                const float4 wv = *reinterpret_cast<const float4 *>(w + (uint64_t)i * H);
+                acc.x = fmaf(a, wv.x, acc.x);
+                acc.y = fmaf(a, wv.y, acc.y);
+                acc.z = fmaf(a, wv.z, acc.z);
+                acc.w = fmaf(a, wv.w, acc.w);
+            }
+            res[(j + 0) * F32_TILE + c] = fmaxf(acc.x, 0.0f);
+            res[(j + 1) * F32_TILE + c] = fmaxf(acc.y, 0.0f);
+            res[(j + 2) * F32_TILE + c] = fmaxf(acc.z, 0.0f);
+            res[(j + 3) * F32_TILE + c] = fmaxf(acc.w, 0.0f);
+        }
+    };
+    layer(a0, a1, F, H1, off_w1, off_b1);
+    __syncthreads();
+    layer(a1, a2, H1, H2, off_w2, off_b2);
+    __syncthreads();
+    if (ug == 0 && cand < n) {
+        float acc = theta[off_b3];
+#pragma unroll 8
+        for (int i = 0; i < H2; ++i) acc = fmaf(a2[i * F32_TILE + c], theta[off_w3 + i], acc);
+        out[cand] = acc;
+    }
+}
+
 // ------------------------------------------------------------ bf16 forward
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -890,9 +936,19 @@ int32_t score_any(const eck_model *m, const void *feat, int32_t feat_dtype, uint
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         const uint64_t blocks = (n + F32_TILE - 1) / F32_TILE;
         if (blocks > 0x7FFFFFFFull) return ECK_EUNSUPPORTED;
-        hipLaunchKernelGGL(score_f32_kernel, dim3((unsigned)blocks), dim3(256), lds, st, m->d_state, F, H1, H2,
-                           m->off_w[0], m->off_b[0], m->off_w[1], m->off_b[1], m->off_w[2], m->off_b[2], (const float *)feat,
-                           ld, n, score_out);
+        // (parameter offsets are then multiples of four floats as well, and the state is 256-byte aligned)
+        const bool by_four = H1 % 4 == 0 && H2 % 4 == 0;
+        if (by_four) {
+            ECK_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(score_f32x4_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            hipLaunchKernelGGL(score_f32x4_kernel, dim3((unsigned)blocks), dim3(256), lds, st, m->d_state, F, H1, H2,
+                               m->off_w[0], m->off_b[0], m->off_w[1], m->off_b[1], m->off_w[2], m->off_b[2],
+                               (const float *)feat, ld, n, score_out);
+        } else {
+            hipLaunchKernelGGL(score_f32_kernel, dim3((unsigned)blocks), dim3(256), lds, st, m->d_state, F, H1, H2,
+                               m->off_w[0], m->off_b[0], m->off_w[1], m->off_b[1], m->off_w[2], m->off_b[2],
+                               (const float *)feat, ld, n, score_out);
+        }
         if (WITH_MIN)
             hipLaunchKernelGGL(min_key_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, score_out, mn.legal, n,
                                mn.seg_len, mn.min_key);

@@ -57,6 +57,19 @@ def test_fp32_model_wide_and_ragged(G):
     assert G.within(got, want, oracle.score_magnitude(widths, theta, f32, n=n), 1e-5) <= 1.0
 
 
+@pytest.mark.parametrize("widths", [[32, 50, 30, 1], [32, 52, 36, 1], [64, 7, 1, 1], [64, 512, 4, 1]])
+def test_fp32_model_widths_with_and_without_four_units_per_thread(G, widths):
+    """hidden widths that are multiples of four take the kernel with four units per thread, others the plain one"""
+    n = 1000 + 37
+    f32, _ = _features("c1" if widths[0] == 32 else "c2", n + 1, widths[0])
+    theta = synth.mlp_theta(widths, 6, bias_scale=0.4)
+    model = G.make_model(widths, eck.F32, theta)
+    got = G.score_gpu(model, G.to_dev(f32), n)
+    want = oracle.score(widths, theta, f32, n=n)
+    assert np.isfinite(got).all()
+    assert G.within(got, want, oracle.score_magnitude(widths, theta, f32, n=n), 1e-5) <= 1.0
+
+
 @pytest.mark.parametrize("widths,cfg,n", [([64, 256, 256, 1], "c2", 5000), ([64, 512, 512, 1], None, 4133),
                                           ([64, 128, 128, 1], "c3", 1500), ([32, 64, 64, 1], "c1", 6400)])
 def test_bf16_model(G, widths, cfg, n):
