@@ -111,6 +111,14 @@ typedef struct eck_model eck_model; /* cost model: fp32 master weights, Adam mom
  * ECK_EUNSUPPORTED (KNOB space on a convolution, limits above exceeded). */
 int32_t eck_space_create(const eck_problem *problem, int32_t kind, eck_space **out);
 
+/* Makes the device copy of the space's parameters and tables now, on the
+ * current device, instead of inside the first call that launches a kernel: one
+ * hipMalloc and one synchronous host-to-device copy (at most a few hundred KB).
+ * For callers that must not allocate or synchronise later on -- code under HIP
+ * graph capture, timed loops.  Does nothing when the copy exists already.
+ * Errors: ECK_EINVAL (null), ECK_EDEVICE. */
+int32_t eck_space_upload(eck_space *space);
+
 /* Frees host tables and the device copy (synchronises the device first). NULL is ignored. */
 void eck_space_destroy(eck_space *space);
 

@@ -223,6 +223,12 @@ extern "C" int32_t eck_space_create(const eck_problem *pb, int32_t kind, eck_spa
     return ECK_OK;
 }
 
+extern "C" int32_t eck_space_upload(eck_space *sp)
+{
+    if (!sp) return ECK_EINVAL;
+    return ensure_device_copy(sp);
+}
+
 extern "C" void eck_space_destroy(eck_space *sp)
 {
     if (!sp) return;

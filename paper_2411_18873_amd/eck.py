@@ -25,7 +25,7 @@ SELECT_THRESHOLD, SELECT_RANK = 0, 1
 MAX_K = 4096
 MAX_BATCH = 128
 
-EXPORTS = ["eck_version", "eck_space_create", "eck_space_destroy", "eck_space_info", "eck_space_table",
+EXPORTS = ["eck_version", "eck_space_create", "eck_space_upload", "eck_space_destroy", "eck_space_info", "eck_space_table",
            "candidate_enumerate", "candidate_enumerate_batch", "eck_candidates_gather", "features_compute",
            "features_compute_batch", "eck_model_create", "eck_model_destroy",
            "eck_model_param_count", "eck_model_set_state", "eck_model_get_state", "costmodel_score", "costmodel_score_min",
@@ -68,6 +68,7 @@ def lib():
         u64, u32, i32, vp, f32 = C.c_uint64, C.c_uint32, C.c_int32, C.c_void_p, C.c_float
         L.eck_version.restype = i32
         L.eck_space_create.argtypes = [C.POINTER(Problem), i32, C.POINTER(vp)]
+        L.eck_space_upload.argtypes = [vp]
         L.eck_space_destroy.argtypes = [vp]
         L.eck_space_destroy.restype = None
         L.eck_space_info.argtypes = [vp, C.POINTER(i32), C.POINTER(u32), C.POINTER(u64)]
@@ -163,6 +164,11 @@ class Space:
         buf = (C.c_uint32 * (4 * n))()
         lib().eck_space_table(self.h, gene, buf, n)
         return [tuple(buf[4 * i:4 * i + 4]) for i in range(n)]
+
+    def upload(self):
+        """make the device copy of the tables now (otherwise the first launch on the space does)"""
+        _check("eck_space_upload", lib().eck_space_upload(self.h))
+        return self
 
     def close(self):
         if getattr(self, "h", None) and _lib is not None:

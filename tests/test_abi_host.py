@@ -77,6 +77,7 @@ def test_space_create_rejects_bad_problems():
     assert _rc_space(synth.gemm(70000, 8, 8), eck.SPACE_SPLIT) == eck.EUNSUPPORTED
     assert _rc_space(synth.conv2d(1, 8, 8, 2, 2, 3, 3, 1, 0), eck.SPACE_SPLIT) == eck.EINVAL  # kernel larger than image
     assert eck.lib().eck_space_create(None, 0, None) == eck.EINVAL
+    assert eck.lib().eck_space_upload(None) == eck.EINVAL
 
 
 FAKE = C.c_void_p(0x1000)  # never dereferenced: every call below must fail validation first
