@@ -751,15 +751,26 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                 for (int c = 0; c < NC; ++c)
                     acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % RING], h1[c][HALF * KSP + ks],
                                                                      (HALF == 0 && ks == 0) ? bias_c : acc[c], 0, 0, 0);
-                if (HAS_PREV && ks >= EPI_FIRST && ks < EPI_FIRST + 8) {
-                    const int j = ks - EPI_FIRST, q = 8 * HALF + j;
+                if (HAS_PREV) {
+                    // Pieces of 16 k-steps: one output-layer step in each of eight k-steps in the middle.  Shorter
+                    // pieces: the eight steps spread over the k-steps after the first, which leaves the first for
+                    // the weight vector requested above to arrive (a step in k-step 0 stalled the wavefront, and
+                    // with it the matrix pipe, for an LDS round trip per piece).
+                    constexpr int SPREAD = KSP > 1 ? KSP - 1 : 1;
+                    const int first_step = KSP >= 16 ? ks - EPI_FIRST : (ks >= 1 ? 8 * (ks - 1) / SPREAD : 0);
+                    const int end_step = KSP >= 16 ? ks - EPI_FIRST + 1 : (ks >= 1 ? 8 * ks / SPREAD : 0);
 #pragma unroll
-                    for (int c = 0; c < NC; ++c) {
-                        y[c] = fmaf(relu(prev[c][q]), wprev[j >> 2][j & 3], y[c]);
-                        // an empty statement that "uses" the sum: without it the compiler gathers the output
-                        // terms of several chunks into one stretch of vector work that no matrix
-                        // instruction overlaps
-                        asm volatile("" : "+v"(y[c]));
+                    for (int j = 0; j < 8; ++j) {
+                        if (j < first_step || j >= end_step) continue;
+                        const int q = 8 * HALF + j;
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) {
+                            y[c] = fmaf(relu(prev[c][q]), wprev[j >> 2][j & 3], y[c]);
+                            // an empty statement that "uses" the sum: without it the compiler gathers the output
+                            // terms of several chunks into one stretch of vector work that no matrix
+                            // instruction overlaps
+                            asm volatile("" : "+v"(y[c]));
+                        }
                     }
                 }
                 // the next chunk's bias, once the output-layer steps are through (its registers are free
@@ -768,9 +779,10 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                     bias_c = bias_fragment(oc + 1 < OC2 ? oc + 1 : oc);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (HAS_PREV && KSP < 8) {
+            if (HAS_PREV && KSP == 1) {
+                // (a piece of one k-step has no k-step after the first)
 #pragma unroll
-                for (int j = KSP; j < 8; ++j)
+                for (int j = 0; j < 8; ++j)
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
                         y[c] = fmaf(relu(prev[c][8 * HALF + j]), wprev[j >> 2][j & 3], y[c]);
