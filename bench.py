@@ -15,7 +15,7 @@ Everything is resident in HBM before the timed region.  Prints ONE JSON line: th
 the c5 step (ms_per_step = the median of the timed steps), `roofline` for the score kernel,
 `hbm` for the calls that only move data (features; top-k for alpha = 1.1, for alpha = inf and, for
 comparison, for alpha = 1.1 when the selection has to find the least latencies itself),
-`other_configs` (configs 1-4, each timed after the c5 region) and `cpu_baseline` (the oracle).
+`other_configs` (configs 1-4, each timed after the c5 region) and `cpu_baseline` (the oracle on 2^20 candidates).
 """
 import argparse
 import json
@@ -36,7 +36,7 @@ PEAK_HBM = 8e12
 TRAFFIC = {"file": "profiles/c5_hbm_traffic_pmc.txt", "score_bf16_kernel<64,512,512>": 2.167e9 + 0.0671e9}
 
 
-def cpu_baseline(cfg, sample_log2=18):
+def cpu_baseline(cfg, sample_log2=20):
     """The oracle, as it stands, on a bounded sample of the same workload: one shape, 2^sample_log2
     candidates through enumerate -> features -> two scores -> top-k, plus the same 4-step update."""
     import numpy as np
@@ -259,7 +259,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
-    ap.add_argument("--cpu-sample-log2", type=int, default=18)
+    ap.add_argument("--cpu-sample-log2", type=int, default=20)
     ap.add_argument("--only", choices=["enumerate", "features", "score", "score_min", "topk", "topk_two_pass", "topk_inf", "update", "treescore",
                                        "treeupdate", "search", "others"],
                     default=None,
