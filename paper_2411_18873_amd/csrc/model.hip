@@ -477,17 +477,12 @@ __device__ __forceinline__ void lds_dma_kb(const unsigned char *uniform_base, ui
 }
 
 // wait until only the operations issued after the fetch in question may still be outstanding:
-// one later piece fetch (N_DMA loads) and / or the NX feature loads of the next tile
+// one later piece fetch (N_DMA loads) and / or NX feature loads of the next tile
 template <int N_DMA, int NX>
-__device__ __forceinline__ void wait_vm(bool dma_after, bool x_after)
+__device__ __forceinline__ void wait_vm(bool dma_after)
 {
-    if (dma_after) {
-        if (x_after) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_DMA + NX) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_DMA) : "memory");
-    } else {
-        if (x_after) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NX) : "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
+    if (dma_after) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_DMA + NX) : "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NX) : "memory");
 }
 
 // WITH_MIN: the kernel also reduces its scores to the least one per segment of seg_len candidates, over the legal
@@ -523,6 +518,18 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     constexpr int PF = RING - 1;                     // LDS read-ahead in k-steps
     constexpr int N_DMA = KSP / 4 > 0 ? KSP / 4 : 1; // 1 KB fetches per wavefront per piece
     constexpr uint32_t W1_BYTES = F * H1 * 2, W1B_BYTES = H1 * 4, PIECE_BYTES = KSP * 1024;
+    // The feature loads of the next tile.  Issued in one burst they fill the load path, and the wavefront -- and with
+    // it the matrix pipe -- stands still until the first of them are through (2 300 cycles of a 47 000-cycle tile at
+    // 512 units); one at a time, a few k-steps apart, they cost nothing.  So where registers allow (two candidate
+    // tiles per wavefront; with four, one more live value spills) they are spread over pieces 1 .. XSPAN, load i in
+    // piece 1 + i * XSPAN / NXLOADS.  The waits on the load counter depend on how many loads the two pieces before
+    // issued, so those pieces have their index known at compile time: the head of the tile and the first PEEL
+    // iterations of the loop over output chunks, written out.
+    constexpr int LOOP_ITERS = (OC2 - 2) / 2;
+    constexpr int PEEL = NC == 2 ? (LOOP_ITERS < 2 ? LOOP_ITERS : 2) : 0;
+    constexpr int XSPAN_FREE = PEEL == LOOP_ITERS ? PIECES - 4 : 4 * PEEL - 1;
+    constexpr int XSPAN = XSPAN_FREE < 1 ? 1 : (XSPAN_FREE > NXLOADS ? NXLOADS : XSPAN_FREE);
+    static_assert(XSPAN + 2 < PIECES || (XSPAN == 1 && PIECES == 4), "the last two pieces of a tile issue no feature loads");
     static_assert(KS2 % 2 == 0 && KSP % RING == 0 && OC2 % 2 == 0 && PIECES % 4 == 0, "unsupported shape");
     static_assert(NC == 2 || NC == 4, "unsupported tile width");
     static_assert(N_DMA + NX < 63, "outstanding loads must fit the load counter");
@@ -551,40 +558,32 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     };
     // the NC candidates of this lane in tile `tile` start at:
     auto first_candidate = [&](uint32_t tile) { return (uint64_t)tile * TILE + (uint64_t)wave * (NC * 32) + NC * col; };
-    // request the features of one tile: rows 16*ks + 8*h + t, NC consecutive candidates each.  Lanes past
-    // the end read the tile's first candidate group instead (their columns are computed but never stored).
+    // request the features of one tile: rows 16*ks + 8*h + t, NC consecutive candidates each, as loads
+    // i = 8*ks + t = 0 .. NXLOADS-1 in that order (x_begin fixes the tile, x_one requests the next load).  Lanes
+    // past the end read the tile's first candidate group instead (their columns are computed but never stored).
     // Row addresses are wave-uniform (scalar base, one scalar add per row); the per-lane part -- half-wave
     // row block plus position inside the tile -- is one 32-bit offset that only changes in a ragged last
     // tile.  Matrices too large for that offset to fit (WIDE_ROWS) take per-lane 64-bit pointers.
-    auto load_tile = [&](uint32_t tile, Raw(&raw)[NXLOADS]) {
+    const unsigned char *x_row = nullptr;
+    uint32_t x_lane_off = 0;
+    auto x_begin = [&](uint32_t tile) {
         constexpr uint64_t ELEM = FEAT_BF16 ? 2 : 4;
         const uint64_t row_bytes = ld * ELEM;
         // cand and ld are multiples of NC, so a group that starts below n lies inside its row
         const uint32_t in_tile = first_candidate(tile) < n ? (uint32_t)((wave * (NC * 32) + NC * col) * ELEM) : 0u;
-        const unsigned char *row = reinterpret_cast<const unsigned char *>(feat) + (uint64_t)tile * (TILE * ELEM);
-        if (!WIDE_ROWS) {
-            const uint32_t lane_off = (uint32_t)h * (uint32_t)(8 * row_bytes) + in_tile;
+        x_row = reinterpret_cast<const unsigned char *>(feat) + (uint64_t)tile * (TILE * ELEM);
+        if (WIDE_ROWS) x_row += (uint64_t)h * (8 * row_bytes) + in_tile;
+        else x_lane_off = (uint32_t)h * (uint32_t)(8 * row_bytes) + in_tile;
+    };
+    auto x_one = [&](int i, Raw(&raw)[NXLOADS]) {
+        const uint64_t row_bytes = ld * (FEAT_BF16 ? 2 : 4);
+        raw[i] = load_raw<NC, FEAT_BF16>(WIDE_ROWS ? x_row : x_row + x_lane_off);
+        x_row += (i % 8 == 7) ? 9 * row_bytes : row_bytes;
+    };
+    auto load_tile = [&](uint32_t tile, Raw(&raw)[NXLOADS]) {
+        x_begin(tile);
 #pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) {
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(row + lane_off);
-                    row += row_bytes;
-                }
-                row += 8 * row_bytes;
-            }
-        } else {
-            const unsigned char *p = row + (uint64_t)h * (8 * row_bytes) + in_tile;
-#pragma unroll
-            for (int ks = 0; ks < KS1; ++ks) {
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    raw[ks * 8 + t] = load_raw<NC, FEAT_BF16>(p);
-                    p += row_bytes;
-                }
-                p += 8 * row_bytes;
-            }
-        }
+        for (int i = 0; i < NXLOADS; ++i) x_one(i, raw);
     };
 
     // legality flags of this lane's NC candidates (one byte each): requested early in the tile whose epilogue reads
@@ -701,25 +700,42 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         auto bias_fragment = [&](int oc) { return *reinterpret_cast<const f32x16 *>(lds_b2 + (oc * 2 + h) * 16); };
         f32x16 bias_c = bias_fragment(0);
 
+        // first feature load of piece q (loads x_first(q) .. x_first(q + 1) - 1 go out in piece q, 1 <= q <= XSPAN), and
+        // the entries the load counter sees for piece q (piece 1 also requests the legality flags)
+        constexpr auto x_first = [](int q) constexpr {
+            return q < 1 ? 0 : (q > XSPAN ? NXLOADS : ((q - 1) * NXLOADS + XSPAN - 1) / XSPAN);
+        };
+        constexpr auto x_loads_in = [x_first](int q) constexpr {
+            return q < 1 || q > XSPAN ? 0 : x_first(q + 1) - x_first(q) + ((WITH_MIN && q == 1) ? 1 : 0);
+        };
         // piece p = 2 * oc + HALF of this tile: matrix work into acc2[PAR] (PAR = oc & 1); in between, the
         // output-layer terms of chunk oc - 1 (held in acc2[PAR ^ 1]) for 8 of its 16 accumulator registers
-        auto run_piece = [&](auto par_tag, auto half_tag, auto has_prev_tag, int oc) {
+        auto run_piece = [&](auto par_tag, auto half_tag, auto has_prev_tag, auto pidx_tag, int oc) {
+            constexpr int PIDX = decltype(pidx_tag)::value; // the piece's index where known at compile time, else -1
             constexpr int PAR = decltype(par_tag)::value, HALF = decltype(half_tag)::value;
             constexpr bool HAS_PREV = decltype(has_prev_tag)::value;
             constexpr int SLOT = 2 * PAR + HALF; // (2 * oc + HALF) & 3
             const int p = 2 * oc + HALF;
-            // piece p+1 must have landed.  Operations issued after its fetch: the fetch of piece p+2 (if
-            // there is one) and, for p = 2 and 3, the feature loads of the next tile (issued in piece 1).
-            wait_vm<N_DMA, NX>(p + 2 < PIECES || more_tiles, p == 2 || p == 3);
+            // piece p+1 must have landed.  Operations issued after its fetch: the feature loads of pieces p-2 and
+            // p-1 and, between them, the fetch of piece p+2 (if there is one).  Where iterations are written out, the
+            // pieces whose index is not known come after the loads and the two pieces behind them.
+            if (PIDX >= 0 || PEEL > 0)
+                wait_vm<N_DMA, (PIDX < 0 ? 0 : x_loads_in(PIDX - 2) + x_loads_in(PIDX - 1))>(p + 2 < PIECES || more_tiles);
+            else if (p == 2 || p == 3) // nothing written out: all loads went out in piece 1
+                wait_vm<N_DMA, x_loads_in(1)>(p + 2 < PIECES || more_tiles);
+            else wait_vm<N_DMA, 0>(p + 2 < PIECES || more_tiles);
             __syncthreads();
             if (p + 3 < PIECES) fetch_piece(p + 3);
             else if (more_tiles) fetch_piece(p + 3 - PIECES);
-            if (p == 1) {
+            if (PIDX == 1) {
                 // the feature loads must be issued after the piece fetch: the counter waits rely on that order
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_sched_barrier(0);
                 if (WITH_MIN) load_legal(tile);
-                load_tile(more_tiles ? tile + gridDim.x : tile, raw);
+                if (XSPAN == 1) load_tile(more_tiles ? tile + gridDim.x : tile, raw);
+                else x_begin(more_tiles ? tile + gridDim.x : tile);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
             }
             const bf16x8 *mine = reinterpret_cast<const bf16x8 *>(lds_ring + SLOT * PIECE_BYTES);
             const bf16x8 *next = reinterpret_cast<const bf16x8 *>(lds_ring + ((SLOT + 1) & 3) * PIECE_BYTES);
@@ -751,6 +767,13 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                 for (int c = 0; c < NC; ++c)
                     acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % RING], h1[c][HALF * KSP + ks],
                                                                      (HALF == 0 && ks == 0) ? bias_c : acc[c], 0, 0, 0);
+                if (XSPAN > 1 && PIDX >= 1 && PIDX <= XSPAN) {
+                    // this piece's feature loads, evenly over its k-steps
+                    constexpr int LO = x_first(PIDX), CNT = x_first(PIDX + 1) - LO, DIV = CNT > 0 ? CNT : 1;
+#pragma unroll
+                    for (int m = 0; m < CNT; ++m)
+                        if (ks == (m * KSP) / DIV + (KSP >= 2 * CNT ? 1 : 0)) x_one(LO + m, raw);
+                }
                 if (HAS_PREV) {
                     // Pieces of 16 k-steps: one output-layer step in each of eight k-steps in the middle.  Shorter
                     // pieces: the eight steps spread over the k-steps after the first, which leaves the first for
@@ -791,16 +814,23 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
 
         using I0 = std::integral_constant<int, 0>;
         using I1 = std::integral_constant<int, 1>;
-        run_piece(I0{}, I0{}, std::false_type{}, 0);
-        run_piece(I0{}, I1{}, std::false_type{}, 0);
-        for (int oc = 1; oc + 1 < OC2; oc += 2) {
-            run_piece(I1{}, I0{}, std::true_type{}, oc);
-            run_piece(I1{}, I1{}, std::true_type{}, oc);
-            run_piece(I0{}, I0{}, std::true_type{}, oc + 1);
-            run_piece(I0{}, I1{}, std::true_type{}, oc + 1);
-        }
-        run_piece(I1{}, I0{}, std::true_type{}, OC2 - 1);
-        run_piece(I1{}, I1{}, std::true_type{}, OC2 - 1);
+        using NoIdx = std::integral_constant<int, -1>;
+        run_piece(I0{}, I0{}, std::false_type{}, std::integral_constant<int, 0>{}, 0);
+        run_piece(I0{}, I1{}, std::false_type{}, std::integral_constant<int, 1>{}, 0);
+        // chunks oc and oc + 1, the index P0 of their first piece known (>= 0) or not
+        auto run_pair = [&](auto p0_tag, int oc) {
+            constexpr int P0 = decltype(p0_tag)::value;
+            run_piece(I1{}, I0{}, std::true_type{}, std::integral_constant<int, P0 < 0 ? -1 : P0>{}, oc);
+            run_piece(I1{}, I1{}, std::true_type{}, std::integral_constant<int, P0 < 0 ? -1 : P0 + 1>{}, oc);
+            run_piece(I0{}, I0{}, std::true_type{}, std::integral_constant<int, P0 < 0 ? -1 : P0 + 2>{}, oc + 1);
+            run_piece(I0{}, I1{}, std::true_type{}, std::integral_constant<int, P0 < 0 ? -1 : P0 + 3>{}, oc + 1);
+        };
+        static_assert(PEEL <= 2, "more iterations to write out than there are below");
+        if (PEEL >= 1) run_pair(std::integral_constant<int, 2>{}, 1);
+        if (PEEL >= 2) run_pair(std::integral_constant<int, 6>{}, 3);
+        for (int oc = 1 + 2 * PEEL; oc + 1 < OC2; oc += 2) run_pair(NoIdx{}, oc);
+        run_piece(I1{}, I0{}, std::true_type{}, std::integral_constant<int, PIECES - 2>{}, OC2 - 1);
+        run_piece(I1{}, I1{}, std::true_type{}, std::integral_constant<int, PIECES - 1>{}, OC2 - 1);
         {
             const f32x16(&last)[NC] = acc2[(OC2 - 1) & 1];
             const f32x4 *wsrc = reinterpret_cast<const f32x4 *>(lds_w3 + ((OC2 - 1) * 2 + h) * 16);
