@@ -514,19 +514,23 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     constexpr int NX = NXLOADS + (WITH_MIN ? 1 : 0); // ... and the load of the legality flags that goes with them
     constexpr int KSP = KS2 / 2;                     // k-steps (= 1 KB fragments) per piece
     constexpr int PIECES = 2 * OC2;                  // pieces per tile
-    constexpr int RING = KSP < 4 ? KSP : 4;          // weight fragments held in registers
+    // weight fragments held in registers: four, or two where registers are short (four candidate tiles at 256 units:
+    // with four the written-out pieces spill; a k-step of four matrix instructions still covers the LDS latency)
+    constexpr int RING = KSP < 4 ? KSP : (NC == 4 && KSP >= 8 ? 2 : 4);
     constexpr int PF = RING - 1;                     // LDS read-ahead in k-steps
     constexpr int N_DMA = KSP / 4 > 0 ? KSP / 4 : 1; // 1 KB fetches per wavefront per piece
     constexpr uint32_t W1_BYTES = F * H1 * 2, W1B_BYTES = H1 * 4, PIECE_BYTES = KSP * 1024;
     // The feature loads of the next tile.  Issued in one burst they fill the load path, and the wavefront -- and with
     // it the matrix pipe -- stands still until the first of them are through (2 300 cycles of a 47 000-cycle tile at
-    // 512 units); one at a time, a few k-steps apart, they cost nothing.  So where registers allow (two candidate
-    // tiles per wavefront; with four, one more live value spills) they are spread over pieces 1 .. XSPAN, load i in
-    // piece 1 + i * XSPAN / NXLOADS.  The waits on the load counter depend on how many loads the two pieces before
+    // 512 units, 3 500 of 30 000 at 256 units with four candidate tiles per wavefront); one at a time, a few k-steps
+    // apart, they cost next to nothing.  So they are spread over pieces 1 .. XSPAN, load i in piece
+    // 1 + i * XSPAN / NXLOADS.  The waits on the load counter depend on how many loads the two pieces before
     // issued, so those pieces have their index known at compile time: the head of the tile and the first PEEL
-    // iterations of the loop over output chunks, written out.
+    // iterations of the loop over output chunks, written out (two with two candidate tiles per wavefront; one with
+    // four, where a second one makes the compiler spill).
     constexpr int LOOP_ITERS = (OC2 - 2) / 2;
-    constexpr int PEEL = NC == 2 ? (LOOP_ITERS < 2 ? LOOP_ITERS : 2) : 0;
+    constexpr int PEEL_WANT = NC == 2 ? 2 : 1;
+    constexpr int PEEL = LOOP_ITERS < PEEL_WANT ? LOOP_ITERS : PEEL_WANT;
     constexpr int XSPAN_FREE = PEEL == LOOP_ITERS ? PIECES - 4 : 4 * PEEL - 1;
     constexpr int XSPAN = XSPAN_FREE < 1 ? 1 : (XSPAN_FREE > NXLOADS ? NXLOADS : XSPAN_FREE);
     static_assert(XSPAN + 2 < PIECES || (XSPAN == 1 && PIECES == 4), "the last two pieces of a tile issue no feature loads");
