@@ -171,6 +171,25 @@ def test_bf16_model_rows_wider_than_a_32bit_lane_offset(G):
     assert np.array_equal(got, compact)
 
 
+@pytest.mark.parametrize("widths,ld_extra", [([64, 512, 512, 1], 2), ([64, 256, 256, 1], 4)])
+def test_bf16_model_wide_rows_over_several_tiles_per_block(G, widths, ld_extra):
+    """The same for the 64-feature kernels, with more tiles than blocks and a ragged last one: the features of a
+    block's next tile are requested load by load while the current tile computes, through 64-bit per-lane
+    addresses here.  (34 GB of device memory, of which only the first columns are written and read.)"""
+    n = 256 * 512 + 3 * 256 + 36
+    _, b16 = _features("c2", n, 64)
+    theta = synth.mlp_theta(widths, 5, bf16=True, bias_scale=0.5)
+    model = G.make_model(widths, eck.BF16, theta)
+    compact = G.score_gpu(model, G.bf16_dev(b16), n)
+    ld = (1 << 28) + ld_extra
+    wide = torch.empty((64, ld), dtype=torch.bfloat16, device="cuda")
+    wide[:, :n] = G.bf16_dev(b16)[:, :n]
+    got = G.score_gpu(model, wide, n)
+    del wide
+    torch.cuda.empty_cache()
+    assert np.array_equal(got, compact)
+
+
 def test_set_get_state_roundtrip(G):
     widths = [64, 256, 256, 1]
     P = synth.param_count(widths)
