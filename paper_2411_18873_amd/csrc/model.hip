@@ -514,9 +514,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     constexpr int NX = NXLOADS + (WITH_MIN ? 1 : 0); // ... and the load of the legality flags that goes with them
     constexpr int KSP = KS2 / 2;                     // k-steps (= 1 KB fragments) per piece
     constexpr int PIECES = 2 * OC2;                  // pieces per tile
-    // weight fragments held in registers: four, or two where registers are short (four candidate tiles at 256 units:
-    // with four the written-out pieces spill; a k-step of four matrix instructions still covers the LDS latency)
-    constexpr int RING = KSP < 4 ? KSP : (NC == 4 && KSP >= 8 ? 2 : 4);
+    constexpr int RING = KSP < 4 ? KSP : 4;          // weight fragments held in registers
     constexpr int PF = RING - 1;                     // LDS read-ahead in k-steps
     constexpr int N_DMA = KSP / 4 > 0 ? KSP / 4 : 1; // 1 KB fetches per wavefront per piece
     constexpr uint32_t W1_BYTES = F * H1 * 2, W1B_BYTES = H1 * 4, PIECE_BYTES = KSP * 1024;
@@ -527,7 +525,8 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     // 1 + i * XSPAN / NXLOADS.  The waits on the load counter depend on how many loads the two pieces before
     // issued, so those pieces have their index known at compile time: the head of the tile and the first PEEL
     // iterations of the loop over output chunks, written out (two with two candidate tiles per wavefront; one with
-    // four, where a second one makes the compiler spill).
+    // four, where a second one makes the compiler spill: the 256 architectural registers hold 128 of accumulators
+    // and 64 of loaded features there).
     constexpr int LOOP_ITERS = (OC2 - 2) / 2;
     constexpr int PEEL_WANT = NC == 2 ? 2 : 1;
     constexpr int PEEL = LOOP_ITERS < PEEL_WANT ? LOOP_ITERS : PEEL_WANT;
@@ -648,10 +647,14 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         // ---- layer 1: h1 = relu(W1^T x + b1), kept as layer-2 B fragments; the conversion of chunk oc-1
         // is issued behind the matrix instructions of chunk oc
         bf16x8 h1[NC][KS2];
-        f32x16 acc1[2][NC];
-        auto convert_chunk = [&](int oc, const f32x16(&acc)[NC]) {
+        // Two candidate tiles at a time (a "group"; NG groups per chunk): the accumulators of the group before are
+        // converted while the matrix instructions of this one run, so two groups' accumulators are live, 64
+        // registers, whatever NC is.
+        constexpr int NG = NC / 2;
+        f32x16 acc1[2][2];
+        auto convert_group = [&](int oc, int g, const f32x16(&acc)[2]) {
 #pragma unroll
-            for (int c = 0; c < NC; ++c)
+            for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     // two floats -> one register of two bf16, then ReLU on the packed bits: a negative bf16 is
@@ -659,12 +662,12 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                     u32x4 words;
 #pragma unroll
                     for (int d = 0; d < 4; ++d) {
-                        const f32x2 pair = {acc[c][8 * half + 2 * d], acc[c][8 * half + 2 * d + 1]};
+                        const f32x2 pair = {acc[cc][8 * half + 2 * d], acc[cc][8 * half + 2 * d + 1]};
                         const bf16x2 cv = __builtin_convertvector(pair, bf16x2);
                         const s16x2 clamped = __builtin_elementwise_max(__builtin_bit_cast(s16x2, cv), (s16x2)(0));
                         words[d] = __builtin_bit_cast(uint32_t, clamped);
                     }
-                    h1[c][2 * oc + half] = park_in_acc(__builtin_bit_cast(bf16x8, words));
+                    h1[2 * g + cc][2 * oc + half] = park_in_acc(__builtin_bit_cast(bf16x8, words));
                 }
         };
         bf16x8 a1[2][KS1]; // weight fragments of two chunks: one in use, one on its way from LDS
@@ -677,21 +680,25 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         load_chunk(0);
 #pragma unroll
         for (int oc = 0; oc < OC1; ++oc) {
-            f32x16(&acc)[NC] = acc1[oc & 1];
             const bf16x8(&a)[KS1] = a1[oc & 1];
             const f32x16 bias = b1c[oc & 1];
             if (oc + 1 < OC1) load_chunk(oc + 1);
 #pragma unroll
-            for (int ks = 0; ks < KS1; ++ks)
+            for (int g = 0; g < NG; ++g) {
+                const int s = oc * NG + g; // groups in the order they are computed
+                f32x16(&acc)[2] = acc1[s & 1];
 #pragma unroll
-                for (int c = 0; c < NC; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], x[c][ks], ks == 0 ? bias : acc[c], 0, 0, 0);
+                for (int ks = 0; ks < KS1; ++ks)
 #pragma unroll
-            for (int c = 0; c < NC; ++c) keep_in_vgprs(acc[c]);
-            if (oc > 0) convert_chunk(oc - 1, acc1[(oc - 1) & 1]);
-            __builtin_amdgcn_sched_barrier(0);
+                    for (int cc = 0; cc < 2; ++cc)
+                        acc[cc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], x[2 * g + cc][ks], ks == 0 ? bias : acc[cc], 0, 0, 0);
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) keep_in_vgprs(acc[cc]);
+                if (s > 0) convert_group((s - 1) / NG, (s - 1) % NG, acc1[(s - 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        convert_chunk(OC1 - 1, acc1[(OC1 - 1) & 1]);
+        convert_group(OC1 - 1, NG - 1, acc1[(OC1 * NG - 1) & 1]);
 
         // ---- layer 2 + output layer
         float y[NC];
@@ -700,9 +707,19 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         f32x16 acc2[2][NC];
         bf16x8 a[RING]; // weight fragments in flight; fragment j of the tile's piece stream sits in a[j % RING]
         // b2 of the chunk about to start, in accumulator-register order: the chunk's first matrix instruction
-        // takes it as its C operand, so the bias never costs a vector instruction
+        // takes it as its C operand, so the bias never costs a vector instruction.  With two candidate tiles it waits
+        // in 16 registers of its own; with four there are none to spare and it is read straight into the chunk's NC
+        // accumulators (free once the output terms of the chunk before the last are through).
+        constexpr bool BIAS_IN_ACC = NC == 4;
+        static_assert(!BIAS_IN_ACC || KSP >= 2, "the output terms of a one-k-step piece come after its loop");
         auto bias_fragment = [&](int oc) { return *reinterpret_cast<const f32x16 *>(lds_b2 + (oc * 2 + h) * 16); };
-        f32x16 bias_c = bias_fragment(0);
+        f32x16 bias_c;
+        if (BIAS_IN_ACC) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) acc2[0][c] = bias_fragment(0);
+        } else {
+            bias_c = bias_fragment(0);
+        }
 
         // first feature load of piece q (loads x_first(q) .. x_first(q + 1) - 1 go out in piece q, 1 <= q <= XSPAN), and
         // the entries the load counter sees for piece q (piece 1 also requests the legality flags)
@@ -770,7 +787,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
                     acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % RING], h1[c][HALF * KSP + ks],
-                                                                     (HALF == 0 && ks == 0) ? bias_c : acc[c], 0, 0, 0);
+                                                                     (!BIAS_IN_ACC && HALF == 0 && ks == 0) ? bias_c : acc[c], 0, 0, 0);
                 if (XSPAN > 1 && PIDX >= 1 && PIDX <= XSPAN) {
                     // this piece's feature loads, evenly over its k-steps
                     constexpr int LO = x_first(PIDX), CNT = x_first(PIDX + 1) - LO, DIV = CNT > 0 ? CNT : 1;
@@ -802,8 +819,14 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                 }
                 // the next chunk's bias, once the output-layer steps are through (its registers are free
                 // again after that chunk's first matrix instructions)
-                if (HALF == 1 && ks == (EPI_FIRST + 8 < KSP ? EPI_FIRST + 8 : KSP - 1))
-                    bias_c = bias_fragment(oc + 1 < OC2 ? oc + 1 : oc);
+                if (HALF == 1 && ks == (EPI_FIRST + 8 < KSP ? EPI_FIRST + 8 : KSP - 1)) {
+                    if (!BIAS_IN_ACC) {
+                        bias_c = bias_fragment(oc + 1 < OC2 ? oc + 1 : oc);
+                    } else if (oc + 1 < OC2) {
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) acc2[PAR ^ 1][c] = bias_fragment(oc + 1);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (HAS_PREV && KSP == 1) {
