@@ -651,6 +651,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         // converted while the matrix instructions of this one run, so two groups' accumulators are live, 64
         // registers, whatever NC is.
         constexpr int NG = NC / 2;
+        constexpr int UNPARKED = (NC == 2 && KS2 == 32) ? 10 : 0; // measured at 512 units: 8, 10, 12 -> -1.2, -1.5, -1.4 % cycles
         f32x16 acc1[2][2];
         auto convert_group = [&](int oc, int g, const f32x16(&acc)[2]) {
 #pragma unroll
@@ -667,7 +668,10 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
                         const s16x2 clamped = __builtin_elementwise_max(__builtin_bit_cast(s16x2, cv), (s16x2)(0));
                         words[d] = __builtin_bit_cast(uint32_t, clamped);
                     }
-                    h1[2 * g + cc][2 * oc + half] = park_in_acc(__builtin_bit_cast(bf16x8, words));
+                    // the first UNPARKED k-steps' fragments stay where the conversion left them: the compiler keeps
+                    // about that many in architectural registers anyway, and parked ones it copies straight back
+                    if (2 * oc + half < UNPARKED) h1[2 * g + cc][2 * oc + half] = __builtin_bit_cast(bf16x8, words);
+                    else h1[2 * g + cc][2 * oc + half] = park_in_acc(__builtin_bit_cast(bf16x8, words));
                 }
         };
         bf16x8 a1[2][KS1]; // weight fragments of two chunks: one in use, one on its way from LDS
