@@ -882,8 +882,10 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
             const float score = total + b3;
             if (h == 0 && cand + c < n) out[cand + c] = score;
             if (WITH_MIN) {
-                const bool legal = !mn.legal || ((legal_bits >> (8 * c)) & 0xFFu);
-                key[c] = (legal && cand + c < n && score == score) ? score_order_key(score) : 0xFFFFFFFFu;
+                // (no short-circuit: the three tests are one compare each, a branch per test costs more)
+                const bool legal = !mn.legal | (((legal_bits >> (8 * c)) & 0xFFu) != 0);
+                const bool counts = legal & (cand + c < n) & (score == score);
+                key[c] = counts ? score_order_key(score) : 0xFFFFFFFFu;
             }
         }
         if (WITH_MIN && mn.tiles_per_seg) {
