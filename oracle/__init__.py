@@ -88,7 +88,8 @@ class Space:
         self.size = size.value
 
     def __del__(self):
-        if getattr(self, "h", None):
+        # at interpreter shutdown the module's globals may already be gone: then the process ends anyway
+        if getattr(self, "h", None) and lib is not None and C is not None:
             lib().orc_space_destroy(C.c_void_p(self.h))
             self.h = None
 

@@ -50,8 +50,8 @@
  * count) is pinned that way, against the loop nest it is read from -- Table 5's
  * shared_ld column depends on a thread layout the paper does not print and is
  * not reproduced.
- * parity unpinned: the 100-step bf16 update trajectory weight for weight
- * (checked statistically only).
+ * The refit's bf16 mode: the plain step on weights rounded in numpy, applied to the
+ * unrounded master.  No function here is without a pin.
  *
  * Floating point: scores and the update run in fp64 on the fp32/bf16 values
  * handed in.  Integer parts are exact.

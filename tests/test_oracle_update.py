@@ -141,6 +141,49 @@ def test_refit_learns_a_positive_linear_energy():
     assert state[-1] == 40
 
 
+def _bf16_rne(x):
+    """round-to-nearest-even to bfloat16, written on the bit pattern with numpy (independent of the oracle's C)"""
+    u = np.asarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return r.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def test_bf16_weight_mode_is_the_plain_step_on_rounded_weights():
+    """The bf16 mode of the refit: forward and backward see the master weights rounded to bf16, the step is applied
+    to the unrounded master.  So from any state, one step in that mode must move the master by exactly what one
+    plain step moves a model whose weights ARE the rounded ones, and leave the same moments -- checked with the
+    rounding redone in numpy, from a fresh state and from one with moments.  And weights that are bf16 values
+    already make the two modes the same function."""
+    widths = [8, 16, 8, 1]
+    P = synth.param_count(widths)
+    rng = np.random.default_rng(4)
+    feat = rng.uniform(0, 4, (8, 64)).astype(np.float32)
+    y = rng.uniform(0.5, 3.0, 64)
+    theta = rng.normal(0, 0.3, P)
+    st = np.concatenate([theta, np.zeros(2 * P + 1)])
+    for _ in range(3):
+        before = st.copy()
+        a = before.copy()
+        oracle.update(widths, a, feat, y, 1, 16, bf16_weights=True)
+        rounded = before.copy()
+        rounded[:P] = _bf16_rne(before[:P])
+        assert np.any(rounded[:P] != before[:P])
+        b = rounded.copy()
+        oracle.update(widths, b, feat, y, 1, 16, bf16_weights=False)
+        assert np.allclose(a[:P] - before[:P], b[:P] - rounded[:P], rtol=0, atol=1e-15)
+        assert np.array_equal(a[P:], b[P:])
+        # and the plain mode from the unrounded weights is a different step
+        c = before.copy()
+        oracle.update(widths, c, feat, y, 1, 16, bf16_weights=False)
+        assert not np.array_equal(c[P:2 * P], a[P:2 * P])
+        st = a
+    exact = np.concatenate([_bf16_rne(theta), np.zeros(2 * P + 1)])
+    p_, q_ = exact.copy(), exact.copy()
+    oracle.update(widths, p_, feat, y, 1, 16, bf16_weights=True)
+    oracle.update(widths, q_, feat, y, 1, 16, bf16_weights=False)
+    assert np.array_equal(p_, q_)
+
+
 def test_nonpositive_energy_is_a_data_error():
     widths = [2, 1]
     state = np.arange(10, dtype=np.float64)
