@@ -533,6 +533,10 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     constexpr int XSPAN_FREE = PEEL == LOOP_ITERS ? PIECES - 4 : 4 * PEEL - 1;
     constexpr int XSPAN = XSPAN_FREE < 1 ? 1 : (XSPAN_FREE > NXLOADS ? NXLOADS : XSPAN_FREE);
     static_assert(XSPAN + 2 < PIECES || (XSPAN == 1 && PIECES == 4), "the last two pieces of a tile issue no feature loads");
+    // WITH_MIN: the piece that requests the legality flags of the tile.  Piece 2 where the loads are spread: requested
+    // in piece 1, next to the set-up of the feature loads, the one load made the compiler permute 104 parked
+    // registers in every tile (+ 27 registers, + 1 % cycles).
+    constexpr int LEGAL_PIECE = XSPAN > 1 ? 2 : 1;
     static_assert(KS2 % 2 == 0 && KSP % RING == 0 && OC2 % 2 == 0 && PIECES % 4 == 0, "unsupported shape");
     static_assert(NC == 2 || NC == 4, "unsupported tile width");
     static_assert(N_DMA + NX < 63, "outstanding loads must fit the load counter");
@@ -590,7 +594,7 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
     };
 
     // legality flags of this lane's NC candidates (one byte each): requested early in the tile whose epilogue reads
-    // them, just before the features of the next tile (so the waits on the load counter see one more load there)
+    // them, among the feature loads of the next tile (the waits on the load counter see one more load in that piece)
     uint32_t legal_bits = 0x01010101u;
     auto load_legal = [&](uint32_t tile) {
         const uint64_t cand = first_candidate(tile);
@@ -726,12 +730,12 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
         }
 
         // first feature load of piece q (loads x_first(q) .. x_first(q + 1) - 1 go out in piece q, 1 <= q <= XSPAN), and
-        // the entries the load counter sees for piece q (piece 1 also requests the legality flags)
+        // the entries the load counter sees for piece q (piece LEGAL_PIECE also requests the legality flags)
         constexpr auto x_first = [](int q) constexpr {
             return q < 1 ? 0 : (q > XSPAN ? NXLOADS : ((q - 1) * NXLOADS + XSPAN - 1) / XSPAN);
         };
         constexpr auto x_loads_in = [x_first](int q) constexpr {
-            return q < 1 || q > XSPAN ? 0 : x_first(q + 1) - x_first(q) + ((WITH_MIN && q == 1) ? 1 : 0);
+            return q < 1 || q > XSPAN ? 0 : x_first(q + 1) - x_first(q) + ((WITH_MIN && q == LEGAL_PIECE) ? 1 : 0);
         };
         // piece p = 2 * oc + HALF of this tile: matrix work into acc2[PAR] (PAR = oc & 1); in between, the
         // output-layer terms of chunk oc - 1 (held in acc2[PAR ^ 1]) for 8 of its 16 accumulator registers
@@ -752,11 +756,18 @@ __global__ __launch_bounds__(256) void score_bf16_kernel(const unsigned char *__
             __syncthreads();
             if (p + 3 < PIECES) fetch_piece(p + 3);
             else if (more_tiles) fetch_piece(p + 3 - PIECES);
+            if (WITH_MIN && LEGAL_PIECE != 1 && PIDX == LEGAL_PIECE) {
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+                load_legal(tile);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if (PIDX == 1) {
                 // the feature loads must be issued after the piece fetch: the counter waits rely on that order
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_sched_barrier(0);
-                if (WITH_MIN) load_legal(tile);
+                if (WITH_MIN && LEGAL_PIECE == 1) load_legal(tile);
                 if (XSPAN == 1) load_tile(more_tiles ? tile + gridDim.x : tile, raw);
                 else x_begin(more_tiles ? tile + gridDim.x : tile);
                 asm volatile("" ::: "memory");
